@@ -1,0 +1,95 @@
+"""Write workloads/calib.json: the per-tensor scales of the benchmark configurations.
+
+Runs only the CPU oracle.  For every configuration a full-precision (fp64) forward pass over a
+few calibration samples records the largest |activation| after each layer (the observe mode of
+the paper's quantizers, section "Quantization Integration to Caffe"); scales are symmetric
+max-abs, s = max|r| / 127 (int8) or / 32767 (int16), zero-point 0, cast to fp32.  Weight scales
+come from the weights themselves; a bias scale is fp32(s_x * s_w).
+
+The scales are *inputs* of the layers (the library takes per-tensor scale / zero-point from the
+caller), so both the oracle and the GPU path read them from the written file.
+
+Usage:  python -m oracle.calibrate
+"""
+import json
+import os
+
+import numpy as np
+
+from workloads import configs as cf
+from . import nets
+
+QSYM = {"int8": 127.0, "int16": 32767.0}
+CALIB_IMAGES = 8
+
+
+def _s(maxabs, dtype):
+    return float(np.float32(maxabs / QSYM[dtype]))
+
+
+def _layer_scales(layers, params, peaks, s_in, dtype):
+    out, s_x = [], s_in
+    for L, (w, b), pk in zip(layers, params, peaks):
+        s_w = _s(float(np.max(np.abs(w))), dtype)
+        s_y = _s(pk, dtype)
+        out.append({"w": s_w, "b": float(np.float32(np.float64(s_x) * np.float64(s_w))), "y": s_y})
+        s_x = s_y
+    return out
+
+
+def main():
+    res = {"note": "written by oracle/calibrate.py; symmetric max-abs scales, zero-points 0",
+           "calib_images": CALIB_IMAGES}
+
+    # config 2: LeNet shape, batch 64 (all 64 samples observed; it is tiny)
+    x, params = cf.lenet_tensors(64)
+    peaks, _ = nets.run_f64_chain_maxabs(cf.LENET_LAYERS, x, params)
+    res["lenet"] = {}
+    for dt in QSYM:
+        s_in = _s(float(np.max(np.abs(x))), dt)
+        res["lenet"][dt] = {"x": s_in, "layers": _layer_scales(cf.LENET_LAYERS, params, peaks, s_in, dt)}
+
+    # config 3: AlexNet-shaped stack, images 0..7
+    x = cf.alexnet_input(CALIB_IMAGES)
+    params = cf.alexnet_conv_params()
+    peaks, _ = nets.run_f64_chain_maxabs(cf.ALEXNET_CONVS, x, params)
+    # the input range is fixed a priori (N(0,1) clipped at 6 sigma) so that it does not depend on
+    # how many images are drawn
+    res["alexnet"] = {}
+    for dt in QSYM:
+        s_in = _s(6.0, dt)
+        res["alexnet"][dt] = {"x": s_in, "layers": _layer_scales(cf.ALEXNET_CONVS, params, peaks, s_in, dt)}
+
+    # config 4: FC layers, first 16 rows observed
+    res["fc"] = {}
+    for i, L in enumerate(cf.ALEXNET_FCS):
+        _, x, w, b = cf.fc_case(i, 16)
+        pk, _ = nets.run_f64_chain_maxabs([L], x, [(w, b)])
+        res["fc"][L.name] = {}
+        for dt in QSYM:
+            s_in = _s(6.0, dt)
+            res["fc"][L.name][dt] = {"x": s_in, "layers": _layer_scales([L], [(w, b)], pk, s_in, dt)}
+
+    # config 5: trunk = config 3's conv1/conv2; gate emits raw accumulators (needs only s_w);
+    # every expert observed on the same calibration images
+    trunk_p, gate_w, experts_p = cf.moe_params()
+    x = cf.alexnet_input(CALIB_IMAGES)
+    _, trunk_out = nets.run_f64_chain_maxabs(cf.MOE_TRUNK, x, trunk_p)
+    res["moe"] = {}
+    epeaks = [nets.run_f64_chain_maxabs(cf.MOE_EXPERT_LAYERS, trunk_out, ps)[0] for ps in experts_p]
+    for dt in QSYM:
+        s_trunk = res["alexnet"][dt]["layers"][1]["y"]
+        res["moe"][dt] = {
+            "gate_w": _s(float(np.max(np.abs(gate_w))), dt),
+            "experts": [_layer_scales(cf.MOE_EXPERT_LAYERS, ps, pk, s_trunk, dt)
+                        for ps, pk in zip(experts_p, epeaks)],
+        }
+
+    path = os.path.join(os.path.dirname(os.path.abspath(cf.__file__)), "calib.json")
+    with open(path, "w") as f:
+        json.dump(res, f, indent=1)
+    print("wrote", path)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,150 @@
+"""Layer chains of the benchmark configurations, evaluated with the CPU oracle.
+
+TEST INFRASTRUCTURE ONLY.  Each function strings oracle routines together in the order the
+paper lists the layers (sections "ImageNet Configuration", "ImageNet-MOE Configuration",
+"Mixture of Experts"); no arithmetic lives here beyond calling them.  Layouts are the logical
+ones (N,C,H,W / K,C/g,R,S / N_out,K_in).
+
+A "scales" record for a layer is a dict {"w": s_w, "b": s_b, "y": s_y} of fp32 values; the
+input scale of a layer is the output scale of the previous one (pooling keeps its input's
+parameters).  All zero-points in the shipped configurations are 0, but every routine takes them.
+"""
+import numpy as np
+
+from . import oracle as o
+
+
+# ------------------------------------------------------------------------------------------
+# integer (int8 / int16) path
+# ------------------------------------------------------------------------------------------
+def quantize_params(w_real, b_real, sc, dtype, z_w=0):
+    """Real weights / bias -> storage codes (weights) and int32-range codes at scale s_b (bias)."""
+    wq = o.quantize(np.asarray(w_real, np.float32), sc["w"], z_w, dtype)
+    # bias lives in the accumulator domain: int32 codes, scale s_b = s_x s_w, zero-point 0
+    bq = None if b_real is None else o.quantize_bias(np.asarray(b_real, np.float32), sc["b"])
+    return wq, bq
+
+
+def int_conv(xq, z_x, s_x, wq, z_w, bq, L, sc, dtype, z_y=0):
+    """conv accumulate -> requantize (ReLU as raised clamp) -> optional max-pool."""
+    t = o.conv2d_acc(xq, z_x, wq, z_w, bq, L.stride, L.pad, L.groups)
+    mult, shift = o.scale_quant_vals(s_x, sc["w"], sc["y"], o.SHIFT_BITS[dtype])
+    y = o.requant(t, mult, o.SHIFT_BITS[dtype], shift, z_y, dtype, L.relu)
+    if L.pool_k:
+        y = o.maxpool_i32(y, L.pool_k, L.pool_s)
+    return y
+
+
+def int_fc(xq, z_x, s_x, wq, z_w, bq, L, sc, dtype, z_y=0):
+    t = o.gemm_acc(xq, z_x, wq, z_w, bq)
+    mult, shift = o.scale_quant_vals(s_x, sc["w"], sc["y"], o.SHIFT_BITS[dtype])
+    return o.requant(t, mult, o.SHIFT_BITS[dtype], shift, z_y, dtype, L.relu)
+
+
+def run_int_chain(layers, x_real, params_real, s_in, scales, dtype, collect=False):
+    """Quantize the real input at scale s_in, then run conv / FC layers in order.  An FC layer
+    after a conv layer sees the activation flattened in (C,H,W) order, as the paper's framework
+    does.  Returns the final codes (and every layer's output if collect)."""
+    xq = o.quantize(np.asarray(x_real, np.float32), s_in, 0, dtype)
+    s_x = s_in
+    outs = []
+    for L, (w, b), sc in zip(layers, params_real, scales):
+        wq, bq = quantize_params(w, b, sc, dtype)
+        if L.kind == "conv":
+            xq = int_conv(xq, 0, s_x, wq, 0, bq, L, sc, dtype)
+        else:
+            xq = int_fc(xq.reshape(xq.shape[0], -1), 0, s_x, wq, 0, bq, L, sc, dtype)
+        s_x = sc["y"]
+        outs.append(xq)
+    return (xq, outs) if collect else xq
+
+
+# ------------------------------------------------------------------------------------------
+# fp16 storage / fp64 reference path
+# ------------------------------------------------------------------------------------------
+def fp16_params(w_real, b_real):
+    """Weights rounded to fp16 values, bias to fp32 values (both held as fp64)."""
+    w = o.round_fp16(np.asarray(w_real, np.float64))
+    b = None if b_real is None else np.asarray(b_real, np.float32).astype(np.float64)
+    return w, b
+
+
+def run_fp16_chain(layers, x_real, params_real, collect=False):
+    """fp16-valued input and weights, exact products, fp64 sums.  Returns the UNROUNDED fp64
+    output of the last layer (after its pool, which commutes with rounding); between layers the
+    activation is rounded to fp16, because that is what the storage type holds."""
+    x = o.round_fp16(np.asarray(x_real, np.float64))
+    outs = []
+    y = x
+    for L, (w, b) in zip(layers, params_real):
+        w16, b32 = fp16_params(w, b)
+        if L.kind == "conv":
+            y = o.conv2d_f64(x, w16, b32, L.stride, L.pad, L.groups, L.relu)
+            if L.pool_k:
+                y = o.maxpool_f64(y, L.pool_k, L.pool_s)
+        else:
+            y = o.gemm_f64(x.reshape(x.shape[0], -1), w16, b32, L.relu)
+        outs.append(y)
+        x = o.round_fp16(y)
+    return (y, outs) if collect else y
+
+
+def run_f64_chain_maxabs(layers, x_real, params_real):
+    """Full-precision forward used by calibration: max |activation| after every layer
+    (the observe mode of the paper's quantizers, section "Quantization Integration to Caffe")."""
+    x = np.asarray(x_real, np.float64)
+    peaks = []
+    for L, (w, b) in zip(layers, params_real):
+        if L.kind == "conv":
+            x = o.conv2d_f64(x, w, b, L.stride, L.pad, L.groups, L.relu)
+            peaks.append(float(np.max(np.abs(x))))
+            if L.pool_k:
+                x = o.maxpool_f64(x, L.pool_k, L.pool_s)
+        else:
+            x = o.gemm_f64(x.reshape(x.shape[0], -1), w, b, L.relu)
+            peaks.append(float(np.max(np.abs(x))))
+    return peaks, x
+
+
+# ------------------------------------------------------------------------------------------
+# mixture of experts, one expert per sample
+# ------------------------------------------------------------------------------------------
+def moe_int(xq, s_x, logits, expert_layers, expert_params_q, expert_scales, dtype):
+    """xq: trunk output codes [B,C,H,W]; logits [B,E]; per-sample: route to the arg-max expert
+    and evaluate that expert's layer chain on that sample alone."""
+    e_idx, counts = o.route_top1(logits)
+    out = None
+    for b in range(xq.shape[0]):
+        e = int(e_idx[b])
+        a, s = xq[b:b + 1], s_x
+        for L, (wq, bq), sc in zip(expert_layers, expert_params_q[e], expert_scales[e]):
+            if L.kind == "conv":
+                a = int_conv(a, 0, s, wq, 0, bq, L, sc, dtype)
+            else:
+                a = int_fc(a.reshape(1, -1), 0, s, wq, 0, bq, L, sc, dtype)
+            s = sc["y"]
+        if out is None:
+            out = np.empty((xq.shape[0],) + a.shape[1:], np.int32)
+        out[b] = a[0]
+    return out, e_idx, counts
+
+
+def moe_fp16(x16, logits, expert_layers, expert_params16):
+    e_idx, counts = o.route_top1(logits)
+    out = None
+    for b in range(x16.shape[0]):
+        e = int(e_idx[b])
+        a = x16[b:b + 1]
+        y = a
+        for L, (w16, b32) in zip(expert_layers, expert_params16[e]):
+            if L.kind == "conv":
+                y = o.conv2d_f64(a, w16, b32, L.stride, L.pad, L.groups, L.relu)
+                if L.pool_k:
+                    y = o.maxpool_f64(y, L.pool_k, L.pool_s)
+            else:
+                y = o.gemm_f64(a.reshape(1, -1), w16, b32, L.relu)
+            a = o.round_fp16(y)
+        if out is None:
+            out = np.empty((x16.shape[0],) + y.shape[1:], np.float64)
+        out[b] = y[0]
+    return out, e_idx, counts

@@ -1,0 +1,248 @@
+"""numpy-facing wrappers around the C oracle (oracle/mpq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY -- see the header of mpq_oracle.c.  Argument marshalling and nothing
+else: every number is computed by the C routines.  Layouts are the paper's logical ones
+(activations N,C,H,W; conv weights K,C/groups,R,S; FC weights N_out,K_in).
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        _lib = C.CDLL(path)
+        _declare(_lib)
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(C.POINTER(ct))
+
+
+def _declare(L):
+    i32p, i64p, f32p, f64p = (C.POINTER(C.c_int32), C.POINTER(C.c_int64),
+                              C.POINTER(C.c_float), C.POINTER(C.c_double))
+    L.orc_max_threads.restype = C.c_int
+    L.orc_set_threads.argtypes = [C.c_int]
+    L.orc_estimate_params.argtypes = [C.c_double, C.c_double, C.c_int64, C.c_int64,
+                                      f64p, i64p, f64p]
+    L.orc_quantize.argtypes = [f32p, C.c_size_t, C.c_float, C.c_int32, C.c_int32, C.c_int32, i32p]
+    L.orc_dequantize.argtypes = [i32p, C.c_size_t, C.c_float, C.c_int32, f32p]
+    L.orc_scale_quant_vals.argtypes = [C.c_float, C.c_float, C.c_float, C.c_int, i64p,
+                                       C.POINTER(C.c_int)]
+    L.orc_scale_quant_vals.restype = C.c_int
+    L.orc_requant_one.argtypes = [C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int64, C.c_int64,
+                                  C.c_int64]
+    L.orc_requant_one.restype = C.c_int64
+    L.orc_requant.argtypes = [i64p, C.c_size_t, C.c_int64, C.c_int, C.c_int, C.c_int32,
+                              C.c_int32, C.c_int32, C.c_int, i32p]
+    conv_args = [i32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int32,
+                 i32p, C.c_int, C.c_int, C.c_int, C.c_int32, i64p,
+                 C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i64p]
+    L.orc_conv2d_acc.argtypes = conv_args
+    L.orc_conv2d_acc_expanded.argtypes = conv_args
+    L.orc_im2col.argtypes = [i32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int32,
+                             C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                             C.c_int, C.c_int, i32p]
+    L.orc_gemm_acc.argtypes = [i32p, C.c_int, C.c_int, C.c_int32, i32p, C.c_int, C.c_int32,
+                               i64p, i64p]
+    L.orc_maxpool_i32.argtypes = [i32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i32p]
+    L.orc_conv2d_f64.argtypes = [f64p, C.c_int, C.c_int, C.c_int, C.c_int,
+                                 f64p, C.c_int, C.c_int, C.c_int, f64p,
+                                 C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f64p]
+    L.orc_gemm_f64.argtypes = [f64p, C.c_int, C.c_int, f64p, C.c_int, f64p, C.c_int, f64p]
+    L.orc_maxpool_f64.argtypes = [f64p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, f64p]
+    L.orc_round_fp16_one.argtypes = [C.c_double]
+    L.orc_round_fp16_one.restype = C.c_double
+    L.orc_round_fp16.argtypes = [f64p, C.c_size_t, f64p]
+    L.orc_route_top1.argtypes = [f64p, C.c_int, C.c_int, i32p, i32p]
+
+
+# storage-type limits -------------------------------------------------------------------------
+QRANGE = {"int8": (-128, 127), "int16": (-32768, 32767)}
+SHIFT_BITS = {"int8": 31, "int16": 15}
+
+
+def _c(a, dt):
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+def max_threads():
+    return int(lib().orc_max_threads())
+
+
+def set_threads(n):
+    lib().orc_set_threads(int(n))
+
+
+def estimate_params(fmin, fmax, imin, imax):
+    s, i0, i1 = C.c_double(), C.c_int64(), C.c_double()
+    lib().orc_estimate_params(float(fmin), float(fmax), int(imin), int(imax),
+                              C.byref(s), C.byref(i0), C.byref(i1))
+    return s.value, i0.value, i1.value
+
+
+def quantize(r, scale, zero, dtype):
+    qmin, qmax = QRANGE[dtype]
+    r = _c(r, np.float32)
+    q = np.empty(r.shape, np.int32)
+    lib().orc_quantize(_p(r, C.c_float), r.size, np.float32(scale), int(zero), qmin, qmax,
+                       _p(q, C.c_int32))
+    return q
+
+
+def quantize_bias(r, scale):
+    """Bias codes: accumulator domain (int32 range), zero-point 0, same rounding as quantize."""
+    r = _c(r, np.float32)
+    q = np.empty(r.shape, np.int32)
+    lib().orc_quantize(_p(r, C.c_float), r.size, np.float32(scale), 0, -2 ** 31, 2 ** 31 - 1,
+                       _p(q, C.c_int32))
+    return q
+
+
+def dequantize(q, scale, zero):
+    q = _c(q, np.int32)
+    r = np.empty(q.shape, np.float32)
+    lib().orc_dequantize(_p(q, C.c_int32), q.size, np.float32(scale), int(zero), _p(r, C.c_float))
+    return r
+
+
+def scale_quant_vals(s_a, s_b, s_c, sb):
+    m, h = C.c_int64(), C.c_int()
+    rc = lib().orc_scale_quant_vals(np.float32(s_a), np.float32(s_b), np.float32(s_c), int(sb),
+                                    C.byref(m), C.byref(h))
+    if rc != 0:
+        raise ValueError("scale ratio is not a positive finite number")
+    return m.value, h.value
+
+
+def requant_one(t, mult, sb, shift, z_out, lo, hi):
+    return int(lib().orc_requant_one(int(t), int(mult), int(sb), int(shift), int(z_out), int(lo),
+                                     int(hi)))
+
+
+def requant(t, mult, sb, shift, z_out, dtype, relu):
+    qmin, qmax = QRANGE[dtype]
+    t = _c(t, np.int64)
+    q = np.empty(t.shape, np.int32)
+    lib().orc_requant(_p(t, C.c_int64), t.size, int(mult), int(sb), int(shift), int(z_out), qmin,
+                      qmax, int(bool(relu)), _p(q, C.c_int32))
+    return q
+
+
+def _conv_out_hw(H, W, R, S, stride, pad):
+    return (H + 2 * pad[0] - R) // stride[0] + 1, (W + 2 * pad[1] - S) // stride[1] + 1
+
+
+def _pair(v):
+    return (int(v), int(v)) if np.isscalar(v) else (int(v[0]), int(v[1]))
+
+
+def conv2d_acc(x, z_x, w, z_w, bias=None, stride=1, pad=0, groups=1, expanded=False):
+    """int64 accumulators (bias included) of a quantized convolution."""
+    x, w = _c(x, np.int32), _c(w, np.int32)
+    N, Cc, H, W = x.shape
+    K, Cg, R, S = w.shape
+    assert Cc % groups == 0 and K % groups == 0 and Cg == Cc // groups
+    stride, pad = _pair(stride), _pair(pad)
+    P, Q = _conv_out_hw(H, W, R, S, stride, pad)
+    t = np.empty((N, K, P, Q), np.int64)
+    b = None if bias is None else _c(bias, np.int64)
+    fn = lib().orc_conv2d_acc_expanded if expanded else lib().orc_conv2d_acc
+    fn(_p(x, C.c_int32), N, Cc, H, W, int(z_x), _p(w, C.c_int32), K, R, S, int(z_w),
+       None if b is None else _p(b, C.c_int64), stride[0], stride[1], pad[0], pad[1], groups,
+       _p(t, C.c_int64))
+    return t
+
+
+def im2col(x, z_x, R, S, stride=1, pad=0, groups=1, g=0):
+    x = _c(x, np.int32)
+    N, Cc, H, W = x.shape
+    stride, pad = _pair(stride), _pair(pad)
+    P, Q = _conv_out_hw(H, W, R, S, stride, pad)
+    Cg = Cc // groups
+    col = np.empty((N * P * Q, Cg * R * S), np.int32)
+    lib().orc_im2col(_p(x, C.c_int32), N, Cc, H, W, int(z_x), R, S, stride[0], stride[1], pad[0],
+                     pad[1], groups, g, _p(col, C.c_int32))
+    return col
+
+
+def gemm_acc(x, z_x, w, z_w, bias=None):
+    x, w = _c(x, np.int32), _c(w, np.int32)
+    M, K = x.shape
+    N, K2 = w.shape
+    assert K == K2
+    t = np.empty((M, N), np.int64)
+    b = None if bias is None else _c(bias, np.int64)
+    lib().orc_gemm_acc(_p(x, C.c_int32), M, K, int(z_x), _p(w, C.c_int32), N, int(z_w),
+                       None if b is None else _p(b, C.c_int64), _p(t, C.c_int64))
+    return t
+
+
+def maxpool_i32(x, k, st):
+    x = _c(x, np.int32)
+    N, Cc, H, W = x.shape
+    P, Q = (H - k) // st + 1, (W - k) // st + 1
+    y = np.empty((N, Cc, P, Q), np.int32)
+    lib().orc_maxpool_i32(_p(x, C.c_int32), N, Cc, H, W, k, st, _p(y, C.c_int32))
+    return y
+
+
+def conv2d_f64(x, w, bias=None, stride=1, pad=0, groups=1, relu=False):
+    x, w = _c(x, np.float64), _c(w, np.float64)
+    N, Cc, H, W = x.shape
+    K, Cg, R, S = w.shape
+    assert Cc % groups == 0 and K % groups == 0 and Cg == Cc // groups
+    stride, pad = _pair(stride), _pair(pad)
+    P, Q = _conv_out_hw(H, W, R, S, stride, pad)
+    y = np.empty((N, K, P, Q), np.float64)
+    b = None if bias is None else _c(bias, np.float64)
+    lib().orc_conv2d_f64(_p(x, C.c_double), N, Cc, H, W, _p(w, C.c_double), K, R, S,
+                         None if b is None else _p(b, C.c_double), stride[0], stride[1], pad[0],
+                         pad[1], groups, int(bool(relu)), _p(y, C.c_double))
+    return y
+
+
+def gemm_f64(x, w, bias=None, relu=False):
+    x, w = _c(x, np.float64), _c(w, np.float64)
+    M, K = x.shape
+    N, K2 = w.shape
+    assert K == K2
+    y = np.empty((M, N), np.float64)
+    b = None if bias is None else _c(bias, np.float64)
+    lib().orc_gemm_f64(_p(x, C.c_double), M, K, _p(w, C.c_double), N,
+                       None if b is None else _p(b, C.c_double), int(bool(relu)), _p(y, C.c_double))
+    return y
+
+
+def maxpool_f64(x, k, st):
+    x = _c(x, np.float64)
+    N, Cc, H, W = x.shape
+    P, Q = (H - k) // st + 1, (W - k) // st + 1
+    y = np.empty((N, Cc, P, Q), np.float64)
+    lib().orc_maxpool_f64(_p(x, C.c_double), N, Cc, H, W, k, st, _p(y, C.c_double))
+    return y
+
+
+def round_fp16(x):
+    x = _c(x, np.float64)
+    y = np.empty(x.shape, np.float64)
+    lib().orc_round_fp16(_p(x, C.c_double), x.size, _p(y, C.c_double))
+    return y
+
+
+def route_top1(logits):
+    lg = _c(logits, np.float64)
+    B, E = lg.shape
+    e = np.empty(B, np.int32)
+    c = np.empty(E, np.int32)
+    lib().orc_route_top1(_p(lg, C.c_double), B, E, _p(e, C.c_int32), _p(c, C.c_int32))
+    return e, c

@@ -1,0 +1,369 @@
+"""Pins of the CPU oracle to things other than itself: values the paper prints, closed forms,
+exact rational / big-integer arithmetic, and library routines (numpy, scipy, torch CPU)."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as o
+from tests.util import read_golden
+from workloads import configs, gen
+
+
+# --------------------------------------------------------------------------------------------
+# Parameter estimation: paper-printed numbers (section "Inference Accuracy", Celsius example)
+# --------------------------------------------------------------------------------------------
+def test_celsius_error_floor_matches_paper():
+    g = read_golden("celsius_error_floor.txt")
+    s8, _, _ = o.estimate_params(g["range_lo"], g["range_hi"], 0, int(g["int8_bins"]))
+    s16, _, _ = o.estimate_params(g["range_lo"], g["range_hi"], 0, int(g["int16_bins"]))
+    # the smallest worst-case error of a uniform quantizer is half a step
+    assert abs(s8 / 2 - g["int8_error_floor"]) < 2e-4
+    assert abs(s16 / 2 - g["int16_error_floor"]) < 5e-4
+    # and quantize -> dequantize really attains at most half a step over that range
+    r = gen.uniform(11, (20000,), g["range_lo"], g["range_hi"]).astype(np.float32)
+    _, z8, _ = o.estimate_params(g["range_lo"], g["range_hi"], -128, 127)
+    q = o.quantize(r, s8, z8, "int8")
+    err = np.abs(o.dequantize(q, s8, z8).astype(np.float64) - r)
+    assert err.max() <= s8 / 2 * (1 + 1e-5)
+    assert err.max() > 0.9 * s8 / 2
+
+
+def test_estimate_params_closed_forms():
+    # fmin = 0  =>  zero-point = imin
+    s, i0, i1 = o.estimate_params(0.0, 51.0, 0, 255)
+    assert s == pytest.approx(0.2) and i0 == 0 and i1 == pytest.approx(5.0)
+    # symmetric range => zero-point at mid range (127.5 rounds to the even neighbour 128)
+    s, i0, i1 = o.estimate_params(-1.0, 1.0, 0, 255)
+    assert i0 == 128 and s == pytest.approx(2 / 255)
+    assert i1 - i0 == pytest.approx(1 / s)
+    # entirely positive range: zero-point clamps to imin; entirely negative: to imax
+    assert o.estimate_params(1.0, 2.0, 0, 255)[1] == 0
+    assert o.estimate_params(-2.0, -1.0, 0, 255)[1] == 255
+    # signed storage is the unsigned one shifted by 128
+    assert o.estimate_params(-0.3, 0.9, -128, 127)[1] == o.estimate_params(-0.3, 0.9, 0, 255)[1] - 128
+
+
+# --------------------------------------------------------------------------------------------
+# quantize / dequantize
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["int8", "int16"])
+def test_quantize_fixed_points_ties_saturation(dtype):
+    qmin, qmax = o.QRANGE[dtype]
+    s, z = np.float32(0.25), 3          # power-of-two scale: r = s k is exact
+    k = np.arange(-40, 40)
+    assert np.array_equal(o.quantize((k * 0.25).astype(np.float32), s, z, dtype), k + z)
+    # ties go to the even integer
+    ties = (k + 0.5) * 0.25
+    expect = np.where(k % 2 == 0, k, k + 1) + z
+    assert np.array_equal(o.quantize(ties.astype(np.float32), s, z, dtype), expect)
+    # saturation, infinities, NaN
+    big = np.array([1e30, -1e30, np.inf, -np.inf, np.nan], np.float32)
+    assert list(o.quantize(big, s, z, dtype)) == [qmax, qmin, qmax, qmin, z]
+    # dequantize of the limits
+    assert list(o.dequantize(np.array([qmin, z, qmax]), s, z)) == [(qmin - z) * 0.25, 0.0, (qmax - z) * 0.25]
+
+
+@pytest.mark.parametrize("dtype,zero", [("int8", 0), ("int8", -17), ("int16", 0), ("int16", 1234)])
+def test_quantize_roundtrip_half_step(dtype, zero):
+    qmin, qmax = o.QRANGE[dtype]
+    s = np.float32(0.0371)
+    lo, hi = float(s) * (qmin - zero), float(s) * (qmax - zero)
+    r = gen.uniform(5, (50000,), lo, hi).astype(np.float32)
+    q = o.quantize(r, s, zero, dtype)
+    assert q.min() >= qmin and q.max() <= qmax
+    back = o.dequantize(q, s, zero).astype(np.float64)
+    # half a step, plus the fp32 rounding of the dequantized product itself
+    assert np.all(np.abs(back - r) <= float(s) / 2 * (1 + 1e-6) + np.abs(back) * 2.0 ** -23)
+    # against exact rational rounding on a sample
+    for v, qq in list(zip(r[:300], q[:300])):
+        x = Fraction(float(v)) / Fraction(float(s))
+        n = round(x)            # Python rounds exact halves to even
+        assert qq == min(max(n + zero, qmin), qmax)
+
+
+# --------------------------------------------------------------------------------------------
+# rescale constants and requantization
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("sb", [31, 15])
+def test_scale_quant_vals_properties(sb):
+    rng = gen.uniform(77, (200, 3), 1e-4, 2.0)
+    for sa, sb_, sc in rng:
+        sa, sb_, sc = np.float32(sa), np.float32(sb_), np.float32(sc)
+        mult, shift = o.scale_quant_vals(sa, sb_, sc, sb)
+        M = Fraction(float(sa)) * Fraction(float(sb_)) / Fraction(float(sc))
+        assert (1 << (sb - 1)) <= mult < (1 << sb)
+        approx = Fraction(mult, 1 << sb) / (Fraction(2) ** shift)
+        # relative error of the fixed-point multiplier: half an ulp of an sb-bit mantissa
+        # (+ the double-precision evaluation of M)
+        assert abs(approx - M) / M <= Fraction(1, 1 << sb) * Fraction(1001, 1000)
+
+
+def test_scale_quant_vals_powers_of_two_and_config1():
+    for sb in (31, 15):
+        assert o.scale_quant_vals(1.0, 1.0, 1.0, sb) == (1 << (sb - 1), -1)
+        assert o.scale_quant_vals(0.5, 0.25, 1.0, sb) == (1 << (sb - 1), 2)
+        assert o.scale_quant_vals(4.0, 2.0, 1.0, sb) == (1 << (sb - 1), -4)
+    # config 1: 0.02 * 0.01 / 0.05 = 0.004 = 0.512 * 2^-7
+    mult, shift = o.scale_quant_vals(0.02, 0.01, 0.05, 31)
+    assert shift == 7
+    M0 = Fraction(float(np.float32(0.02))) * Fraction(float(np.float32(0.01))) \
+        / Fraction(float(np.float32(0.05))) * 128
+    assert abs(mult - M0 * (1 << 31)) <= Fraction(1, 2) + Fraction(1, 1000)
+    assert abs(mult / 2 ** 31 - 0.512) < 1e-6
+    with pytest.raises(ValueError):
+        o.scale_quant_vals(0.0, 1.0, 1.0, 31)
+
+
+def _requant_bigint(t, mult, sb, shift, z, lo, hi):
+    """The listing's integer pipeline with Python integers (arbitrary precision)."""
+    p = t * mult
+    y = abs(p) >> sb                # truncation toward zero = floor of the magnitude
+    y = -y if p < 0 else y
+    y = (y >> shift) if shift >= 0 else y * (1 << -shift)     # Python >> is floor
+    return min(max(y + z, lo), hi)
+
+
+@pytest.mark.parametrize("dtype", ["int8", "int16"])
+def test_requant_bigint_and_real_bracket(dtype):
+    qmin, qmax = o.QRANGE[dtype]
+    sb = o.SHIFT_BITS[dtype]
+    cases = [(0.02, 0.01, 0.05), (0.5, 0.5, 0.01), (1.0, 1.0, 1.0), (3e-3, 7e-3, 0.9), (2.0, 3.0, 0.5)]
+    # accumulator range: int32 for 8-bit storage (so t * mult < 2^62), up to 2^44 for 16-bit
+    big = 2 ** 31 - 1 if dtype == "int8" else 2 ** 44
+    ts = np.concatenate([gen.integers(3, (400,), -5000, 5000), gen.integers(4, (200,), -big, big),
+                         np.arange(-40, 41)])
+    for sa, sw, sy in cases:
+        mult, shift = o.scale_quant_vals(sa, sw, sy, sb)
+        M = Fraction(float(np.float32(sa))) * Fraction(float(np.float32(sw))) / Fraction(float(np.float32(sy)))
+        for z in (0, 5):
+            got = o.requant(ts, mult, sb, shift, z, dtype, relu=False)
+            for t, g in zip(ts.tolist(), got.tolist()):
+                assert g == _requant_bigint(t, mult, sb, shift, z, qmin, qmax)
+                # bracket: the rule is truncate-then-floor, never more than one step below the
+                # exact real product t M (plus the multiplier's relative error), never above it
+                # for t >= 0; for t < 0 truncation may lift it by less than one step.
+                if qmin < g < qmax:
+                    exact = Fraction(t) * M
+                    slack = abs(exact) * Fraction(2, 1 << sb) + Fraction(1, 1000)
+                    up = Fraction(1 << -shift) if shift < 0 else Fraction(1)
+                    assert exact - up - slack <= (g - z) <= exact + up + slack
+                    if t >= 0:
+                        assert (g - z) <= exact + slack
+
+
+def test_requant_negative_truncates_then_floors():
+    # mult = 2^30 (M0 = 0.5), sb = 31, shift = 1: y = trunc(t / 2) then floor(y / 2)
+    mult, sb, shift = 1 << 30, 31, 1
+    expect = {-1: 0, -2: -1, -3: -1, -4: -1, -5: -1, -6: -2, -7: -2, 7: 1, 3: 0, 5: 1, 0: 0}
+    for t, y in expect.items():
+        assert o.requant_one(t, mult, sb, shift, 0, -128, 127) == y
+    # left shift branch (M >= 1): plain multiplication by a power of two, also for negatives
+    assert o.requant_one(-3, 1 << 30, 31, -3, 0, -128, 127) == -8   # trunc(-1.5) = -1, * 8
+    assert o.requant_one(3, 1 << 30, 31, -3, 0, -128, 127) == 8
+
+
+def test_relu_commutes_with_requant():
+    # requant(max(t, 0)) == max(requant(t), z): the raised lower clamp is the paper's ReLU kernel
+    ts = np.arange(-3000, 3000, 7)
+    for (sa, sw, sy), z in [((0.02, 0.01, 0.05), 0), ((0.3, 0.2, 0.11), -20), ((1.0, 2.0, 0.7), 9)]:
+        mult, shift = o.scale_quant_vals(sa, sw, sy, 31)
+        fused = o.requant(ts, mult, 31, shift, z, "int8", relu=True)
+        pre = o.requant(np.maximum(ts, 0), mult, 31, shift, z, "int8", relu=False)
+        post = np.maximum(o.requant(ts, mult, 31, shift, z, "int8", relu=False), z)
+        assert np.array_equal(fused, pre) and np.array_equal(fused, post)
+
+
+# --------------------------------------------------------------------------------------------
+# convolution indexing: identity / one-hot kernels, library routines, second formulation
+# --------------------------------------------------------------------------------------------
+def _rand_codes(seed, shape, lo=-128, hi=127):
+    return gen.integers(seed, shape, lo, hi)
+
+
+def test_conv_one_hot_kernel_is_shifted_copy():
+    N, Cc, H, W = 2, 3, 9, 8
+    x = _rand_codes(1, (N, Cc, H, W))
+    for (c0, r0, s0, stride, pad) in [(0, 0, 0, 1, 0), (2, 1, 2, 1, 1), (1, 2, 0, 2, 1), (0, 1, 1, 3, 2)]:
+        w = np.zeros((4, Cc, 3, 3), np.int64)
+        w[1, c0, r0, s0] = 1
+        t = o.conv2d_acc(x, 0, w, 0, None, stride, pad, 1)
+        P, Q = t.shape[2:]
+        ref = np.zeros((N, P, Q), np.int64)
+        for p in range(P):
+            for q in range(Q):
+                h, ww = p * stride - pad + r0, q * stride - pad + s0
+                if 0 <= h < H and 0 <= ww < W:
+                    ref[:, p, q] = x[:, c0, h, ww]
+        assert np.array_equal(t[:, 1], ref)
+        assert not t[:, [0, 2, 3]].any()
+
+
+def test_conv_groups_only_see_their_channels():
+    x = _rand_codes(2, (1, 6, 5, 5))
+    w = np.zeros((4, 3, 1, 1), np.int64)       # groups = 2: K/g = 2, C/g = 3
+    w[0, 1, 0, 0] = 1                          # group 0, its channel 1  -> input channel 1
+    w[3, 2, 0, 0] = 1                          # group 1, its channel 2  -> input channel 5
+    t = o.conv2d_acc(x, 0, w, 0, None, 1, 0, 2)
+    assert np.array_equal(t[0, 0], x[0, 1]) and np.array_equal(t[0, 3], x[0, 5])
+    assert not t[0, 1].any() and not t[0, 2].any()
+
+
+@pytest.mark.parametrize("stride,pad,groups", [(1, 0, 1), (1, 2, 2), (2, 1, 1), (4, 0, 1), (3, 2, 4)])
+def test_conv_matches_torch_cpu_library(stride, pad, groups):
+    N, Cc, H, W, K, R = 2, 8, 13, 11, 12, 5
+    x = _rand_codes(10 + stride, (N, Cc, H, W))
+    w = _rand_codes(20 + pad, (K, Cc // groups, R, R - 2))
+    b = _rand_codes(30, (K,), -1000, 1000)
+    zx, zw = 7, -3
+    t = o.conv2d_acc(x, zx, w, zw, b, stride, pad, groups)
+    # library: fp64 convolution of the differences (zero padding == "outside taps contribute 0");
+    # all values are small integers so fp64 is exact
+    ref = torch.nn.functional.conv2d(torch.from_numpy((x - zx).astype(np.float64)),
+                                     torch.from_numpy((w - zw).astype(np.float64)),
+                                     torch.from_numpy(b.astype(np.float64)),
+                                     stride=stride, padding=pad, groups=groups).numpy()
+    assert np.array_equal(t, ref.astype(np.int64))
+    # the floating-point oracle against the same library routine
+    xf, wf, bf = gen.normal(1, x.shape), gen.normal(2, w.shape), gen.normal(3, (K,))
+    y = o.conv2d_f64(xf, wf, bf, stride, pad, groups, relu=True)
+    ref = torch.relu(torch.nn.functional.conv2d(torch.from_numpy(xf), torch.from_numpy(wf),
+                                                torch.from_numpy(bf), stride=stride, padding=pad,
+                                                groups=groups)).numpy()
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_conv_is_correlation_not_flipped():
+    from scipy.signal import correlate2d
+    x = _rand_codes(5, (1, 1, 7, 6))
+    w = _rand_codes(6, (1, 1, 3, 2))
+    t = o.conv2d_acc(x, 0, w, 0)
+    assert np.array_equal(t[0, 0], correlate2d(x[0, 0], w[0, 0], mode="valid"))
+
+
+@pytest.mark.parametrize("zx,zw", [(0, 0), (5, 0), (0, -9), (-128, 127), (13, -7)])
+def test_expanded_form_equals_differences_first(zx, zw):
+    x = _rand_codes(40, (2, 4, 7, 7))
+    w = _rand_codes(41, (6, 2, 3, 3))
+    b = _rand_codes(42, (6,), -500, 500)
+    a = o.conv2d_acc(x, zx, w, zw, b, 2, 1, 2)
+    e = o.conv2d_acc(x, zx, w, zw, b, 2, 1, 2, expanded=True)
+    assert np.array_equal(a, e)
+
+
+def test_conv_equals_im2col_gemm_and_gemm_is_1x1_conv():
+    x = _rand_codes(50, (2, 6, 8, 7))
+    w = _rand_codes(51, (8, 3, 3, 3))
+    b = _rand_codes(52, (8,), -99, 99)
+    zx, zw, stride, pad, groups = 4, -2, 2, 1, 2
+    t = o.conv2d_acc(x, zx, w, zw, b, stride, pad, groups)
+    N, K, P, Q = t.shape
+    for g in range(groups):
+        col = o.im2col(x, zx, 3, 3, stride, pad, groups, g)
+        wg = w[g * 4:(g + 1) * 4].reshape(4, -1)
+        tg = o.gemm_acc(col, zx, wg, zw, b[g * 4:(g + 1) * 4]).reshape(N, P, Q, 4).transpose(0, 3, 1, 2)
+        assert np.array_equal(t[:, g * 4:(g + 1) * 4], tg)
+    # GEMM == 1x1 convolution on a 1x1 image
+    xm = _rand_codes(53, (5, 33))
+    wm = _rand_codes(54, (9, 33))
+    bm = _rand_codes(55, (9,), -50, 50)
+    tg = o.gemm_acc(xm, 3, wm, 1, bm)
+    tc = o.conv2d_acc(xm.reshape(5, 33, 1, 1), 3, wm.reshape(9, 33, 1, 1), 1, bm)
+    assert np.array_equal(tg, tc.reshape(5, 9))
+    # and numpy's integer matmul
+    assert np.array_equal(tg, (xm - 3) @ (wm - 1).T + bm)
+
+
+def test_gemm_f64_matches_numpy():
+    x, w, b = gen.normal(1, (7, 40)), gen.normal(2, (11, 40)), gen.normal(3, (11,))
+    assert np.allclose(o.gemm_f64(x, w, b, relu=True), np.maximum(x @ w.T + b, 0), rtol=1e-12, atol=1e-13)
+
+
+def test_int16_accumulators_beyond_int32():
+    K = 4096
+    x = np.full((1, K), 32767, np.int64)
+    w = np.stack([np.full(K, 32767), np.full(K, -32768)]).astype(np.int64)
+    t = o.gemm_acc(x, 0, w, 0)
+    assert t[0, 0] == K * 32767 * 32767 > 2 ** 31
+    assert t[0, 1] == -K * 32767 * 32768
+    mult, shift = o.scale_quant_vals(1e-3, 1e-3, 400.0, 15)
+    for v in t[0].tolist():
+        got = o.requant_one(v, mult, 15, shift, 0, -32768, 32767)
+        assert got == _requant_bigint(v, mult, 15, shift, 0, -32768, 32767)
+        assert -32768 < got < 32767        # not saturated: the check is meaningful
+
+
+# --------------------------------------------------------------------------------------------
+# pooling
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("k,st,H", [(3, 2, 13), (3, 2, 55), (2, 2, 24), (2, 2, 8)])
+def test_maxpool_matches_torch_and_commutes_with_quantize(k, st, H):
+    r = gen.normal(60 + H, (2, 3, H, H)).astype(np.float32)
+    q = o.quantize(r, 0.03, 2, "int8")
+    y = o.maxpool_i32(q, k, st)
+    ref = torch.nn.functional.max_pool2d(torch.from_numpy(q.astype(np.float64)), k, st).numpy()
+    assert np.array_equal(y, ref.astype(np.int32))
+    yf = o.maxpool_f64(r.astype(np.float64), k, st)
+    ref = torch.nn.functional.max_pool2d(torch.from_numpy(r.astype(np.float64)), k, st).numpy()
+    assert np.array_equal(yf, ref)
+    # monotone affine map: pooling the codes == quantizing the pooled reals
+    assert np.array_equal(y, o.quantize(yf.astype(np.float32), 0.03, 2, "int8"))
+
+
+# --------------------------------------------------------------------------------------------
+# fp16 rounding
+# --------------------------------------------------------------------------------------------
+def test_round_fp16_matches_numpy_half():
+    v = np.concatenate([gen.normal(70, (20000,), 0, 1.0), gen.normal(71, (5000,), 0, 1e-6),
+                        gen.normal(72, (5000,), 0, 3e4), gen.uniform(73, (2000,), -7e4, 7e4),
+                        [0.0, -0.0, 65504.0, 65519.99, 65520.0, -65520.0, 2.0 ** -24, 2.0 ** -25,
+                         1.5 * 2.0 ** -25, 2.0 ** -14, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11]])
+    with np.errstate(over="ignore"):
+        ref = v.astype(np.float16).astype(np.float64)
+    got = o.round_fp16(v)
+    assert np.array_equal(got, ref)
+
+
+# --------------------------------------------------------------------------------------------
+# routing
+# --------------------------------------------------------------------------------------------
+def test_route_top1():
+    lg = gen.normal(80, (300, 5))
+    e, c = o.route_top1(lg)
+    assert np.array_equal(e, np.argmax(lg, axis=1))
+    assert np.array_equal(c, np.bincount(e, minlength=5)) and c.sum() == 300
+    # ties: lowest index
+    t = np.array([[1.0, 3.0, 3.0, 2.0], [0.0, 0.0, 0.0, 0.0], [-1.0, -2.0, -1.0, -3.0]])
+    assert list(o.route_top1(t)[0]) == [1, 0, 0]
+    # everything favours one expert
+    lg[:, 3] += 100
+    e, c = o.route_top1(lg)
+    assert (e == 3).all() and list(c) == [0, 0, 0, 300, 0]
+    # benchmark-mode logits hit the prescribed 40/30/20/10 % split exactly
+    e, c = o.route_top1(configs.moe_benchmark_logits())
+    assert tuple(c) == configs.MOE_COUNTS_256
+
+
+# --------------------------------------------------------------------------------------------
+# shape tables against statements of the paper
+# --------------------------------------------------------------------------------------------
+def test_alexnet_shape_table_matches_printed_storage():
+    g = read_golden("alexnet_storage.txt")
+    n = sum(L.K * (L.C // L.groups) * L.R * L.S + L.K for L in configs.ALEXNET_CONVS)
+    n += sum(L.N * L.K + L.N for L in configs.ALEXNET_FCS)
+    assert round(n * 4 / g["unit_bytes"], 1) == g["fp32_mib"]
+    assert round(n * 2 / g["unit_bytes"], 1) == g["fp16_mib"] == g["int16_mib"]
+    assert round(n * 1 / g["unit_bytes"], 1) == g["int8_mib"]
+
+
+def test_quarter_width_expert_is_about_16x_cheaper():
+    g = read_golden("moe_cost_ratios.txt")
+    d = int(g["width_divisor"])
+    full = configs.ALEXNET_CONVS[2:]
+    hw = 13
+    full_macs = sum(L.macs(hw, hw) for L in full)
+    quarter = [configs.Conv(L.name, L.K // d, L.C // d, L.R, L.S, L.stride, L.pad, L.groups) for L in full]
+    q_macs = sum(L.macs(hw, hw) for L in quarter)
+    assert full_macs / q_macs == pytest.approx(g["expert_cost_divisor"])
+    assert g["experts_total"] / g["experts_per_sample"] == g["compute_reduction"]

@@ -1,0 +1,206 @@
+"""Shapes and seeded real-valued tensors of the five benchmark configurations.
+
+Pure description + random draws (workloads.gen): no quantization, no layer arithmetic.  Every
+tensor is returned in the paper's logical layout (activations N,C,H,W; conv weights
+K,C/groups,R,S; FC weights N_out,K_in) as fp64; consumers cast / quantize / re-lay-out on their
+own side.
+
+Seeds: 1000 * config + tensor ordinal (config 1 uses base 0, i.e. seeds 0, 1, 2).
+He-normal: std = sqrt(2 / (C/groups * R * S)).  "N(0, x)" is read as standard deviation x.
+"""
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+
+from . import gen
+
+
+@dataclass
+class Conv:
+    name: str
+    K: int            # output channels
+    C: int            # input channels (all groups)
+    R: int
+    S: int
+    stride: int = 1
+    pad: int = 0
+    groups: int = 1
+    relu: bool = True
+    pool_k: int = 0   # max-pool that follows (0 = none)
+    pool_s: int = 0
+    kind: str = "conv"
+
+    def out_hw(self, H, W):
+        P = (H + 2 * self.pad - self.R) // self.stride + 1
+        Q = (W + 2 * self.pad - self.S) // self.stride + 1
+        return P, Q
+
+    def macs(self, H, W):
+        P, Q = self.out_hw(H, W)
+        return P * Q * self.K * (self.C // self.groups) * self.R * self.S
+
+
+@dataclass
+class FC:
+    name: str
+    N: int            # output features
+    K: int            # input features
+    relu: bool = True
+    kind: str = "fc"
+
+    def macs(self):
+        return self.N * self.K
+
+
+# ---- config 3: AlexNet-shaped convolution stack (paper section "ImageNet Configuration") ------
+ALEXNET_INPUT = (3, 227, 227)
+ALEXNET_CONVS = [
+    Conv("conv1", 96, 3, 11, 11, stride=4, pad=0, groups=1, pool_k=3, pool_s=2),
+    Conv("conv2", 256, 96, 5, 5, stride=1, pad=2, groups=2, pool_k=3, pool_s=2),
+    Conv("conv3", 384, 256, 3, 3, stride=1, pad=1, groups=1),
+    Conv("conv4", 384, 384, 3, 3, stride=1, pad=1, groups=2),
+    Conv("conv5", 256, 384, 3, 3, stride=1, pad=1, groups=2, pool_k=3, pool_s=2),
+]
+
+# ---- config 4: AlexNet-shaped fully connected layers as standalone GEMMs ----------------------
+ALEXNET_FCS = [
+    FC("fc6", 4096, 9216, relu=True),
+    FC("fc7", 4096, 4096, relu=True),
+    FC("fc8", 1000, 4096, relu=False),
+]
+FC_BATCHES = (1, 16, 256)
+
+# ---- config 2: LeNet-shaped net ---------------------------------------------------------------
+LENET_INPUT = (1, 28, 28)
+LENET_LAYERS = [
+    Conv("conv1", 20, 1, 5, 5, relu=False, pool_k=2, pool_s=2),
+    Conv("conv2", 50, 20, 5, 5, relu=False, pool_k=2, pool_s=2),
+    FC("ip1", 500, 800, relu=True),
+    FC("ip2", 10, 500, relu=False),
+]
+
+# ---- config 5: mixture-of-experts variant -----------------------------------------------------
+MOE_EXPERTS = 4
+MOE_COUNTS_256 = (102, 77, 51, 26)          # 40 / 30 / 20 / 10 % of 256, summing to 256
+MOE_TRUNK = ALEXNET_CONVS[:2]               # conv1 + pool, conv2 + pool -> 256 x 13 x 13
+MOE_GATE = FC("gate", MOE_EXPERTS, 256 * 13 * 13, relu=False)
+MOE_EXPERT_LAYERS = [                        # half the channel width of config 3's conv3..conv5
+    Conv("conv3", 192, 256, 3, 3, pad=1, groups=1),
+    Conv("conv4", 192, 192, 3, 3, pad=1, groups=2),
+    Conv("conv5", 128, 192, 3, 3, pad=1, groups=2, pool_k=3, pool_s=2),
+    FC("fc", 2048, 128 * 6 * 6, relu=True),
+]
+
+
+def _he_std(layer: Conv) -> float:
+    return float(np.sqrt(2.0 / ((layer.C // layer.groups) * layer.R * layer.S)))
+
+
+def conv_weights(seed: int, layer: Conv, std: Optional[float] = None) -> np.ndarray:
+    std = _he_std(layer) if std is None else std
+    return gen.normal(seed, (layer.K, layer.C // layer.groups, layer.R, layer.S), 0.0, std)
+
+
+def fc_weights(seed: int, layer: FC, std: float) -> np.ndarray:
+    return gen.normal(seed, (layer.N, layer.K), 0.0, std)
+
+
+def bias(seed: int, n: int, std: float = 0.1) -> np.ndarray:
+    return gen.normal(seed, (n,), 0.0, std)
+
+
+# ---- config 1 -------------------------------------------------------------------------------
+@dataclass
+class Config1:
+    """Single int8 conv layer given directly as integer codes."""
+    layer: Conv = field(default_factory=lambda: Conv("conv", 16, 3, 3, 3, stride=1, pad=1, relu=True))
+    s_x: float = 0.02
+    s_w: float = 0.01
+    s_y: float = 0.05
+
+    def tensors(self):
+        x = gen.integers(0, (1, 3, 32, 32), -128, 127)
+        w = gen.integers(1, (16, 3, 3, 3), -128, 127)
+        b = gen.integers(2, (16,), -1000, 1000)
+        return x, w, b
+
+
+# ---- config 2 -------------------------------------------------------------------------------
+def lenet_tensors(batch: int = 64):
+    base = 2000
+    x = gen.uniform(base + 0, (batch,) + LENET_INPUT, 0.0, 1.0)
+    params = []
+    for i, L in enumerate(LENET_LAYERS):
+        if L.kind == "conv":
+            w = conv_weights(base + 10 + 2 * i, L, std=0.05)
+            b = bias(base + 11 + 2 * i, L.K, 0.05)
+        else:
+            w = fc_weights(base + 10 + 2 * i, L, std=0.05)
+            b = bias(base + 11 + 2 * i, L.N, 0.05)
+        params.append((w, b))
+    return x, params
+
+
+# ---- config 3 -------------------------------------------------------------------------------
+def alexnet_input(batch: int, first: int = 0) -> np.ndarray:
+    """Images [first, first + batch) of the config-3 batch; image i never depends on batch."""
+    out = np.empty((batch,) + ALEXNET_INPUT, np.float64)
+    for i in range(batch):
+        out[i] = _alex_image(first + i)
+    return out
+
+
+def _alex_image(index: int) -> np.ndarray:
+    # one seed per image keeps any sub-batch identical to the same images of the full batch
+    return gen.normal(3_000_000 + index, ALEXNET_INPUT, 0.0, 1.0)
+
+
+def alexnet_conv_params(layers: List[Conv] = None, base: int = 3000):
+    layers = ALEXNET_CONVS if layers is None else layers
+    out = []
+    for i, L in enumerate(layers):
+        out.append((conv_weights(base + 10 + 2 * i, L), bias(base + 11 + 2 * i, L.K, 0.1)))
+    return out
+
+
+# ---- config 4 -------------------------------------------------------------------------------
+def fc_case(layer_index: int, batch: int):
+    L = ALEXNET_FCS[layer_index]
+    base = 4000 + 100 * layer_index
+    x = np.abs(gen.normal(base + 0, (256, L.K), 0.0, 1.0))[:batch]   # rows independent of batch
+    w = fc_weights(base + 1, L, std=0.01)
+    b = bias(base + 2, L.N, 0.1)
+    return L, x, w, b
+
+
+# ---- config 5 -------------------------------------------------------------------------------
+def moe_params():
+    """Trunk shares config 3's conv1/conv2 parameters; gate and experts have their own seeds."""
+    trunk = alexnet_conv_params(MOE_TRUNK, base=3000)
+    gate_w = fc_weights(5001, MOE_GATE, std=float(np.sqrt(1.0 / MOE_GATE.K)))
+    experts = []
+    for e in range(MOE_EXPERTS):
+        ps = []
+        for i, L in enumerate(MOE_EXPERT_LAYERS):
+            seed = 5100 + 100 * e + 2 * i
+            if L.kind == "conv":
+                ps.append((conv_weights(seed, L), bias(seed + 1, L.K, 0.1)))
+            else:
+                ps.append((fc_weights(seed, L, std=float(np.sqrt(2.0 / L.K))), bias(seed + 1, L.N, 0.1)))
+        experts.append(ps)
+    return trunk, gate_w, experts
+
+
+def moe_benchmark_logits(batch: int = 256, counts=MOE_COUNTS_256, seed: int = 5002) -> np.ndarray:
+    """N(0,1) logits [batch, E] whose per-row maximum sits in a seeded assignment with exactly
+    counts[e] rows for expert e: the row's largest entry is swapped into the assigned column."""
+    E = len(counts)
+    assert sum(counts) == batch
+    lg = gen.normal(seed, (batch, E), 0.0, 1.0)
+    assign = np.repeat(np.arange(E), counts)[gen.permutation(seed + 1, batch)]
+    top = np.argmax(lg, axis=1)
+    rows = np.arange(batch)
+    a, b = lg[rows, top].copy(), lg[rows, assign].copy()
+    lg[rows, top], lg[rows, assign] = b, a
+    return lg
