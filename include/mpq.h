@@ -1,0 +1,213 @@
+/*
+ * mpq.h -- C ABI of libmpq: mixed-precision (int8 / int16 / fp16) convolution, fully-connected
+ * and mixture-of-experts inference kernels for AMD MI355X (gfx950).
+ *
+ * Source of the operations: F. Tschopp, "Tuning of Mixture-of-Experts Mixed-Precision Neural
+ * Networks" (2018).  Each entry point cites the passage that defines what it computes.
+ *
+ * General conventions
+ *   - Every `void* stream` is a hipStream_t (NULL = the default stream).  Calls only enqueue
+ *     work on that stream: no device synchronisation, no allocation, no host read-back.
+ *   - Every data pointer is a DEVICE pointer unless its comment says "host".  The caller owns
+ *     all buffers (inputs, outputs, packed weights, workspace) and keeps them alive until the
+ *     stream has passed the call.  Outputs must not alias inputs.
+ *   - Activations are NHWC (channel fastest).  A matrix [M, K] is the tensor n=M, h=w=1, c=K.
+ *   - Quantized storage is signed two's complement (int8, int16) with a per-tensor affine map
+ *     real = scale * (code - zero_point)  (section "Quantized Operations").  The paper's
+ *     unsigned codes map onto it by subtracting 128 (32768) from code and zero-point.
+ *   - Errors are returned, never thrown; argument errors are detected on the host before any
+ *     kernel is launched, and nothing is launched in that case.
+ */
+#ifndef MPQ_H
+#define MPQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MPQ_OK = 0,
+    MPQ_ERR_INVALID_ARG = 1,   /* null pointer, bad enum, scale <= 0 or non-finite, zero-point out of range */
+    MPQ_ERR_SHAPE = 2,         /* tensor shapes inconsistent with each other or with the descriptor */
+    MPQ_ERR_UNSUPPORTED = 3,   /* valid request that this build has no kernel for */
+    MPQ_ERR_WORKSPACE = 4,     /* workspace / packed-weight buffer smaller than the size query says */
+    MPQ_ERR_DEVICE = 5         /* a HIP call (launch) reported an error */
+} mpq_status;
+
+typedef enum {
+    MPQ_INT8 = 0,
+    MPQ_INT16 = 1,
+    MPQ_FP16 = 2,
+    MPQ_FP32 = 3,
+    MPQ_INT32 = 4
+} mpq_dtype;
+
+/* Per-tensor affine quantization parameters; ignored for MPQ_FP16 / MPQ_FP32 tensors. */
+typedef struct {
+    float scale;          /* > 0, finite */
+    int32_t zero_point;   /* within the storage type's range */
+} mpq_qparams;
+
+/* Non-owning view of a device tensor in NHWC order. */
+typedef struct {
+    void *data;
+    int32_t dtype;        /* mpq_dtype */
+    int32_t n, h, w, c;
+    mpq_qparams q;
+} mpq_tensor;
+
+/*
+ * Geometry of one convolution / fully-connected layer (section "ImageNet Configuration" lists
+ * the layer kinds: convolution with kernel size, stride, pad, group; ReLU; max pooling).
+ * Output size per axis: floor((in + 2 pad - kernel) / stride) + 1.  groups splits input and
+ * output channels into contiguous blocks.  relu != 0 applies max(., 0) in the real domain.
+ * pool_k > 0 appends a pool_k x pool_k max-pool with stride pool_s (no padding, floor size),
+ * which keeps the quantization parameters of the convolution output.
+ * A fully-connected layer is r = s = 1 on a 1x1 image (use mpq_gemm_desc()).
+ */
+typedef struct {
+    int32_t c, k;                 /* input / output channels (all groups) */
+    int32_t r, s;                 /* kernel height / width */
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;
+    int32_t groups;
+    int32_t relu;
+    int32_t pool_k, pool_s;       /* 0, 0 = no pooling */
+} mpq_conv_desc;
+
+const char *mpq_status_string(mpq_status s);
+
+/* Version of this ABI (bumped when a signature or packed layout changes). */
+int32_t mpq_abi_version(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * Quantizer conversions (section "Quantization Integration to Caffe": a quantizer converts a
+ * blob between the floating-point and the quantized type; the affine map is the one of section
+ * "Quantized Operations").
+ *   quantize:   dst[i] = clamp(round_half_even(src[i] / scale) + zero_point, type_min, type_max)
+ *               with the quotient evaluated in fp64; NaN -> zero_point, +-inf saturate.
+ *               dtype: MPQ_INT8, MPQ_INT16, or MPQ_INT32 (bias codes, accumulator domain).
+ *   dequantize: dst[i] = (float)(src[i] - zero_point) * scale  (one fp32 multiply).
+ *   to_fp16 / from_fp16: fp32 <-> fp16 storage, round-to-nearest-even.
+ * count elements, contiguous.  count == 0 is a valid no-op.
+ * ------------------------------------------------------------------------------------------- */
+mpq_status mpq_quantize(const float *src, void *dst, size_t count, mpq_dtype dtype,
+                        mpq_qparams q, void *stream);
+mpq_status mpq_dequantize(const void *src, float *dst, size_t count, mpq_dtype dtype,
+                          mpq_qparams q, void *stream);
+mpq_status mpq_to_fp16(const float *src, void *dst, size_t count, void *stream);
+mpq_status mpq_from_fp16(const void *src, float *dst, size_t count, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Integer rescale constants (section "Quantized Operations", the (x * m) >> h equation; the
+ * shift_bits expression in the listing "Caffe device abstracted launch code"):
+ * M = s_x s_w / s_y = M0 2^e with M0 in [0.5, 1); mult = round(M0 2^sb), shift = -e,
+ * sb = 31 for MPQ_INT8 and 15 for MPQ_INT16.  Host-only helper; outputs are host pointers.
+ * This is what mpq_conv2d / mpq_gemm derive internally from the three scales.
+ * ------------------------------------------------------------------------------------------- */
+mpq_status mpq_scale_quant_vals(float s_x, float s_w, float s_y, mpq_dtype dtype,
+                                int64_t *mult /* host */, int32_t *shift /* host */);
+
+/* ---------------------------------------------------------------------------------------------
+ * Weight packing (one-time, outside the hot path).  Converts weights from the logical layout
+ * K, C/groups, R, S (the paper's framework keeps them so) into the kernel layout used by
+ * mpq_conv2d / mpq_gemm for this descriptor and dtype, and appends the per-output-channel sums
+ * of the weight codes that the expanded zero-point form needs (section "Quantized Operations",
+ * second multiplication equation: the - b i0(a) term is constant per output channel).
+ *   w_kcrs   device, dtype elements, K * (C/groups) * R * S of them
+ *   packed   device, at least mpq_packed_weight_bytes() bytes, 256-byte aligned
+ * ------------------------------------------------------------------------------------------- */
+size_t mpq_packed_weight_bytes(const mpq_conv_desc *d, mpq_dtype dtype);
+mpq_status mpq_pack_weights(const void *w_kcrs, const mpq_conv_desc *d, mpq_dtype dtype,
+                            void *packed, size_t packed_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Convolution with fused bias + ReLU + requantize (+ optional max-pool).
+ * Integer types (x, w, y all MPQ_INT8 or all MPQ_INT16), per output element
+ *   acc = sum over the window of (x - z_x)(w - z_w)          (section "Quantized Operations";
+ *         taps outside the image contribute 0; cross-correlation; exact, never wraps)
+ *   t   = acc + bias[k]                                      (bias: int32 codes at scale s_x s_w)
+ *   y   = (t * mult) / 2^sb   truncating toward zero, then  >> shift  (arithmetic; a negative
+ *         shift multiplies by 2^-shift)                      (integer branch of the quantized
+ *         ReLU listing in section "Emitted OpenCL Runtime Code", applied to every operator)
+ *   out = min(max(y + z_y, lo), type_max), lo = relu ? max(type_min, z_y) : type_min
+ * y.dtype may instead be MPQ_INT32: then out = t (raw accumulator, no rescale; used for gating).
+ * MPQ_FP16: out = fp16(relu(sum in fp32 of x w + bias[k])), bias fp32; y.dtype MPQ_FP16 or
+ * MPQ_FP32 (raw).  The paper accumulates floats in the storage type; fp32 is used here.
+ *   x        input view; x->c == d->c
+ *   w_packed from mpq_pack_weights with the same descriptor and dtype; w_q its parameters
+ *   bias     device, k entries (int32 for integer types, fp32 for fp16), or NULL
+ *   y        output view; n, h, w, c must equal the layer's output shape (after pooling)
+ *   ws       device scratch of at least mpq_conv2d_workspace_bytes(), 256-byte aligned
+ * ------------------------------------------------------------------------------------------- */
+size_t mpq_conv2d_workspace_bytes(const mpq_tensor *x, const mpq_conv_desc *d);
+mpq_status mpq_conv2d(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q,
+                      const void *bias, mpq_tensor *y, const mpq_conv_desc *d,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Fully-connected layer y[m, n] = epilogue(sum_k (x[m,k] - z_x)(w[n,k] - z_w) + bias[n]),
+ * same arithmetic and dtype rules as mpq_conv2d (the paper's InnerProduct layers, section
+ * "ImageNet Configuration").  x is [M, K] (n=M, h=w=1, c=K); weights are logically [N, K],
+ * packed with mpq_pack_weights(mpq_gemm_desc(K, N, relu)).
+ * ------------------------------------------------------------------------------------------- */
+mpq_conv_desc mpq_gemm_desc(int32_t k_in, int32_t n_out, int32_t relu);
+size_t mpq_gemm_workspace_bytes(const mpq_tensor *x, int32_t n_out);
+mpq_status mpq_gemm(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q,
+                    const void *bias, mpq_tensor *y, int32_t relu,
+                    void *ws, size_t ws_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Max-pool (the pooling layers of section "ImageNet Configuration"): window k x k, stride s,
+ * no padding, floor output size; integer or fp16 max; output keeps the input's parameters.
+ * ------------------------------------------------------------------------------------------- */
+mpq_status mpq_maxpool2d(const mpq_tensor *x, mpq_tensor *y, int32_t k, int32_t s, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Mixture-of-experts stage, one expert per sample (section "Mixture of Experts": the gating
+ * selection picks experts per sample; outputs of the selected experts are summed weighted by
+ * probabilities renormalised over the selection -- with top_k = 1 that weight is 1).
+ *   expert[b] = argmax_i logits[b, i]   (lowest index on ties)
+ *   y[b]      = expert_chain[expert[b]](x[b])
+ * Internally: route -> per-expert counts / exclusive offsets / stable permutation -> gather the
+ * samples into expert-contiguous order -> each layer as ONE launch over all experts' segments
+ * -> scatter rows back to sample order.
+ *
+ * All experts share layer geometry ("identical input and output tensor dimensions") and differ
+ * in weights and quantization parameters.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    mpq_conv_desc desc;        /* geometry; an FC layer is mpq_gemm_desc() */
+    int32_t is_fc;             /* 1: the activation is flattened (h, w, c order) before the layer */
+    const void *w_packed;      /* device: num_experts packed weight blobs, expert e at e * w_stride */
+    size_t w_stride;           /* bytes; >= mpq_packed_weight_bytes(desc) and a multiple of 256 */
+    const void *bias;          /* device: [num_experts][desc.k] or NULL */
+    const mpq_qparams *w_q;    /* host: [num_experts] */
+    const mpq_qparams *y_q;    /* host: [num_experts] output parameters of this layer */
+} mpq_moe_layer;
+
+size_t mpq_moe_workspace_bytes(const mpq_tensor *x, int32_t num_experts,
+                               const mpq_moe_layer *layers /* host */, int32_t num_layers);
+/*
+ *   x            trunk output [B, h, w, c]
+ *   logits       device [B, num_experts], logits_dtype MPQ_INT32 or MPQ_FP32
+ *   top_k        must be 1
+ *   layers       host array of num_layers descriptors
+ *   y            [B, 1, 1, n_out] (or [B, h', w', c'] if the last layer is a convolution);
+ *                y->q is ignored: row b carries its expert's last-layer parameters
+ *   expert_index optional device out [B]; expert_counts optional device out [num_experts]
+ *                (the c_i of the paper's load-balancing term)
+ */
+mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype logits_dtype,
+                           int32_t num_experts, int32_t top_k,
+                           const mpq_moe_layer *layers, int32_t num_layers,
+                           mpq_tensor *y, int32_t *expert_index, int32_t *expert_counts,
+                           void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPQ_H */

@@ -1,0 +1,197 @@
+"""ctypes binding of libmpq.so: the same entry points as include/mpq.h, argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch appears here only as the owner of
+device memory and streams.  Loading fails loudly if the library has not been built.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmpq.so")
+
+INT8, INT16, FP16, FP32, INT32 = 0, 1, 2, 3, 4
+DTYPE_ID = {"int8": INT8, "int16": INT16, "fp16": FP16, "fp32": FP32, "int32": INT32}
+TORCH_DTYPE = {INT8: torch.int8, INT16: torch.int16, FP16: torch.float16, FP32: torch.float32,
+               INT32: torch.int32}
+STATUS = {0: "ok", 1: "invalid argument", 2: "shape mismatch", 3: "unsupported",
+          4: "workspace too small or misaligned", 5: "device error"}
+
+EXPORTS = ["mpq_status_string", "mpq_abi_version", "mpq_quantize", "mpq_dequantize", "mpq_to_fp16",
+           "mpq_from_fp16", "mpq_scale_quant_vals", "mpq_packed_weight_bytes", "mpq_pack_weights",
+           "mpq_conv2d_workspace_bytes", "mpq_conv2d", "mpq_gemm_desc", "mpq_gemm_workspace_bytes",
+           "mpq_gemm", "mpq_maxpool2d", "mpq_moe_workspace_bytes", "mpq_moe_forward"]
+
+
+class QParams(C.Structure):
+    _fields_ = [("scale", C.c_float), ("zero_point", C.c_int32)]
+
+
+class Tensor(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("dtype", C.c_int32), ("n", C.c_int32), ("h", C.c_int32),
+                ("w", C.c_int32), ("c", C.c_int32), ("q", QParams)]
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [("c", C.c_int32), ("k", C.c_int32), ("r", C.c_int32), ("s", C.c_int32),
+                ("stride_h", C.c_int32), ("stride_w", C.c_int32), ("pad_h", C.c_int32),
+                ("pad_w", C.c_int32), ("groups", C.c_int32), ("relu", C.c_int32),
+                ("pool_k", C.c_int32), ("pool_s", C.c_int32)]
+
+
+class MoeLayer(C.Structure):
+    _fields_ = [("desc", ConvDesc), ("is_fc", C.c_int32), ("w_packed", C.c_void_p),
+                ("w_stride", C.c_size_t), ("bias", C.c_void_p), ("w_q", C.POINTER(QParams)),
+                ("y_q", C.POINTER(QParams))]
+
+
+class MpqError(RuntimeError):
+    def __init__(self, status, where):
+        super().__init__(f"{where}: {STATUS.get(status, status)} (status {status})")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library.  There is no fallback: a missing build is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        vp, sz, i32 = C.c_void_p, C.c_size_t, C.c_int32
+        TP, DP = C.POINTER(Tensor), C.POINTER(ConvDesc)
+        L.mpq_status_string.restype = C.c_char_p
+        L.mpq_status_string.argtypes = [C.c_int]
+        L.mpq_abi_version.restype = i32
+        L.mpq_quantize.argtypes = [vp, vp, sz, C.c_int, QParams, vp]
+        L.mpq_dequantize.argtypes = [vp, vp, sz, C.c_int, QParams, vp]
+        L.mpq_to_fp16.argtypes = [vp, vp, sz, vp]
+        L.mpq_from_fp16.argtypes = [vp, vp, sz, vp]
+        L.mpq_scale_quant_vals.argtypes = [C.c_float, C.c_float, C.c_float, C.c_int,
+                                           C.POINTER(C.c_int64), C.POINTER(i32)]
+        L.mpq_packed_weight_bytes.restype = sz
+        L.mpq_packed_weight_bytes.argtypes = [DP, C.c_int]
+        L.mpq_pack_weights.argtypes = [vp, DP, C.c_int, vp, sz, vp]
+        L.mpq_conv2d_workspace_bytes.restype = sz
+        L.mpq_conv2d_workspace_bytes.argtypes = [TP, DP]
+        L.mpq_conv2d.argtypes = [TP, vp, QParams, vp, TP, DP, vp, sz, vp]
+        L.mpq_gemm_desc.restype = ConvDesc
+        L.mpq_gemm_desc.argtypes = [i32, i32, i32]
+        L.mpq_gemm_workspace_bytes.restype = sz
+        L.mpq_gemm_workspace_bytes.argtypes = [TP, i32]
+        L.mpq_gemm.argtypes = [TP, vp, QParams, vp, TP, i32, vp, sz, vp]
+        L.mpq_maxpool2d.argtypes = [TP, TP, i32, i32, vp]
+        L.mpq_moe_workspace_bytes.restype = sz
+        L.mpq_moe_workspace_bytes.argtypes = [TP, i32, C.POINTER(MoeLayer), i32]
+        L.mpq_moe_forward.argtypes = [TP, vp, C.c_int, i32, i32, C.POINTER(MoeLayer), i32, TP, vp, vp,
+                                      vp, sz, vp]
+        for name in EXPORTS:
+            getattr(L, name)
+        _lib = L
+    return _lib
+
+
+def _check(status, where):
+    if status != 0:
+        raise MpqError(status, where)
+
+
+def _stream(stream):
+    if stream is not None:
+        return C.c_void_p(stream)
+    if not torch.cuda.is_available():      # host-only argument checks: nothing will be launched
+        return C.c_void_p(0)
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    return C.c_void_p(t.data_ptr()) if isinstance(t, torch.Tensor) else C.c_void_p(int(t))
+
+
+def tensor(t, dtype, n, h, w, c, scale=1.0, zero_point=0):
+    """Non-owning NHWC view of a torch tensor (or a raw device address)."""
+    return Tensor(_ptr(t), dtype, n, h, w, c, QParams(float(scale), int(zero_point)))
+
+
+def conv_desc(c, k, r, s, stride=1, pad=0, groups=1, relu=False, pool_k=0, pool_s=0):
+    return ConvDesc(c, k, r, s, stride, stride, pad, pad, groups, int(bool(relu)), pool_k, pool_s)
+
+
+def gemm_desc(k_in, n_out, relu=False):
+    return lib().mpq_gemm_desc(k_in, n_out, int(bool(relu)))
+
+
+# ---- one function per C entry point --------------------------------------------------------
+def mpq_quantize(src, dst, count, dtype, scale, zero_point=0, stream=None):
+    _check(lib().mpq_quantize(_ptr(src), _ptr(dst), count, dtype, QParams(float(scale), int(zero_point)),
+                              _stream(stream)), "mpq_quantize")
+
+
+def mpq_dequantize(src, dst, count, dtype, scale, zero_point=0, stream=None):
+    _check(lib().mpq_dequantize(_ptr(src), _ptr(dst), count, dtype, QParams(float(scale), int(zero_point)),
+                                _stream(stream)), "mpq_dequantize")
+
+
+def mpq_to_fp16(src, dst, count, stream=None):
+    _check(lib().mpq_to_fp16(_ptr(src), _ptr(dst), count, _stream(stream)), "mpq_to_fp16")
+
+
+def mpq_from_fp16(src, dst, count, stream=None):
+    _check(lib().mpq_from_fp16(_ptr(src), _ptr(dst), count, _stream(stream)), "mpq_from_fp16")
+
+
+def mpq_scale_quant_vals(s_x, s_w, s_y, dtype):
+    m, h = C.c_int64(), C.c_int32()
+    _check(lib().mpq_scale_quant_vals(s_x, s_w, s_y, dtype, C.byref(m), C.byref(h)), "mpq_scale_quant_vals")
+    return m.value, h.value
+
+
+def mpq_packed_weight_bytes(desc, dtype):
+    return int(lib().mpq_packed_weight_bytes(C.byref(desc), dtype))
+
+
+def mpq_pack_weights(w_kcrs, desc, dtype, packed, packed_bytes, stream=None):
+    _check(lib().mpq_pack_weights(_ptr(w_kcrs), C.byref(desc), dtype, _ptr(packed), packed_bytes,
+                                  _stream(stream)), "mpq_pack_weights")
+
+
+def mpq_conv2d_workspace_bytes(x, desc):
+    return int(lib().mpq_conv2d_workspace_bytes(C.byref(x), C.byref(desc)))
+
+
+def mpq_conv2d(x, w_packed, w_scale, w_zero, bias, y, desc, ws=None, ws_bytes=0, stream=None):
+    _check(lib().mpq_conv2d(C.byref(x), _ptr(w_packed), QParams(float(w_scale), int(w_zero)), _ptr(bias),
+                            C.byref(y), C.byref(desc), _ptr(ws), ws_bytes, _stream(stream)), "mpq_conv2d")
+
+
+def mpq_gemm_workspace_bytes(x, n_out):
+    return int(lib().mpq_gemm_workspace_bytes(C.byref(x), n_out))
+
+
+def mpq_gemm(x, w_packed, w_scale, w_zero, bias, y, relu, ws=None, ws_bytes=0, stream=None):
+    _check(lib().mpq_gemm(C.byref(x), _ptr(w_packed), QParams(float(w_scale), int(w_zero)), _ptr(bias),
+                          C.byref(y), int(bool(relu)), _ptr(ws), ws_bytes, _stream(stream)), "mpq_gemm")
+
+
+def mpq_maxpool2d(x, y, k, s, stream=None):
+    _check(lib().mpq_maxpool2d(C.byref(x), C.byref(y), k, s, _stream(stream)), "mpq_maxpool2d")
+
+
+def mpq_moe_workspace_bytes(x, num_experts, layers):
+    arr = (MoeLayer * len(layers))(*layers)
+    return int(lib().mpq_moe_workspace_bytes(C.byref(x), num_experts, arr, len(layers)))
+
+
+def mpq_moe_forward(x, logits, logits_dtype, num_experts, top_k, layers, y, expert_index=None,
+                    expert_counts=None, ws=None, ws_bytes=0, stream=None):
+    arr = (MoeLayer * len(layers))(*layers)
+    _check(lib().mpq_moe_forward(C.byref(x), _ptr(logits), logits_dtype, num_experts, top_k, arr,
+                                 len(layers), C.byref(y), _ptr(expert_index), _ptr(expert_counts),
+                                 _ptr(ws), ws_bytes, _stream(stream)), "mpq_moe_forward")

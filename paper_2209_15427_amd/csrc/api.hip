@@ -1,0 +1,587 @@
+// C-ABI entry points of libmpq: argument validation, host-side planning (packed layout, kernel
+// choice, rescale constants) and kernel launches.  No allocation, no synchronisation.
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+namespace mpq {
+
+// ---------------------------------------------------------------------------------------------
+// planning
+// ---------------------------------------------------------------------------------------------
+Plan make_plan(const mpq_conv_desc &d, int dtype, int in_w) {
+    Plan p;
+    std::memset(&p, 0, sizeof(p));
+    p.esize = dtype_size(dtype);
+    p.Cg = d.c / d.groups;
+    p.Kg = d.k / d.groups;
+    p.Kdim = d.r * d.s * p.Cg;
+    const int chunk_elems = kChunkBytes / p.esize;
+    long long packed_len;
+    if ((p.Cg * p.esize) % kChunkBytes == 0) {
+        p.mode = kModeTap;
+        p.row_pitch = d.s * p.Cg;
+        p.s_pitch = p.Cg;
+        p.taps = d.r * d.s;
+        p.tap_elems = p.Cg;
+        packed_len = p.Kdim;
+    } else if (d.groups == 1 && d.c <= 4 && d.pad_w == 0 && d.pad_h == 0 && d.s * 4 >= chunk_elems &&
+               (d.stride_w * 4 * p.esize) % kChunkBytes == 0 && dtype != MPQ_INT16) {
+        // first-layer shape: a kernel row (s, c) becomes one contiguous run of a 4-channel copy
+        p.mode = kModeRow;
+        p.Cpad = 4;
+        p.tap_elems = (int)round_up((size_t)d.s * 4, chunk_elems);
+        p.row_pitch = p.tap_elems;
+        p.s_pitch = 4;
+        p.taps = d.r;
+        packed_len = (long long)d.r * p.tap_elems;
+        if (in_w > 0) {
+            int Q = (in_w - d.s) / d.stride_w + 1;
+            int need = (Q - 1) * d.stride_w + p.tap_elems / 4;
+            if (need < in_w) need = in_w;
+            p.Wp = (int)round_up((size_t)need, 4);
+        }
+    } else {
+        p.mode = kModeGeneric;
+        p.row_pitch = d.s * p.Cg;
+        p.s_pitch = p.Cg;
+        p.taps = d.r * d.s;
+        p.tap_elems = p.Cg;
+        packed_len = p.Kdim;
+    }
+    p.Kp = (int)(round_up((size_t)packed_len * p.esize, kStepBytes) / p.esize);
+    p.wsum_off = round_up((size_t)d.k * p.Kp * p.esize, 256);
+    p.total = p.wsum_off + round_up((size_t)d.k * 4, 256);
+    return p;
+}
+
+namespace {
+
+bool finite_pos(float v) { return std::isfinite(v) && v > 0.f; }
+
+bool is_int_storage(int dt) { return dt == MPQ_INT8 || dt == MPQ_INT16; }
+
+void storage_range(int dt, int *lo, int *hi) {
+    if (dt == MPQ_INT8) { *lo = -128; *hi = 127; }
+    else { *lo = -32768; *hi = 32767; }
+}
+
+bool qparams_ok(int dt, const mpq_qparams &q) {
+    if (!is_int_storage(dt)) return true;
+    int lo, hi;
+    storage_range(dt, &lo, &hi);
+    return finite_pos(q.scale) && q.zero_point >= lo && q.zero_point <= hi;
+}
+
+bool desc_ok(const mpq_conv_desc &d) {
+    if (d.c < 1 || d.k < 1 || d.r < 1 || d.s < 1) return false;
+    if (d.stride_h < 1 || d.stride_w < 1 || d.pad_h < 0 || d.pad_w < 0) return false;
+    if (d.groups < 1 || d.c % d.groups != 0 || d.k % d.groups != 0) return false;
+    if (d.pool_k < 0 || (d.pool_k > 0 && d.pool_s < 1)) return false;
+    if ((long long)d.r * d.s * (d.c / d.groups) > (1ll << 28)) return false;
+    return true;
+}
+
+// M = s_x s_w / s_y = M0 2^e, M0 in [0.5, 1): mult = round(M0 2^sb), shift = -e
+// (section "Quantized Operations", (x m) >> h; sb from the launch-code listing's shift_bits).
+mpq_status rescale_constants(float s_x, float s_w, float s_y, int dtype, long long *mult, int *shift) {
+    if (!finite_pos(s_x) || !finite_pos(s_w) || !finite_pos(s_y)) return MPQ_ERR_INVALID_ARG;
+    const int sb = dtype == MPQ_INT8 ? 31 : 15;
+    const double ratio = ((double)s_x * (double)s_w) / (double)s_y;
+    if (!(ratio > 0.0) || !std::isfinite(ratio)) return MPQ_ERR_INVALID_ARG;
+    int e = 0;
+    const double m0 = std::frexp(ratio, &e);
+    long long m = std::llrint(std::ldexp(m0, sb));
+    if (m == (1ll << sb)) {
+        m >>= 1;
+        e += 1;
+    }
+    if (-e < -15) return MPQ_ERR_UNSUPPORTED;   // ratio >= 2^15: the left shift would leave the accumulator
+    *mult = m;
+    *shift = -e > 62 ? 62 : -e;
+    return MPQ_OK;
+}
+
+mpq_status build_epi(int in_dtype, int out_dtype, const mpq_qparams &xq, const mpq_qparams &wq,
+                     const mpq_qparams &yq, int relu, Epi *e) {
+    std::memset(e, 0, sizeof(*e));
+    e->relu = relu ? 1 : 0;
+    if (in_dtype == MPQ_FP16) {
+        e->kind = out_dtype == MPQ_FP32 ? kEpiRawF32 : kEpiHalf;
+        return MPQ_OK;
+    }
+    e->zx = xq.zero_point;
+    e->zw = wq.zero_point;
+    e->sb = in_dtype == MPQ_INT8 ? 31 : 15;
+    if (out_dtype == MPQ_INT32) {
+        e->kind = kEpiRawI32;
+        return MPQ_OK;
+    }
+    e->kind = kEpiRequant;
+    mpq_status s = rescale_constants(xq.scale, wq.scale, yq.scale, in_dtype, &e->mult, &e->shift);
+    if (s != MPQ_OK) return s;
+    int lo, hi;
+    storage_range(out_dtype, &lo, &hi);
+    e->zy = yq.zero_point;
+    e->hi = hi;
+    e->lo = (relu && yq.zero_point > lo) ? yq.zero_point : lo;
+    return MPQ_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) % 16) == 0; }
+
+struct Geometry {
+    int P, Q;      // convolution output
+    int Po, Qo;    // after pooling
+};
+
+mpq_status geometry(const mpq_tensor &x, const mpq_conv_desc &d, Geometry *g) {
+    long long P = ((long long)x.h + 2ll * d.pad_h - d.r);
+    long long Q = ((long long)x.w + 2ll * d.pad_w - d.s);
+    if (P < 0 || Q < 0) return MPQ_ERR_SHAPE;
+    g->P = (int)(P / d.stride_h + 1);
+    g->Q = (int)(Q / d.stride_w + 1);
+    g->Po = g->P;
+    g->Qo = g->Q;
+    if (d.pool_k > 0) {
+        if (g->P < d.pool_k || g->Q < d.pool_k) return MPQ_ERR_SHAPE;
+        g->Po = (g->P - d.pool_k) / d.pool_s + 1;
+        g->Qo = (g->Q - d.pool_k) / d.pool_s + 1;
+    }
+    return MPQ_OK;
+}
+
+struct WsLayout {
+    size_t pad_off, pad_bytes;    // channel-padded copy of the input (row mode)
+    size_t mid_off, mid_bytes;    // unpooled convolution output
+    size_t total;
+};
+
+WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, const Geometry &g,
+                   int out_dtype) {
+    WsLayout w;
+    std::memset(&w, 0, sizeof(w));
+    size_t off = 0;
+    if (pl.mode == kModeRow) {
+        w.pad_off = off;
+        w.pad_bytes = round_up((size_t)x.n * x.h * pl.Wp * pl.Cpad * pl.esize, 256);
+        off += w.pad_bytes;
+    }
+    if (d.pool_k > 0) {
+        w.mid_off = off;
+        w.mid_bytes = round_up((size_t)x.n * g.P * g.Q * d.k * dtype_size(out_dtype), 256);
+        off += w.mid_bytes;
+    }
+    w.total = off;
+    return w;
+}
+
+// Everything mpq_conv2d and the MoE layer loop need to launch one convolution.
+mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias, void *y_data,
+                    int y_dtype, const mpq_conv_desc &d, const Epi &epi, const SegTable *seg,
+                    void *ws, size_t ws_bytes, hipStream_t st) {
+    Geometry g;
+    mpq_status s = geometry(x, d, &g);
+    if (s != MPQ_OK) return s;
+    Plan pl = make_plan(d, x.dtype, x.w);
+    WsLayout wl = ws_layout(x, d, pl, g, y_dtype);
+    if (wl.total > 0 && (ws == nullptr || ws_bytes < wl.total || !aligned16(ws))) return MPQ_ERR_WORKSPACE;
+    if ((long long)x.n * g.P * g.Q > 0x7ffffc00ll) return MPQ_ERR_UNSUPPORTED;
+
+    ConvArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.x = x.data;
+    a.w = w_packed;
+    a.bias = bias;
+    a.N = x.n; a.H = x.h; a.W = x.w; a.C = x.c;
+    a.K = d.k; a.R = d.r; a.S = d.s;
+    a.P = g.P; a.Q = g.Q;
+    a.stride_h = d.stride_h; a.stride_w = d.stride_w; a.pad_h = d.pad_h; a.pad_w = d.pad_w;
+    a.groups = d.groups;
+    a.in_dtype = x.dtype;
+    a.out_dtype = y_dtype;
+    a.plan = pl;
+    a.epi = epi;
+    if (seg) a.seg = *seg;
+    char *wsb = reinterpret_cast<char *>(ws);
+    void *conv_out = d.pool_k > 0 ? (void *)(wsb + wl.mid_off) : y_data;
+    a.y = conv_out;
+
+    // kernel choice
+    const bool mfma_type = x.dtype == MPQ_INT8 || x.dtype == MPQ_FP16;
+    bool zw_ok = (x.dtype == MPQ_FP16) || epi.zw == 0;
+    if (seg)
+        for (int e = 0; e < seg->num_experts; ++e) zw_ok = zw_ok && (x.dtype == MPQ_FP16 || seg->epi[e].zw == 0);
+    bool use_mfma = mfma_type && zw_ok && pl.mode != kModeGeneric && (pl.Kg % 4 == 0) && aligned16(x.data) &&
+                    aligned16(w_packed) && aligned16(conv_out) && (bias == nullptr || aligned16(bias)) &&
+                    ((size_t)d.k * dtype_size(y_dtype)) % 4 == 0;
+    if (pl.mode == kModeTap) use_mfma = use_mfma && ((size_t)x.c * pl.esize) % kChunkBytes == 0;
+    if (seg && seg->w_stride % 256 != 0) use_mfma = false;
+
+    hipError_t err = hipSuccess;
+    if (use_mfma) {
+        a.ksteps = (int)((size_t)pl.Kp * pl.esize / kStepBytes);
+        a.cpt = pl.tap_elems * pl.esize / kChunkBytes;
+        a.nchunks = pl.taps * a.cpt;
+        unsigned zb = (unsigned)(epi.zx & 0xff);
+        a.fill_word = x.dtype == MPQ_INT8 ? zb * 0x01010101u : 0u;
+        if (pl.mode == kModeRow) {
+            void *xp = wsb + wl.pad_off;
+            err = launch_pad_channels(x.data, xp, x.n, x.h, x.w, x.c, pl.Wp, pl.Cpad, pl.esize,
+                                      x.dtype == MPQ_INT8 ? epi.zx : 0, st);
+            if (err != hipSuccess) return MPQ_ERR_DEVICE;
+            a.x = xp;
+            a.W = pl.Wp;
+            a.C = pl.Cpad;
+            a.s_eff = 1;
+            a.tap_px = pl.tap_elems / pl.Cpad;
+        } else {
+            a.s_eff = d.s;
+            a.tap_px = 1;
+        }
+        err = launch_conv_mfma(a, st);
+    } else if (!seg && gemv_eligible(a)) {
+        err = launch_gemv(a, st);
+    } else {
+        err = launch_conv_generic(a, st);
+    }
+    if (err != hipSuccess) return MPQ_ERR_DEVICE;
+    if (d.pool_k > 0) {
+        err = launch_maxpool(conv_out, y_data, x.n, g.P, g.Q, d.k, d.pool_k, d.pool_s, y_dtype, st);
+        if (err != hipSuccess) return MPQ_ERR_DEVICE;
+    }
+    return MPQ_OK;
+}
+
+mpq_status check_conv_args(const mpq_tensor *x, const void *w_packed, const mpq_qparams &w_q,
+                           const mpq_tensor *y, const mpq_conv_desc *d, Geometry *g) {
+    if (!x || !y || !d || !w_packed) return MPQ_ERR_INVALID_ARG;
+    if (x->dtype != MPQ_INT8 && x->dtype != MPQ_INT16 && x->dtype != MPQ_FP16) return MPQ_ERR_INVALID_ARG;
+    const bool integer = is_int_storage(x->dtype);
+    if (integer) {
+        if (y->dtype != x->dtype && y->dtype != MPQ_INT32) return MPQ_ERR_UNSUPPORTED;
+    } else {
+        if (y->dtype != MPQ_FP16 && y->dtype != MPQ_FP32) return MPQ_ERR_UNSUPPORTED;
+    }
+    if (!desc_ok(*d)) return MPQ_ERR_INVALID_ARG;
+    if (x->n < 0 || x->h < 1 || x->w < 1 || x->c < 1) return MPQ_ERR_SHAPE;
+    if (x->c != d->c) return MPQ_ERR_SHAPE;
+    if (!qparams_ok(x->dtype, x->q) || !qparams_ok(x->dtype, w_q)) return MPQ_ERR_INVALID_ARG;
+    if (integer && y->dtype == x->dtype && !qparams_ok(y->dtype, y->q)) return MPQ_ERR_INVALID_ARG;
+    if (d->pool_k > 0 && (y->dtype == MPQ_INT32 || y->dtype == MPQ_FP32)) return MPQ_ERR_UNSUPPORTED;
+    mpq_status s = geometry(*x, *d, g);
+    if (s != MPQ_OK) return s;
+    if (y->n != x->n || y->h != g->Po || y->w != g->Qo || y->c != d->k) return MPQ_ERR_SHAPE;
+    if (x->n > 0 && (!x->data || !y->data)) return MPQ_ERR_INVALID_ARG;
+    if (x->data && x->data == y->data) return MPQ_ERR_INVALID_ARG;
+    return MPQ_OK;
+}
+
+}  // namespace
+
+bool mfma_eligible(const Plan &, const mpq_conv_desc &, int, const Epi &, int) { return false; }
+
+}  // namespace mpq
+
+using namespace mpq;
+
+extern "C" {
+
+const char *mpq_status_string(mpq_status s) {
+    switch (s) {
+        case MPQ_OK: return "ok";
+        case MPQ_ERR_INVALID_ARG: return "invalid argument";
+        case MPQ_ERR_SHAPE: return "shape mismatch";
+        case MPQ_ERR_UNSUPPORTED: return "unsupported";
+        case MPQ_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case MPQ_ERR_DEVICE: return "device error";
+        default: return "unknown status";
+    }
+}
+
+int32_t mpq_abi_version(void) { return 1; }
+
+mpq_status mpq_quantize(const float *src, void *dst, size_t count, mpq_dtype dtype, mpq_qparams q,
+                        void *stream) {
+    if (dtype != MPQ_INT8 && dtype != MPQ_INT16 && dtype != MPQ_INT32) return MPQ_ERR_INVALID_ARG;
+    if (!finite_pos(q.scale)) return MPQ_ERR_INVALID_ARG;
+    if (dtype != MPQ_INT32 && !qparams_ok(dtype, q)) return MPQ_ERR_INVALID_ARG;
+    if (count == 0) return MPQ_OK;
+    if (!src || !dst) return MPQ_ERR_INVALID_ARG;
+    return launch_quantize(src, dst, count, dtype, q.scale, q.zero_point, (hipStream_t)stream) == hipSuccess
+               ? MPQ_OK : MPQ_ERR_DEVICE;
+}
+
+mpq_status mpq_dequantize(const void *src, float *dst, size_t count, mpq_dtype dtype, mpq_qparams q,
+                          void *stream) {
+    if (dtype != MPQ_INT8 && dtype != MPQ_INT16 && dtype != MPQ_INT32) return MPQ_ERR_INVALID_ARG;
+    if (!finite_pos(q.scale)) return MPQ_ERR_INVALID_ARG;
+    if (dtype != MPQ_INT32 && !qparams_ok(dtype, q)) return MPQ_ERR_INVALID_ARG;
+    if (count == 0) return MPQ_OK;
+    if (!src || !dst) return MPQ_ERR_INVALID_ARG;
+    return launch_dequantize(src, dst, count, dtype, q.scale, q.zero_point, (hipStream_t)stream) == hipSuccess
+               ? MPQ_OK : MPQ_ERR_DEVICE;
+}
+
+mpq_status mpq_to_fp16(const float *src, void *dst, size_t count, void *stream) {
+    if (count == 0) return MPQ_OK;
+    if (!src || !dst) return MPQ_ERR_INVALID_ARG;
+    return launch_to_fp16(src, dst, count, (hipStream_t)stream) == hipSuccess ? MPQ_OK : MPQ_ERR_DEVICE;
+}
+
+mpq_status mpq_from_fp16(const void *src, float *dst, size_t count, void *stream) {
+    if (count == 0) return MPQ_OK;
+    if (!src || !dst) return MPQ_ERR_INVALID_ARG;
+    return launch_from_fp16(src, dst, count, (hipStream_t)stream) == hipSuccess ? MPQ_OK : MPQ_ERR_DEVICE;
+}
+
+mpq_status mpq_scale_quant_vals(float s_x, float s_w, float s_y, mpq_dtype dtype, int64_t *mult,
+                                int32_t *shift) {
+    if (!mult || !shift || !is_int_storage(dtype)) return MPQ_ERR_INVALID_ARG;
+    long long m = 0;
+    int h = 0;
+    mpq_status s = rescale_constants(s_x, s_w, s_y, dtype, &m, &h);
+    if (s != MPQ_OK) return s;
+    *mult = m;
+    *shift = h;
+    return MPQ_OK;
+}
+
+size_t mpq_packed_weight_bytes(const mpq_conv_desc *d, mpq_dtype dtype) {
+    if (!d || !desc_ok(*d)) return 0;
+    if (dtype != MPQ_INT8 && dtype != MPQ_INT16 && dtype != MPQ_FP16) return 0;
+    return make_plan(*d, dtype, 0).total;
+}
+
+mpq_status mpq_pack_weights(const void *w_kcrs, const mpq_conv_desc *d, mpq_dtype dtype, void *packed,
+                            size_t packed_bytes, void *stream) {
+    if (!w_kcrs || !d || !packed) return MPQ_ERR_INVALID_ARG;
+    if (dtype != MPQ_INT8 && dtype != MPQ_INT16 && dtype != MPQ_FP16) return MPQ_ERR_INVALID_ARG;
+    if (!desc_ok(*d)) return MPQ_ERR_INVALID_ARG;
+    Plan p = make_plan(*d, dtype, 0);
+    if (packed_bytes < p.total) return MPQ_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(packed) % 256 != 0) return MPQ_ERR_WORKSPACE;
+    return launch_pack(w_kcrs, packed, *d, p, dtype, (hipStream_t)stream) == hipSuccess ? MPQ_OK : MPQ_ERR_DEVICE;
+}
+
+size_t mpq_conv2d_workspace_bytes(const mpq_tensor *x, const mpq_conv_desc *d) {
+    if (!x || !d || !desc_ok(*d) || x->c != d->c || x->n < 0 || x->h < 1 || x->w < 1) return 0;
+    Geometry g;
+    if (geometry(*x, *d, &g) != MPQ_OK) return 0;
+    Plan pl = make_plan(*d, x->dtype, x->w);
+    return ws_layout(*x, *d, pl, g, x->dtype).total;
+}
+
+mpq_status mpq_conv2d(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q, const void *bias,
+                      mpq_tensor *y, const mpq_conv_desc *d, void *ws, size_t ws_bytes, void *stream) {
+    Geometry g;
+    mpq_status s = check_conv_args(x, w_packed, w_q, y, d, &g);
+    if (s != MPQ_OK) return s;
+    Epi epi;
+    s = build_epi(x->dtype, y->dtype, x->q, w_q, y->q, d->relu, &epi);
+    if (s != MPQ_OK) return s;
+    if (x->n == 0) return MPQ_OK;
+    return run_conv(*x, w_packed, bias, y->data, y->dtype, *d, epi, nullptr, ws, ws_bytes, (hipStream_t)stream);
+}
+
+mpq_conv_desc mpq_gemm_desc(int32_t k_in, int32_t n_out, int32_t relu) {
+    mpq_conv_desc d;
+    std::memset(&d, 0, sizeof(d));
+    d.c = k_in;
+    d.k = n_out;
+    d.r = d.s = 1;
+    d.stride_h = d.stride_w = 1;
+    d.groups = 1;
+    d.relu = relu;
+    return d;
+}
+
+size_t mpq_gemm_workspace_bytes(const mpq_tensor *x, int32_t n_out) {
+    (void)x;
+    (void)n_out;
+    return 0;
+}
+
+mpq_status mpq_gemm(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q, const void *bias,
+                    mpq_tensor *y, int32_t relu, void *ws, size_t ws_bytes, void *stream) {
+    if (!x || !y) return MPQ_ERR_INVALID_ARG;
+    if (x->h != 1 || x->w != 1 || y->h != 1 || y->w != 1) return MPQ_ERR_SHAPE;
+    if (x->c < 1 || y->c < 1) return MPQ_ERR_SHAPE;
+    mpq_conv_desc d = mpq_gemm_desc(x->c, y->c, relu);
+    return mpq_conv2d(x, w_packed, w_q, bias, y, &d, ws, ws_bytes, stream);
+}
+
+mpq_status mpq_maxpool2d(const mpq_tensor *x, mpq_tensor *y, int32_t k, int32_t s, void *stream) {
+    if (!x || !y) return MPQ_ERR_INVALID_ARG;
+    if (x->dtype != MPQ_INT8 && x->dtype != MPQ_INT16 && x->dtype != MPQ_FP16) return MPQ_ERR_INVALID_ARG;
+    if (y->dtype != x->dtype) return MPQ_ERR_UNSUPPORTED;
+    if (k < 1 || s < 1) return MPQ_ERR_INVALID_ARG;
+    if (x->n < 0 || x->h < k || x->w < k || x->c < 1) return MPQ_ERR_SHAPE;
+    int P = (x->h - k) / s + 1, Q = (x->w - k) / s + 1;
+    if (y->n != x->n || y->h != P || y->w != Q || y->c != x->c) return MPQ_ERR_SHAPE;
+    if (x->n == 0) return MPQ_OK;
+    if (!x->data || !y->data || x->data == y->data) return MPQ_ERR_INVALID_ARG;
+    return launch_maxpool(x->data, y->data, x->n, x->h, x->w, x->c, k, s, x->dtype, (hipStream_t)stream) == hipSuccess
+               ? MPQ_OK : MPQ_ERR_DEVICE;
+}
+
+// ---------------------------------------------------------------------------------------------
+// mixture of experts
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+struct MoeShapes {
+    // activation shape entering layer i (per sample) and leaving it
+    int h[17], w[17], c[17];
+};
+
+struct MoeWs {
+    size_t expert_off, counts_off, offsets_off, perm_off;   // int arrays
+    size_t buf_off[2];                                      // ping-pong activations (gathered order)
+    size_t buf_bytes;
+    size_t layer_ws_off, layer_ws_bytes;
+    size_t total;
+};
+
+mpq_status moe_plan(const mpq_tensor &x, int E, const mpq_moe_layer *layers, int L, MoeShapes *sh, MoeWs *ws) {
+    if (L < 1 || L > 16 || E < 1 || E > kMaxExperts) return MPQ_ERR_UNSUPPORTED;
+    sh->h[0] = x.h; sh->w[0] = x.w; sh->c[0] = x.c;
+    size_t max_act = (size_t)x.n * x.h * x.w * x.c * dtype_size(x.dtype);
+    size_t max_ws = 0;
+    for (int i = 0; i < L; ++i) {
+        const mpq_moe_layer &ly = layers[i];
+        if (!desc_ok(ly.desc)) return MPQ_ERR_INVALID_ARG;
+        mpq_tensor in;
+        std::memset(&in, 0, sizeof(in));
+        in.dtype = x.dtype;
+        in.n = x.n;
+        if (ly.is_fc) {
+            in.h = in.w = 1;
+            in.c = sh->h[i] * sh->w[i] * sh->c[i];
+        } else {
+            in.h = sh->h[i]; in.w = sh->w[i]; in.c = sh->c[i];
+        }
+        if (in.c != ly.desc.c) return MPQ_ERR_SHAPE;
+        Geometry g;
+        mpq_status s = geometry(in, ly.desc, &g);
+        if (s != MPQ_OK) return s;
+        sh->h[i + 1] = g.Po; sh->w[i + 1] = g.Qo; sh->c[i + 1] = ly.desc.k;
+        size_t act = (size_t)x.n * g.Po * g.Qo * ly.desc.k * dtype_size(x.dtype);
+        if (act > max_act) max_act = act;
+        Plan pl = make_plan(ly.desc, x.dtype, in.w);
+        size_t lw = ws_layout(in, ly.desc, pl, g, x.dtype).total;
+        if (lw > max_ws) max_ws = lw;
+        if (ly.w_stride < pl.total) return MPQ_ERR_WORKSPACE;
+    }
+    size_t off = 0;
+    ws->expert_off = off;  off += round_up((size_t)x.n * 4, 256);
+    ws->counts_off = off;  off += round_up((size_t)E * 4, 256);
+    ws->offsets_off = off; off += round_up((size_t)(E + 1) * 4, 256);
+    ws->perm_off = off;    off += round_up((size_t)x.n * 4, 256);
+    ws->buf_bytes = round_up(max_act, 256);
+    ws->buf_off[0] = off;  off += ws->buf_bytes;
+    ws->buf_off[1] = off;  off += ws->buf_bytes;
+    ws->layer_ws_off = off;
+    ws->layer_ws_bytes = max_ws;
+    off += round_up(max_ws, 256);
+    ws->total = off;
+    return MPQ_OK;
+}
+
+}  // namespace
+
+size_t mpq_moe_workspace_bytes(const mpq_tensor *x, int32_t num_experts, const mpq_moe_layer *layers,
+                               int32_t num_layers) {
+    if (!x || !layers) return 0;
+    MoeShapes sh;
+    MoeWs ws;
+    if (moe_plan(*x, num_experts, layers, num_layers, &sh, &ws) != MPQ_OK) return 0;
+    return ws.total;
+}
+
+mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype logits_dtype,
+                           int32_t num_experts, int32_t top_k, const mpq_moe_layer *layers,
+                           int32_t num_layers, mpq_tensor *y, int32_t *expert_index,
+                           int32_t *expert_counts, void *ws, size_t ws_bytes, void *stream) {
+    if (!x || !y || !layers || !logits) return MPQ_ERR_INVALID_ARG;
+    if (top_k != 1) return MPQ_ERR_UNSUPPORTED;
+    if (logits_dtype != MPQ_INT32 && logits_dtype != MPQ_FP32) return MPQ_ERR_INVALID_ARG;
+    if (x->dtype != MPQ_INT8 && x->dtype != MPQ_INT16 && x->dtype != MPQ_FP16) return MPQ_ERR_INVALID_ARG;
+    if (y->dtype != x->dtype) return MPQ_ERR_UNSUPPORTED;
+    if (x->n < 0 || x->h < 1 || x->w < 1 || x->c < 1) return MPQ_ERR_SHAPE;
+    if (!qparams_ok(x->dtype, x->q)) return MPQ_ERR_INVALID_ARG;
+    MoeShapes sh;
+    MoeWs wl;
+    mpq_status s = moe_plan(*x, num_experts, layers, num_layers, &sh, &wl);
+    if (s != MPQ_OK) return s;
+    const int L = num_layers, E = num_experts, B = x->n;
+    if (y->n != B || (size_t)y->h * y->w * y->c != (size_t)sh.h[L] * sh.w[L] * sh.c[L]) return MPQ_ERR_SHAPE;
+    for (int i = 0; i < L; ++i) {
+        if (!layers[i].w_packed || !layers[i].w_q || !layers[i].y_q) return MPQ_ERR_INVALID_ARG;
+        for (int e = 0; e < E; ++e)
+            if (!qparams_ok(x->dtype, layers[i].w_q[e]) || !qparams_ok(x->dtype, layers[i].y_q[e]))
+                return MPQ_ERR_INVALID_ARG;
+    }
+    // per-layer, per-expert epilogue constants (host, before anything is launched)
+    SegTable segs[16];
+    for (int i = 0; i < L; ++i) {
+        std::memset(&segs[i], 0, sizeof(SegTable));
+        segs[i].num_experts = E;
+        segs[i].bias_stride = layers[i].desc.k;
+        segs[i].w_stride = layers[i].w_stride;
+        for (int e = 0; e < E; ++e) {
+            mpq_qparams xq = i == 0 ? x->q : layers[i - 1].y_q[e];
+            s = build_epi(x->dtype, x->dtype, xq, layers[i].w_q[e], layers[i].y_q[e], layers[i].desc.relu,
+                          &segs[i].epi[e]);
+            if (s != MPQ_OK) return s;
+        }
+    }
+    if (B == 0) return MPQ_OK;
+    if (!x->data || !y->data) return MPQ_ERR_INVALID_ARG;
+    if (!ws || ws_bytes < wl.total || !aligned16(ws)) return MPQ_ERR_WORKSPACE;
+
+    hipStream_t st = (hipStream_t)stream;
+    char *wsb = reinterpret_cast<char *>(ws);
+    int *d_expert = reinterpret_cast<int *>(wsb + wl.expert_off);
+    int *d_counts = reinterpret_cast<int *>(wsb + wl.counts_off);
+    int *d_offsets = reinterpret_cast<int *>(wsb + wl.offsets_off);
+    int *d_perm = reinterpret_cast<int *>(wsb + wl.perm_off);
+    const int es = dtype_size(x->dtype);
+
+    // selection stage: arg-max expert per sample, counts c_i, offsets, stable permutation
+    if (launch_route(logits, logits_dtype, B, E, expert_index ? expert_index : d_expert,
+                     expert_counts ? expert_counts : d_counts, d_offsets, d_perm, st) != hipSuccess)
+        return MPQ_ERR_DEVICE;
+    // gather samples into expert-contiguous order
+    size_t row_in = (size_t)x->h * x->w * x->c * es;
+    if (launch_gather_rows(x->data, wsb + wl.buf_off[0], d_perm, B, row_in, st) != hipSuccess)
+        return MPQ_ERR_DEVICE;
+    int cur = 0;
+    for (int i = 0; i < L; ++i) {
+        const mpq_moe_layer &ly = layers[i];
+        mpq_tensor in;
+        std::memset(&in, 0, sizeof(in));
+        in.data = wsb + wl.buf_off[cur];
+        in.dtype = x->dtype;
+        in.n = B;
+        if (ly.is_fc) {
+            in.h = in.w = 1;
+            in.c = sh.h[i] * sh.w[i] * sh.c[i];
+        } else {
+            in.h = sh.h[i]; in.w = sh.w[i]; in.c = sh.c[i];
+        }
+        segs[i].offsets = d_offsets;
+        s = run_conv(in, ly.w_packed, ly.bias, wsb + wl.buf_off[cur ^ 1], x->dtype, ly.desc, segs[i].epi[0],
+                     &segs[i], wsb + wl.layer_ws_off, wl.layer_ws_bytes, st);
+        if (s != MPQ_OK) return s;
+        cur ^= 1;
+    }
+    // scatter rows back to sample order
+    size_t row_out = (size_t)sh.h[L] * sh.w[L] * sh.c[L] * es;
+    if (launch_scatter_rows(wsb + wl.buf_off[cur], y->data, d_perm, B, row_out, st) != hipSuccess)
+        return MPQ_ERR_DEVICE;
+    return MPQ_OK;
+}
+
+}  // extern "C"

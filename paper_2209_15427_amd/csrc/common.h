@@ -1,0 +1,133 @@
+// Internal declarations shared by the libmpq translation units (host planning + kernel params).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "mpq.h"
+
+namespace mpq {
+
+constexpr int kChunkBytes = 16;   // one lane's global / LDS access; one MFMA operand slice
+constexpr int kStepBytes = 64;    // K extent staged per LDS tile row
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline int dtype_size(int dt) {
+    switch (dt) {
+        case MPQ_INT8: return 1;
+        case MPQ_INT16: return 2;
+        case MPQ_FP16: return 2;
+        case MPQ_FP32: return 4;
+        case MPQ_INT32: return 4;
+        default: return 0;
+    }
+}
+
+// How a layer's weights are laid out after packing, and which kernel family may run it.
+enum PlanMode {
+    kModeGeneric = 0,   // direct convolution, any geometry
+    kModeTap = 1,       // implicit GEMM, one K chunk lies inside one (r, s) tap   (C/groups * esize % 16 == 0)
+    kModeRow = 2,       // implicit GEMM, a whole kernel row (s, c) is one contiguous run of a
+                        // channel-padded copy of the input                       (first layer, C <= 4)
+};
+
+struct Plan {
+    int mode;
+    int esize;        // bytes per element of x / w
+    int Cg, Kg;       // channels per group
+    int row_pitch;    // packed k index = r * row_pitch + s * s_pitch + c
+    int s_pitch;
+    int taps;         // number of contiguous runs per output pixel: R*S (tap) or R (row)
+    int tap_elems;    // elements per run: Cg (tap) or padded S*Cpad (row)
+    int Kdim;         // R * S * Cg, the real reduction length
+    int Kp;           // packed reduction length per output channel (elements), multiple of 64 B
+    int Cpad;         // row mode: channels of the padded input copy
+    int Wp;           // row mode: width of the padded input copy
+    size_t wsum_off;  // byte offset of int32 wsum[K] in the packed blob
+    size_t total;     // packed blob size in bytes (multiple of 256)
+};
+
+// Epilogue selector + constants (per tensor; per expert in the MoE launches).
+enum EpiKind { kEpiRequant = 0, kEpiRawI32 = 1, kEpiHalf = 2, kEpiRawF32 = 3 };
+
+struct Epi {
+    long long mult;
+    int kind;
+    int sb;
+    int shift;
+    int zy;
+    int lo, hi;
+    int zx, zw;
+    int relu;
+    int pad_;
+};
+
+constexpr int kMaxExperts = 16;
+
+// Grouped launch over experts (MoE): rows are samples in expert-contiguous order; expert e owns
+// samples [offsets[e], offsets[e + 1]).  The per-expert epilogue constants travel by value in the
+// kernel arguments, so no host-to-device copy is needed per call.
+struct SegTable {
+    const int *offsets;    // device [E + 1] exclusive sample offsets, or nullptr for a plain launch
+    int num_experts;
+    int bias_stride;       // elements between experts' bias vectors
+    size_t w_stride;       // bytes between experts' packed weights
+    Epi epi[kMaxExperts];
+};
+
+struct ConvArgs {
+    const void *x;
+    const void *w;         // packed
+    const void *bias;
+    void *y;
+    int N, H, W, C;        // input as the kernel sees it (row mode: the padded copy)
+    int K, R, S;
+    int P, Q;              // convolution output size (before pooling)
+    int stride_h, stride_w, pad_h, pad_w, groups;
+    int out_dtype;         // storage dtype of y
+    int in_dtype;
+    // implicit-GEMM view of the reduction axis (filled by the host for the MFMA kernels)
+    int s_eff;             // taps per kernel row as the kernel walks them (S, or 1 in row mode)
+    int cpt;               // 16-byte chunks per tap
+    int nchunks;           // real chunks along the reduction axis (taps * cpt)
+    int ksteps;            // 64-byte steps along the packed reduction axis
+    int tap_px;            // input pixels one tap spans (1, or the padded row length in row mode)
+    int ptiles;            // pixel tiles in the grid (filled by the launcher)
+    unsigned fill_word;    // the input zero-point replicated over 32 bits (out-of-image taps)
+    Plan plan;
+    Epi epi;
+    SegTable seg;
+};
+
+Plan make_plan(const mpq_conv_desc &d, int dtype, int in_w);
+bool mfma_eligible(const Plan &p, const mpq_conv_desc &d, int dtype, const Epi &e, int x_c);
+
+// launchers (each returns the hipError_t of its launch)
+hipError_t launch_quantize(const float *src, void *dst, size_t n, int dtype, float scale, int zp,
+                           hipStream_t st);
+hipError_t launch_dequantize(const void *src, float *dst, size_t n, int dtype, float scale, int zp,
+                             hipStream_t st);
+hipError_t launch_to_fp16(const float *src, void *dst, size_t n, hipStream_t st);
+hipError_t launch_from_fp16(const void *src, float *dst, size_t n, hipStream_t st);
+hipError_t launch_pack(const void *w_kcrs, void *packed, const mpq_conv_desc &d, const Plan &p,
+                       int dtype, hipStream_t st);
+hipError_t launch_pad_channels(const void *x, void *xp, int N, int H, int W, int C, int Wp, int Cpad,
+                               int esize, int fill, hipStream_t st);
+hipError_t launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int k, int s, int dtype,
+                          hipStream_t st);
+hipError_t launch_conv_generic(const ConvArgs &a, hipStream_t st);
+hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
+bool gemv_eligible(const ConvArgs &a);
+hipError_t launch_gemv(const ConvArgs &a, hipStream_t st);
+
+// MoE helpers
+hipError_t launch_route(const void *logits, int logits_dtype, int B, int E, int *expert, int *counts,
+                        int *offsets, int *perm, hipStream_t st);
+hipError_t launch_gather_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes,
+                              hipStream_t st);
+hipError_t launch_scatter_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes,
+                               hipStream_t st);
+
+}  // namespace mpq

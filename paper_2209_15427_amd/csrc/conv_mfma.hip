@@ -1,0 +1,311 @@
+// Implicit-GEMM convolution / fully-connected kernel on the gfx950 matrix cores.
+//
+// Computes the accumulate step  acc[m, k] = sum_j x_patch[m, j] * w[k, j]  of the quantized
+// multiplication in its expanded form (section "Quantized Operations", second equation: the
+// products of the raw codes run on the fast integer path, the zero-point terms are constant per
+// output channel and are folded into the epilogue) and the fused bias + ReLU + requantize
+// epilogue.  int8 x int8 -> int32 uses v_mfma_i32_32x32x32_i8, fp16 x fp16 -> fp32 uses
+// v_mfma_f32_32x32x16_f16; both consume 16 bytes of the reduction axis per lane, so the tiling
+// below is written in bytes and shared by the two types.
+//
+// Tiling: a 256-thread workgroup (4 wavefronts) owns BC output channels x BP output pixels.
+// The reduction axis is walked in 64-byte steps; per step the weight tile (BC rows x 64 B) and
+// the gathered input tile (BP rows x 64 B) are staged in LDS (double buffered, one barrier per
+// step).  Weights are the MFMA "A" operand (rows = channels) and pixels the "B" operand, so a
+// lane's accumulator registers hold 4 consecutive output channels of one pixel: an NHWC store
+// of 4 (int8), 8 (fp16) or 16 (raw) contiguous bytes.
+//
+// LDS rows are 4 chunks of 16 B; chunk c of row r is stored at slot c ^ ((r >> 2) & 3) so that
+// both the 16-byte stores (4 lanes per row) and the fragment reads (32 lanes = 32 rows of one
+// chunk) touch every bank group once.
+#include "common.h"
+#include "epilogue.h"
+
+namespace mpq {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+
+template <typename T> struct Mma;
+template <> struct Mma<int8_t> {
+    typedef v16i Acc;
+    static __device__ __forceinline__ Acc run(v4i a, v4i b, Acc c) {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Mma<_Float16> {
+    typedef v16f Acc;
+    static __device__ __forceinline__ Acc run(v4i a, v4i b, Acc c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c,
+                                                      0, 0, 0);
+    }
+};
+
+constexpr int kThreads = 256;
+
+template <typename T, int BC, int BP, int WGC, int WGP>
+__global__ void __launch_bounds__(kThreads) conv_mfma_kernel(ConvArgs a) {
+    static_assert(WGC * WGP == 4, "four wavefronts per workgroup");
+    constexpr int WTC = BC / WGC, WTP = BP / WGP;   // per-wave tile
+    constexpr int TC = WTC / 32, TP = WTP / 32;     // 32x32 MFMA tiles per wave
+    constexpr int PASS_C = BC / 64, PASS_P = BP / 64;
+    constexpr int ES = (int)sizeof(T);
+    typedef typename Mma<T>::Acc Acc;
+
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2][(BC + BP) * kStepBytes];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wc = wave % WGC, wp = wave / WGC;
+    const Plan &pl = a.plan;
+    const int PQ = a.P * a.Q;
+
+    // ---- which tile -----------------------------------------------------------------------
+    const int ctiles = (pl.Kg + BC - 1) / BC;
+    int bid = blockIdx.x;
+    const int ct = bid % ctiles;
+    bid /= ctiles;
+    int pt = bid % a.ptiles;
+    const int g = bid / a.ptiles;
+
+    int m_begin = 0, m_end = a.N * PQ;
+    const char *wbase = (const char *)a.w;
+    const char *bias = (const char *)a.bias;
+    Epi epi = a.epi;
+    if (a.seg.offsets) {
+        // expert-aligned pixel tiles: expert e owns ceil(rows_e / BP) consecutive tiles
+        int e = 0, tile_base = 0;
+        bool found = false;
+        for (; e < a.seg.num_experts; ++e) {
+            int lo = a.seg.offsets[e], hi = a.seg.offsets[e + 1];
+            int tiles = ((hi - lo) * PQ + BP - 1) / BP;
+            if (pt < tile_base + tiles) {
+                m_begin = lo * PQ;
+                m_end = hi * PQ;
+                pt -= tile_base;
+                found = true;
+                break;
+            }
+            tile_base += tiles;
+        }
+        if (!found) return;   // uniform over the workgroup: taken before any barrier
+        wbase += (size_t)e * a.seg.w_stride;
+        if (bias) bias += (size_t)e * a.seg.bias_stride * 4;
+        epi = a.seg.epi[e];
+    }
+    const int m0 = m_begin + pt * BP;
+    const int ch0 = ct * BC;
+    if (m0 >= m_end) return;
+
+    // ---- per-thread load coordinates --------------------------------------------------------
+    const int lrow = tid >> 2, lchunk = tid & 3;
+    const int slot = (lchunk ^ ((lrow >> 2) & 3)) * kChunkBytes;
+    const int S_eff = a.s_eff, cpt = a.cpt;
+
+    const char *xg = (const char *)a.x;
+    long long xbase[PASS_P];
+    int h0[PASS_P], w0[PASS_P];
+    bool mval[PASS_P];
+#pragma unroll
+    for (int i = 0; i < PASS_P; ++i) {
+        int m = m0 + i * 64 + lrow;
+        mval[i] = m < m_end;
+        int mm = mval[i] ? m : m_begin;
+        int n = mm / PQ, rem = mm % PQ;
+        int p = rem / a.Q, q = rem % a.Q;
+        h0[i] = p * a.stride_h - a.pad_h;
+        w0[i] = q * a.stride_w - a.pad_w;
+        xbase[i] = ((((long long)n * a.H + h0[i]) * a.W + w0[i]) * a.C + (long long)g * pl.Cg) * ES;
+    }
+    const char *wrow[PASS_C];
+    bool cval[PASS_C];
+#pragma unroll
+    for (int i = 0; i < PASS_C; ++i) {
+        int ch = ch0 + i * 64 + lrow;
+        cval[i] = ch < pl.Kg;
+        wrow[i] = wbase + ((size_t)(g * pl.Kg + (cval[i] ? ch : 0)) * pl.Kp) * ES + lchunk * kChunkBytes;
+    }
+
+    int kc = lchunk;              // this thread's chunk index along the reduction axis
+    int cc = kc % cpt;            // chunk within the tap
+    int tap = kc / cpt;
+    int tr = tap / S_eff, ts = tap % S_eff;
+
+    const unsigned fillword = a.fill_word;
+    v4i regW[PASS_C], regX[PASS_P];
+
+    auto fetch = [&](int kt) {
+#pragma unroll
+        for (int i = 0; i < PASS_C; ++i) {
+            v4i v = {0, 0, 0, 0};
+            if (cval[i]) v = *reinterpret_cast<const v4i *>(wrow[i] + (size_t)kt * kStepBytes);
+            regW[i] = v;
+        }
+        const long long tapoff = (((long long)tr * a.W + ts) * a.C) * ES + cc * kChunkBytes;
+        const bool kval = kc < a.nchunks;
+#pragma unroll
+        for (int i = 0; i < PASS_P; ++i) {
+            int h = h0[i] + tr, w = w0[i] + ts;
+            bool ok = mval[i] && kval && h >= 0 && h < a.H && w >= 0 && (w + a.tap_px) <= a.W;
+            v4i v = {(int)fillword, (int)fillword, (int)fillword, (int)fillword};
+            if (!kval) v = v4i{0, 0, 0, 0};
+            if (ok) v = *reinterpret_cast<const v4i *>(xg + xbase[i] + tapoff);
+            regX[i] = v;
+        }
+        kc += 4;
+        cc += 4;
+        while (cc >= cpt) {
+            cc -= cpt;
+            if (++ts == S_eff) {
+                ts = 0;
+                ++tr;
+            }
+        }
+    };
+    auto stage = [&](int buf) {
+        unsigned char *A = lds[buf];
+        unsigned char *B = lds[buf] + BC * kStepBytes;
+#pragma unroll
+        for (int i = 0; i < PASS_C; ++i)
+            *reinterpret_cast<v4i *>(A + (i * 64 + lrow) * kStepBytes + slot) = regW[i];
+#pragma unroll
+        for (int i = 0; i < PASS_P; ++i)
+            *reinterpret_cast<v4i *>(B + (i * 64 + lrow) * kStepBytes + slot) = regX[i];
+    };
+
+    Acc acc[TC][TP];
+#pragma unroll
+    for (int i = 0; i < TC; ++i)
+#pragma unroll
+        for (int j = 0; j < TP; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    const int ksteps = a.ksteps;
+    fetch(0);
+    stage(0);
+    __syncthreads();
+
+    const int frow = lane & 31, fk = lane >> 5;
+    for (int kt = 0; kt < ksteps; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < ksteps) fetch(kt + 1);
+        const unsigned char *A = lds[buf] + (wc * WTC) * kStepBytes;
+        const unsigned char *B = lds[buf] + (BC + wp * WTP) * kStepBytes;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v4i af[TC], bf[TP];
+#pragma unroll
+            for (int i = 0; i < TC; ++i) {
+                int row = i * 32 + frow;
+                int sl = ((ks * 2 + fk) ^ ((row >> 2) & 3)) * kChunkBytes;
+                af[i] = *reinterpret_cast<const v4i *>(A + row * kStepBytes + sl);
+            }
+#pragma unroll
+            for (int j = 0; j < TP; ++j) {
+                int row = j * 32 + frow;
+                int sl = ((ks * 2 + fk) ^ ((row >> 2) & 3)) * kChunkBytes;
+                bf[j] = *reinterpret_cast<const v4i *>(B + row * kStepBytes + sl);
+            }
+#pragma unroll
+            for (int i = 0; i < TC; ++i)
+#pragma unroll
+                for (int j = 0; j < TP; ++j) acc[i][j] = Mma<T>::run(af[i], bf[j], acc[i][j]);
+        }
+        if (kt + 1 < ksteps) stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue -------------------------------------------------------------------------
+    // accumulator register v of lane l in a 32x32 tile: channel 8*(v/4) + 4*(l/32) + v%4, pixel l%32
+    const int *wsum = reinterpret_cast<const int *>(wbase + pl.wsum_off);
+#pragma unroll
+    for (int j = 0; j < TP; ++j) {
+        const int m = m0 + wp * WTP + j * 32 + frow;
+        if (m >= m_end) continue;
+#pragma unroll
+        for (int i = 0; i < TC; ++i) {
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int ch = ch0 + wc * WTC + i * 32 + vq * 8 + fk * 4;
+                if (ch >= pl.Kg) continue;
+                const int kabs = g * pl.Kg + ch;
+                const size_t o = (size_t)m * a.K + kabs;
+                if constexpr (ES == 1) {
+                    v4i b4 = {0, 0, 0, 0};
+                    if (bias) b4 = *reinterpret_cast<const v4i *>(bias + (size_t)kabs * 4);
+                    if (epi.zx != 0) {
+                        v4i s4 = *reinterpret_cast<const v4i *>(wsum + kabs);
+                        b4 -= s4 * epi.zx;
+                    }
+                    int t[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u] + b4[u];
+                    if (epi.kind == kEpiRawI32) {
+                        *reinterpret_cast<v4i *>((int *)a.y + o) = v4i{t[0], t[1], t[2], t[3]};
+                    } else {
+                        unsigned packed = 0;
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            packed |= ((unsigned)requant64((long long)t[u], epi) & 0xffu) << (8 * u);
+                        *reinterpret_cast<unsigned *>((int8_t *)a.y + o) = packed;
+                    }
+                } else {
+                    float b4[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (bias) {
+                        float4 bb = *reinterpret_cast<const float4 *>(bias + (size_t)kabs * 4);
+                        b4[0] = bb.x; b4[1] = bb.y; b4[2] = bb.z; b4[3] = bb.w;
+                    }
+                    float t[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        t[u] = acc[i][j][vq * 4 + u] + b4[u];
+                        if (epi.relu) t[u] = t[u] > 0.f ? t[u] : 0.f;
+                    }
+                    if (epi.kind == kEpiRawF32) {
+                        *reinterpret_cast<float4 *>((float *)a.y + o) = make_float4(t[0], t[1], t[2], t[3]);
+                    } else {
+                        typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+                        v4h hv = {(_Float16)t[0], (_Float16)t[1], (_Float16)t[2], (_Float16)t[3]};
+                        *reinterpret_cast<v4h *>((_Float16 *)a.y + o) = hv;
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <typename T, int BC, int BP, int WGC, int WGP>
+hipError_t launch_one(ConvArgs a, hipStream_t st) {
+    const int PQ = a.P * a.Q;
+    const int ctiles = (a.plan.Kg + BC - 1) / BC;
+    long long rows = (long long)a.N * PQ;
+    int ptiles = (int)((rows + BP - 1) / BP);
+    if (a.seg.offsets) ptiles += a.seg.num_experts;   // upper bound with expert-aligned tiles
+    a.ptiles = ptiles;
+    long long blocks = (long long)ptiles * ctiles * a.groups;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
+    conv_mfma_kernel<T, BC, BP, WGC, WGP><<<(unsigned)blocks, kThreads, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
+    const int Kg = a.plan.Kg;
+    // channel tile: 128 when that wastes no MFMA rows (or the layer is wide and ragged), else 64
+    if (Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0)) return launch_one<T, 128, 128, 2, 2>(a, st);
+    return launch_one<T, 64, 256, 1, 4>(a, st);
+}
+
+}  // namespace
+
+hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st) {
+    if (a.in_dtype == MPQ_INT8) return launch_typed<int8_t>(a, st);
+    return launch_typed<_Float16>(a, st);
+}
+
+}  // namespace mpq

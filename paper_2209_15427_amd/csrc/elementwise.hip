@@ -1,0 +1,296 @@
+// Memory-bound helper kernels: quantizer conversions, fp16 conversion, weight packing,
+// channel padding of the first layer's input, max-pool.
+#include "common.h"
+
+namespace mpq {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+inline int grid_for(size_t work, int threads, int max_blocks = 256 * 32) {
+    size_t b = (work + threads - 1) / threads;
+    if (b < 1) b = 1;
+    if (b > (size_t)max_blocks) b = max_blocks;
+    return (int)b;
+}
+
+// round-half-even of the fp64 quotient, + zero-point, clamped; NaN -> zero-point
+__device__ __forceinline__ int quant_one(float r, double scale, int zp, int lo, int hi) {
+    double v = (double)r;
+    if (v != v) return zp;
+    double t = __builtin_rint(v / scale);
+    t = t > 4.0e9 ? 4.0e9 : (t < -4.0e9 ? -4.0e9 : t);
+    long long o = (long long)t + (long long)zp;
+    o = o < lo ? lo : (o > hi ? hi : o);
+    return (int)o;
+}
+
+template <typename OutT>
+__global__ void __launch_bounds__(kThreads)
+quantize_kernel(const float *__restrict__ src, OutT *__restrict__ dst, size_t n, float scale,
+                int zp, int lo, int hi, int vec_ok) {
+    const double s = (double)scale;
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    size_t n4 = vec_ok ? n / 4 : 0;
+    for (size_t i = tid; i < n4; i += nthreads) {
+        float4 v = reinterpret_cast<const float4 *>(src)[i];
+        OutT o[4];
+        o[0] = (OutT)quant_one(v.x, s, zp, lo, hi);
+        o[1] = (OutT)quant_one(v.y, s, zp, lo, hi);
+        o[2] = (OutT)quant_one(v.z, s, zp, lo, hi);
+        o[3] = (OutT)quant_one(v.w, s, zp, lo, hi);
+        if constexpr (sizeof(OutT) == 1) {
+            reinterpret_cast<uint32_t *>(dst)[i] = *reinterpret_cast<uint32_t *>(o);
+        } else if constexpr (sizeof(OutT) == 2) {
+            reinterpret_cast<uint2 *>(dst)[i] = *reinterpret_cast<uint2 *>(o);
+        } else {
+            reinterpret_cast<uint4 *>(dst)[i] = *reinterpret_cast<uint4 *>(o);
+        }
+    }
+    for (size_t i = n4 * 4 + tid; i < n; i += nthreads) dst[i] = (OutT)quant_one(src[i], s, zp, lo, hi);
+}
+
+template <typename InT>
+__global__ void __launch_bounds__(kThreads)
+dequantize_kernel(const InT *__restrict__ src, float *__restrict__ dst, size_t n, float scale, int zp) {
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = tid; i < n; i += nthreads) {
+        float d = (float)((int)src[i] - zp);
+        dst[i] = d * scale;
+    }
+}
+
+__global__ void __launch_bounds__(kThreads)
+to_fp16_kernel(const float *__restrict__ src, _Float16 *__restrict__ dst, size_t n) {
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = tid; i < n; i += nthreads) dst[i] = (_Float16)src[i];
+}
+
+__global__ void __launch_bounds__(kThreads)
+from_fp16_kernel(const _Float16 *__restrict__ src, float *__restrict__ dst, size_t n) {
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = tid; i < n; i += nthreads) dst[i] = (float)src[i];
+}
+
+// packed[k][r * row_pitch + s * s_pitch + c] = w[k][c][r][s]; everything else 0.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+pack_kernel(const T *__restrict__ w, T *__restrict__ packed, int K, int Cg, int R, int S, int Kp,
+            int row_pitch, int s_pitch, int c_limit) {
+    size_t total = (size_t)K * Kp;
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = tid; i < total; i += nthreads) {
+        int k = (int)(i / Kp);
+        int idx = (int)(i % Kp);
+        int r = idx / row_pitch;
+        int rem = idx % row_pitch;
+        int s = rem / s_pitch;
+        int c = rem % s_pitch;
+        T v = (T)0;
+        if (r < R && s < S && c < c_limit) v = w[(((size_t)k * Cg + c) * R + r) * S + s];
+        packed[i] = v;
+    }
+}
+
+// wsum[k] = sum of the real weight codes of output channel k (int8 / int16 only).
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+wsum_kernel(const T *__restrict__ w, int *__restrict__ wsum, int K, int per_k) {
+    int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    long long s = 0;
+    const T *p = w + (size_t)k * per_k;
+    for (int i = 0; i < per_k; ++i) s += (int)p[i];
+    wsum[k] = (int)s;
+}
+
+__global__ void __launch_bounds__(kThreads) fill_i32_kernel(int *__restrict__ p, int n, int v) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// xp[n][h][wp][cp] = x[n][h][wp][cp] inside the image / channel range, fill elsewhere.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+pad_channels_kernel(const T *__restrict__ x, T *__restrict__ xp, int N, int H, int W, int C, int Wp,
+                    int Cpad, T fill) {
+    size_t total = (size_t)N * H * Wp;
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = tid; i < total; i += nthreads) {
+        int wp = (int)(i % Wp);
+        size_t nh = i / Wp;
+        T v[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] = fill;
+        if (wp < W) {
+            const T *src = x + (nh * W + wp) * C;
+            for (int c = 0; c < C; ++c) v[c] = src[c];
+        }
+        T *dst = xp + i * Cpad;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) dst[c] = v[c];
+    }
+}
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+maxpool_kernel(const T *__restrict__ x, T *__restrict__ y, int N, int H, int W, int C, int P, int Q,
+               int k, int st) {
+    size_t total = (size_t)N * P * Q * C;
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = tid; i < total; i += nthreads) {
+        int c = (int)(i % C);
+        size_t px = i / C;
+        int q = (int)(px % Q);
+        size_t np = px / Q;
+        int p = (int)(np % P);
+        int n = (int)(np / P);
+        const T *base = x + (((size_t)n * H + (size_t)p * st) * W + (size_t)q * st) * C + c;
+        T m = base[0];
+        for (int r = 0; r < k; ++r)
+            for (int s = 0; s < k; ++s) {
+                T v = base[((size_t)r * W + s) * C];
+                m = v > m ? v : m;
+            }
+        y[i] = m;
+    }
+}
+
+// 16-byte-per-thread variant for int8 (C % 16 == 0): max over the window on 16 channels at once.
+__global__ void __launch_bounds__(kThreads)
+maxpool_i8x16_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, int N, int H, int W, int C,
+                     int P, int Q, int k, int st) {
+    typedef signed char v16c __attribute__((ext_vector_type(16)));
+    int cv = C / 16;
+    size_t total = (size_t)N * P * Q * cv;
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = tid; i < total; i += nthreads) {
+        int c = (int)(i % cv);
+        size_t px = i / cv;
+        int q = (int)(px % Q);
+        size_t np = px / Q;
+        int p = (int)(np % P);
+        int n = (int)(np / P);
+        const int8_t *base = x + (((size_t)n * H + (size_t)p * st) * W + (size_t)q * st) * C + c * 16;
+        v16c m = *reinterpret_cast<const v16c *>(base);
+        for (int r = 0; r < k; ++r)
+            for (int s = 0; s < k; ++s) {
+                v16c v = *reinterpret_cast<const v16c *>(base + ((size_t)r * W + s) * C);
+                m = __builtin_elementwise_max(m, v);
+            }
+        *reinterpret_cast<v16c *>(y + px * C + c * 16) = m;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_quantize(const float *src, void *dst, size_t n, int dtype, float scale, int zp,
+                           hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    int vec_ok = ((reinterpret_cast<uintptr_t>(src) % 16) == 0 && (reinterpret_cast<uintptr_t>(dst) % 16) == 0);
+    int grid = grid_for((n + 3) / 4, kThreads);
+    if (dtype == MPQ_INT8)
+        quantize_kernel<int8_t><<<grid, kThreads, 0, st>>>(src, (int8_t *)dst, n, scale, zp, -128, 127, vec_ok);
+    else if (dtype == MPQ_INT16)
+        quantize_kernel<int16_t><<<grid, kThreads, 0, st>>>(src, (int16_t *)dst, n, scale, zp, -32768, 32767, vec_ok);
+    else
+        quantize_kernel<int32_t><<<grid, kThreads, 0, st>>>(src, (int32_t *)dst, n, scale, zp, INT32_MIN, INT32_MAX, vec_ok);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize(const void *src, float *dst, size_t n, int dtype, float scale, int zp,
+                             hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    int grid = grid_for(n, kThreads);
+    if (dtype == MPQ_INT8)
+        dequantize_kernel<int8_t><<<grid, kThreads, 0, st>>>((const int8_t *)src, dst, n, scale, zp);
+    else if (dtype == MPQ_INT16)
+        dequantize_kernel<int16_t><<<grid, kThreads, 0, st>>>((const int16_t *)src, dst, n, scale, zp);
+    else
+        dequantize_kernel<int32_t><<<grid, kThreads, 0, st>>>((const int32_t *)src, dst, n, scale, zp);
+    return hipGetLastError();
+}
+
+hipError_t launch_to_fp16(const float *src, void *dst, size_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    to_fp16_kernel<<<grid_for(n, kThreads), kThreads, 0, st>>>(src, (_Float16 *)dst, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_from_fp16(const void *src, float *dst, size_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    from_fp16_kernel<<<grid_for(n, kThreads), kThreads, 0, st>>>((const _Float16 *)src, dst, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_pack(const void *w_kcrs, void *packed, const mpq_conv_desc &d, const Plan &p,
+                       int dtype, hipStream_t st) {
+    size_t total = (size_t)d.k * p.Kp;
+    int grid = grid_for(total, kThreads);
+    int c_limit = p.Cg;
+    if (p.esize == 1) {
+        pack_kernel<int8_t><<<grid, kThreads, 0, st>>>((const int8_t *)w_kcrs, (int8_t *)packed, d.k, p.Cg,
+                                                       d.r, d.s, p.Kp, p.row_pitch, p.s_pitch, c_limit);
+    } else {
+        pack_kernel<int16_t><<<grid, kThreads, 0, st>>>((const int16_t *)w_kcrs, (int16_t *)packed, d.k,
+                                                        p.Cg, d.r, d.s, p.Kp, p.row_pitch, p.s_pitch, c_limit);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    int *wsum = reinterpret_cast<int *>(reinterpret_cast<char *>(packed) + p.wsum_off);
+    int per_k = p.Cg * d.r * d.s;
+    int g2 = (d.k + kThreads - 1) / kThreads;
+    if (dtype == MPQ_INT8)
+        wsum_kernel<int8_t><<<g2, kThreads, 0, st>>>((const int8_t *)w_kcrs, wsum, d.k, per_k);
+    else if (dtype == MPQ_INT16)
+        wsum_kernel<int16_t><<<g2, kThreads, 0, st>>>((const int16_t *)w_kcrs, wsum, d.k, per_k);
+    else
+        fill_i32_kernel<<<g2, kThreads, 0, st>>>(wsum, d.k, 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_channels(const void *x, void *xp, int N, int H, int W, int C, int Wp, int Cpad,
+                               int esize, int fill, hipStream_t st) {
+    size_t total = (size_t)N * H * Wp;
+    int grid = grid_for(total, kThreads);
+    if (esize == 1)
+        pad_channels_kernel<int8_t><<<grid, kThreads, 0, st>>>((const int8_t *)x, (int8_t *)xp, N, H, W, C,
+                                                              Wp, Cpad, (int8_t)fill);
+    else
+        pad_channels_kernel<int16_t><<<grid, kThreads, 0, st>>>((const int16_t *)x, (int16_t *)xp, N, H, W,
+                                                                C, Wp, Cpad, (int16_t)fill);
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int k, int s, int dtype,
+                          hipStream_t st) {
+    int P = (H - k) / s + 1, Q = (W - k) / s + 1;
+    size_t total = (size_t)N * P * Q * C;
+    if (total == 0) return hipSuccess;
+    bool aligned = (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
+    if (dtype == MPQ_INT8 && C % 16 == 0 && aligned) {
+        maxpool_i8x16_kernel<<<grid_for(total / 16, kThreads), kThreads, 0, st>>>(
+            (const int8_t *)x, (int8_t *)y, N, H, W, C, P, Q, k, s);
+    } else if (dtype == MPQ_INT8) {
+        maxpool_kernel<int8_t><<<grid_for(total, kThreads), kThreads, 0, st>>>((const int8_t *)x, (int8_t *)y,
+                                                                             N, H, W, C, P, Q, k, s);
+    } else if (dtype == MPQ_INT16) {
+        maxpool_kernel<int16_t><<<grid_for(total, kThreads), kThreads, 0, st>>>(
+            (const int16_t *)x, (int16_t *)y, N, H, W, C, P, Q, k, s);
+    } else {
+        maxpool_kernel<_Float16><<<grid_for(total, kThreads), kThreads, 0, st>>>(
+            (const _Float16 *)x, (_Float16 *)y, N, H, W, C, P, Q, k, s);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace mpq

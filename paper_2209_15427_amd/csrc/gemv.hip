@@ -1,0 +1,189 @@
+// Fully-connected layer with a small batch (or a small output width): the memory-bound regime.
+//
+// acc[m, n] = sum_k x[m, k] w[n, k] on the raw codes (expanded zero-point form, section
+// "Quantized Operations"), then the same fused epilogue as the convolution kernels.
+//
+// One of the two matrices has at most 16 rows ("resident": re-read by every workgroup, it stays
+// in L2); the other is streamed from HBM exactly once ("streamed": ROWS rows per workgroup, all
+// 256 threads striding the reduction axis in 16-byte chunks, several loads in flight per lane).
+// Batch 1..16 FC layers stream the weights; a gating layer with <= 16 outputs streams the
+// activations instead.  Lane partial sums are combined with cross-lane shuffles and one LDS hop.
+#include "common.h"
+#include "epilogue.h"
+
+namespace mpq {
+
+namespace {
+
+constexpr int kThreads = 256;
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+
+struct GemvArgs {
+    const char *streamed;     // [ns][ld_s] bytes
+    const char *resident;     // [nr][ld_r] bytes
+    const void *bias;
+    const int *wsum;
+    void *y;
+    int ns, nr;
+    long long ld_s, ld_r;     // bytes between rows
+    int chunks;               // 16-byte chunks of real reduction length
+    int swapped;              // 0: streamed = weights (row = n), resident = x (row = m); 1: the reverse
+    int N;                    // output width (row stride of y in elements)
+    int out_dtype;
+    Epi epi;
+};
+
+template <typename T> struct Dot;
+template <> struct Dot<int8_t> {
+    typedef int Acc;
+    static __device__ __forceinline__ Acc run(v4i a, v4i b, Acc c) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_sdot4(a[i], b[i], c, false);
+        return c;
+    }
+};
+template <> struct Dot<_Float16> {
+    typedef float Acc;
+    static __device__ __forceinline__ Acc run(v4i a, v4i b, Acc c) {
+        const v8h ah = __builtin_bit_cast(v8h, a), bh = __builtin_bit_cast(v8h, b);
+        c = __builtin_amdgcn_fdot2(__builtin_shufflevector(ah, ah, 0, 1), __builtin_shufflevector(bh, bh, 0, 1), c, false);
+        c = __builtin_amdgcn_fdot2(__builtin_shufflevector(ah, ah, 2, 3), __builtin_shufflevector(bh, bh, 2, 3), c, false);
+        c = __builtin_amdgcn_fdot2(__builtin_shufflevector(ah, ah, 4, 5), __builtin_shufflevector(bh, bh, 4, 5), c, false);
+        c = __builtin_amdgcn_fdot2(__builtin_shufflevector(ah, ah, 6, 7), __builtin_shufflevector(bh, bh, 6, 7), c, false);
+        return c;
+    }
+};
+
+template <typename Acc> __device__ __forceinline__ Acc wave_sum(Acc v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+template <typename T, int NR, int ROWS>
+__global__ void __launch_bounds__(kThreads) gemv_kernel(GemvArgs g) {
+    typedef typename Dot<T>::Acc Acc;
+    __shared__ Acc red[4][NR * ROWS];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int s0 = blockIdx.x * ROWS;
+
+    const char *srow[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        int s = s0 + r;
+        s = s < g.ns ? s : g.ns - 1;
+        srow[r] = g.streamed + (size_t)s * g.ld_s;
+    }
+    Acc acc[NR][ROWS];
+#pragma unroll
+    for (int m = 0; m < NR; ++m)
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) acc[m][r] = 0;
+
+    for (int j = tid; j < g.chunks; j += kThreads) {
+        v4i wv[ROWS];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r)
+            wv[r] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(srow[r] + (size_t)j * kChunkBytes));
+#pragma unroll
+        for (int m = 0; m < NR; ++m) {
+            int mm = m < g.nr ? m : g.nr - 1;
+            v4i xv = *reinterpret_cast<const v4i *>(g.resident + (size_t)mm * g.ld_r + (size_t)j * kChunkBytes);
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) acc[m][r] = Dot<T>::run(xv, wv[r], acc[m][r]);
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < NR; ++m)
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            Acc v = wave_sum(acc[m][r]);
+            if (lane == 0) red[wave][m * ROWS + r] = v;
+        }
+    __syncthreads();
+    if (tid < NR * ROWS) {
+        const int m = tid / ROWS, r = tid % ROWS;
+        const int s = s0 + r;
+        if (m < g.nr && s < g.ns) {
+            Acc v = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
+            const int row = g.swapped ? s : m;     // batch index
+            const int n = g.swapped ? m : s;       // output feature
+            const size_t o = (size_t)row * g.N + n;
+            if constexpr (sizeof(T) == 1) {
+                int t = v;
+                if (g.bias) t += ((const int *)g.bias)[n];
+                if (g.epi.zx != 0) t -= g.epi.zx * g.wsum[n];
+                if (g.epi.kind == kEpiRawI32) ((int *)g.y)[o] = t;
+                else ((int8_t *)g.y)[o] = (int8_t)requant64((long long)t, g.epi);
+            } else {
+                float t = v;
+                if (g.bias) t += ((const float *)g.bias)[n];
+                if (g.epi.relu) t = t > 0.f ? t : 0.f;
+                if (g.epi.kind == kEpiRawF32) ((float *)g.y)[o] = t;
+                else ((_Float16 *)g.y)[o] = (_Float16)t;
+            }
+        }
+    }
+}
+
+template <typename T, int NR>
+hipError_t launch_rows(const GemvArgs &g, hipStream_t st) {
+    // rows per workgroup: enough workgroups to cover the chip several times over
+    if (g.ns >= 4096) {
+        gemv_kernel<T, NR, 4><<<(g.ns + 3) / 4, kThreads, 0, st>>>(g);
+    } else if (g.ns >= 2048) {
+        gemv_kernel<T, NR, 2><<<(g.ns + 1) / 2, kThreads, 0, st>>>(g);
+    } else {
+        gemv_kernel<T, NR, 1><<<g.ns, kThreads, 0, st>>>(g);
+    }
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_nr(const GemvArgs &g, hipStream_t st) {
+    if (g.nr <= 1) return launch_rows<T, 1>(g, st);
+    if (g.nr <= 2) return launch_rows<T, 2>(g, st);
+    if (g.nr <= 4) return launch_rows<T, 4>(g, st);
+    if (g.nr <= 8) return launch_rows<T, 8>(g, st);
+    return launch_rows<T, 16>(g, st);
+}
+
+}  // namespace
+
+bool gemv_eligible(const ConvArgs &a) {
+    if (a.R != 1 || a.S != 1 || a.H != 1 || a.W != 1 || a.groups != 1) return false;
+    if (a.in_dtype != MPQ_INT8 && a.in_dtype != MPQ_FP16) return false;
+    if (a.in_dtype == MPQ_INT8 && a.epi.zw != 0) return false;
+    const int es = a.plan.esize;
+    if (((size_t)a.C * es) % kChunkBytes != 0) return false;
+    if ((reinterpret_cast<uintptr_t>(a.x) % 16) || (reinterpret_cast<uintptr_t>(a.w) % 16)) return false;
+    return a.N <= 16 || a.K <= 16;
+}
+
+hipError_t launch_gemv(const ConvArgs &a, hipStream_t st) {
+    GemvArgs g;
+    const int es = a.plan.esize;
+    g.bias = a.bias;
+    g.wsum = reinterpret_cast<const int *>((const char *)a.w + a.plan.wsum_off);
+    g.y = a.y;
+    g.chunks = (int)((size_t)a.C * es / kChunkBytes);
+    g.N = a.K;
+    g.out_dtype = a.out_dtype;
+    g.epi = a.epi;
+    const long long ld_w = (long long)a.plan.Kp * es, ld_x = (long long)a.C * es;
+    if (a.N <= 16) {
+        g.swapped = 0;
+        g.streamed = (const char *)a.w; g.ns = a.K; g.ld_s = ld_w;
+        g.resident = (const char *)a.x; g.nr = a.N; g.ld_r = ld_x;
+    } else {
+        g.swapped = 1;
+        g.streamed = (const char *)a.x; g.ns = a.N; g.ld_s = ld_x;
+        g.resident = (const char *)a.w; g.nr = a.K; g.ld_r = ld_w;
+    }
+    if (a.in_dtype == MPQ_INT8) return launch_nr<int8_t>(g, st);
+    return launch_nr<_Float16>(g, st);
+}
+
+}  // namespace mpq

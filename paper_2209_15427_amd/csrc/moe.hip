@@ -1,0 +1,145 @@
+// Gating selection and sample dispatch of the mixture-of-experts stage (section "Mixture of
+// Experts": experts are selected per sample; with one expert per sample the mixing weight is 1).
+//
+// route_kernel: expert[b] = argmax_i logits[b, i] (lowest index on ties), the per-expert usage
+// counts c_i, their exclusive prefix sums, and the stable permutation that lists the samples
+// expert by expert.  One workgroup; samples are bucketed with wavefront ballots: a lane's rank
+// among the samples of its expert is the population count of the ballot mask below its lane,
+// plus the totals of the earlier wavefronts and of the earlier rounds.
+#include "common.h"
+
+namespace mpq {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+template <typename LT>
+__global__ void __launch_bounds__(kThreads)
+route_kernel(const LT *__restrict__ logits, int B, int E, int *__restrict__ expert, int *__restrict__ counts,
+             int *__restrict__ offsets, int *__restrict__ perm) {
+    __shared__ int cnt[kMaxExperts];
+    __shared__ int running[kMaxExperts];
+    __shared__ int wave_cnt[kWaves][kMaxExperts];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < kMaxExperts) cnt[tid] = 0;
+    __syncthreads();
+
+    // pass 1: arg-max and usage counts
+    for (int b0 = 0; b0 < B; b0 += kThreads) {
+        const int b = b0 + tid;
+        const bool valid = b < B;
+        int best = 0;
+        if (valid) {
+            const LT *row = logits + (size_t)b * E;
+            LT bv = row[0];
+            for (int i = 1; i < E; ++i) {
+                LT v = row[i];
+                if (v > bv) { bv = v; best = i; }
+            }
+            expert[b] = best;
+        }
+        for (int e = 0; e < E; ++e) {
+            unsigned long long mask = __ballot(valid && best == e);
+            if (lane == 0 && mask) atomicAdd(&cnt[e], __popcll(mask));
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            offsets[e] = run;
+            running[e] = run;
+            counts[e] = cnt[e];
+            run += cnt[e];
+        }
+        offsets[E] = run;
+    }
+    __syncthreads();
+
+    // pass 2: stable position of every sample inside its expert's segment
+    for (int b0 = 0; b0 < B; b0 += kThreads) {
+        const int b = b0 + tid;
+        const bool valid = b < B;
+        const int mine = valid ? expert[b] : -1;
+        int rank = 0;
+        for (int e = 0; e < E; ++e) {
+            unsigned long long mask = __ballot(mine == e);
+            if (lane == 0) wave_cnt[wave][e] = __popcll(mask);
+            if (mine == e) rank = __popcll(mask & ((1ull << lane) - 1ull));
+        }
+        __syncthreads();
+        if (valid) {
+            int pos = running[mine] + rank;
+            for (int w = 0; w < wave; ++w) pos += wave_cnt[w][mine];
+            perm[pos] = b;
+        }
+        __syncthreads();
+        if (tid < E) {
+            int add = 0;
+            for (int w = 0; w < kWaves; ++w) add += wave_cnt[w][tid];
+            running[tid] += add;
+        }
+        __syncthreads();
+    }
+}
+
+// dst row i = src row perm[i] (gather) or dst row perm[i] = src row i (scatter)
+template <bool kScatter>
+__global__ void __launch_bounds__(kThreads)
+move_rows_kernel(const char *__restrict__ src, char *__restrict__ dst, const int *__restrict__ perm, int B,
+                 size_t row_bytes, int vec) {
+    const size_t per_row = vec ? row_bytes / 16 : row_bytes;
+    const size_t total = (size_t)B * per_row;
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = tid; i < total; i += nthreads) {
+        const int row = (int)(i / per_row);
+        const size_t off = i % per_row;
+        const int other = perm[row];
+        const size_t srow = kScatter ? row : other, drow = kScatter ? other : row;
+        if (vec) {
+            reinterpret_cast<uint4 *>(dst + drow * row_bytes)[off] =
+                reinterpret_cast<const uint4 *>(src + srow * row_bytes)[off];
+        } else {
+            dst[drow * row_bytes + off] = src[srow * row_bytes + off];
+        }
+    }
+}
+
+template <bool kScatter>
+hipError_t move_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes, hipStream_t st) {
+    if (B == 0 || row_bytes == 0) return hipSuccess;
+    int vec = (row_bytes % 16 == 0) && (reinterpret_cast<uintptr_t>(src) % 16 == 0) &&
+              (reinterpret_cast<uintptr_t>(dst) % 16 == 0);
+    size_t work = (size_t)B * (vec ? row_bytes / 16 : row_bytes);
+    size_t blocks = (work + kThreads - 1) / kThreads;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    move_rows_kernel<kScatter><<<(int)blocks, kThreads, 0, st>>>((const char *)src, (char *)dst, perm, B,
+                                                                row_bytes, vec);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_route(const void *logits, int logits_dtype, int B, int E, int *expert, int *counts,
+                        int *offsets, int *perm, hipStream_t st) {
+    if (logits_dtype == MPQ_INT32)
+        route_kernel<int><<<1, kThreads, 0, st>>>((const int *)logits, B, E, expert, counts, offsets, perm);
+    else
+        route_kernel<float><<<1, kThreads, 0, st>>>((const float *)logits, B, E, expert, counts, offsets, perm);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes,
+                              hipStream_t st) {
+    return move_rows<false>(src, dst, perm, B, row_bytes, st);
+}
+
+hipError_t launch_scatter_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes,
+                               hipStream_t st) {
+    return move_rows<true>(src, dst, perm, B, row_bytes, st);
+}
+
+}  // namespace mpq

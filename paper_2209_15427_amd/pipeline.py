@@ -1,0 +1,148 @@
+"""Device-side plumbing above the binding: upload real-valued parameters, have the library
+quantize / convert and pack them, allocate activations once, and enqueue the layer calls.
+
+Nothing here computes layer arithmetic: every number comes out of a libmpq kernel.  torch is
+used to hold device memory and to re-lay-out host tensors (N,C,H,W -> N,H,W,C; FC weight columns
+from (c,h,w) to (h,w,c) order after a convolution).
+"""
+import numpy as np
+import torch
+
+from . import binding as mb
+
+DEV = "cuda"
+
+
+def _dev(a, dtype=torch.float32):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dtype).to(DEV)
+
+
+def alloc_bytes(n):
+    """256-byte aligned device buffer (torch's caching allocator aligns to 512)."""
+    return torch.empty(max(int(n), 1), dtype=torch.uint8, device=DEV)
+
+
+def to_storage(real_nchw_or_mk, dtype, scale=1.0, zero=0, nhwc=True):
+    """Real-valued host array -> device storage tensor (quantized codes or fp16) via the library."""
+    a = np.asarray(real_nchw_or_mk, np.float32)
+    if nhwc and a.ndim == 4:
+        a = a.transpose(0, 2, 3, 1)
+    src = _dev(a)
+    dst = torch.empty(src.shape, dtype=mb.TORCH_DTYPE[dtype], device=DEV)
+    if dtype == mb.FP16:
+        mb.mpq_to_fp16(src, dst, src.numel())
+    else:
+        mb.mpq_quantize(src, dst, src.numel(), dtype, scale, zero)
+    return dst
+
+
+class Layer:
+    """One conv / FC layer resident on the device: packed weights, bias, descriptor, scales."""
+
+    def __init__(self, spec, w_real, b_real, dtype, sc=None, fc_from_chw=None, w_zero=0):
+        self.spec, self.dtype = spec, dtype
+        self.is_fc = spec.kind == "fc"
+        if self.is_fc:
+            self.desc = mb.gemm_desc(spec.K, spec.N, spec.relu)
+            w = np.asarray(w_real, np.float32)
+            if fc_from_chw is not None:        # columns arrive in (c,h,w) order; the device is NHWC
+                c, h, wd = fc_from_chw
+                w = w.reshape(spec.N, c, h, wd).transpose(0, 2, 3, 1).reshape(spec.N, -1)
+            w = w.reshape(spec.N, spec.K, 1, 1)
+            self.k_out = spec.N
+        else:
+            self.desc = mb.conv_desc(spec.C, spec.K, spec.R, spec.S, spec.stride, spec.pad, spec.groups,
+                                     spec.relu, spec.pool_k, spec.pool_s)
+            w = np.asarray(w_real, np.float32)
+            self.k_out = spec.K
+        self.w_scale = 1.0 if sc is None else sc["w"]
+        self.y_scale = 1.0 if sc is None else sc["y"]
+        self.w_zero = w_zero
+        # weights: library-side conversion to the storage type, then packing
+        self.w_kcrs = to_storage(w, dtype, self.w_scale, w_zero, nhwc=False)
+        self.packed_bytes = mb.mpq_packed_weight_bytes(self.desc, dtype)
+        self.packed = alloc_bytes(self.packed_bytes)
+        mb.mpq_pack_weights(self.w_kcrs, self.desc, dtype, self.packed, self.packed_bytes)
+        # bias: int32 codes at scale s_x s_w for integer layers, fp32 for fp16 layers
+        self.bias = None
+        if b_real is not None:
+            b = _dev(np.asarray(b_real, np.float32))
+            if dtype == mb.FP16:
+                self.bias = b
+            else:
+                self.bias = torch.empty(b.shape, dtype=torch.int32, device=DEV)
+                mb.mpq_quantize(b, self.bias, b.numel(), mb.INT32, sc["b"], 0)
+
+    def out_shape(self, n, h, w):
+        s = self.spec
+        if self.is_fc:
+            return n, 1, 1, s.N
+        P, Q = s.out_hw(h, w)
+        if s.pool_k:
+            P, Q = (P - s.pool_k) // s.pool_s + 1, (Q - s.pool_k) // s.pool_s + 1
+        return n, P, Q, s.K
+
+
+class Chain:
+    """A stack of layers with pre-allocated activations; forward() only enqueues kernels."""
+
+    def __init__(self, specs, params_real, dtype, batch, in_chw, s_in=1.0, scales=None, raw_last=False):
+        self.dtype, self.batch = dtype, batch
+        c, h, w = in_chw
+        self.in_shape = (batch, h, w, c)
+        self.s_in = s_in
+        self.layers, self.acts, self.views = [], [], []
+        shape = self.in_shape
+        prev_conv_chw = None
+        ws_need = 0
+        for i, (spec, (wr, br)) in enumerate(zip(specs, params_real)):
+            sc = None if scales is None else scales[i]
+            from_chw = None
+            if spec.kind == "fc" and (shape[1] > 1 or shape[2] > 1):
+                from_chw = (shape[3], shape[1], shape[2])
+            L = Layer(spec, wr, br, dtype, sc, from_chw)
+            oshape = L.out_shape(shape[0], shape[1], shape[2])
+            out_dt = dtype
+            if raw_last and i == len(specs) - 1:
+                out_dt = mb.FP32 if dtype == mb.FP16 else mb.INT32
+            y = torch.empty(oshape, dtype=mb.TORCH_DTYPE[out_dt], device=DEV)
+            self.layers.append(L)
+            self.acts.append(y)
+            s_x = s_in if i == 0 else (1.0 if scales is None else scales[i - 1]["y"])
+            if spec.kind == "fc":
+                xin = (shape[0], 1, 1, shape[1] * shape[2] * shape[3])
+            else:
+                xin = shape
+            xv = lambda data, xin=xin, s_x=s_x: mb.tensor(data, dtype, *xin, scale=s_x)
+            yv = mb.tensor(y, out_dt, *oshape, scale=L.y_scale)
+            self.views.append((xv, yv))
+            if spec.kind != "fc":
+                ws_need = max(ws_need, mb.mpq_conv2d_workspace_bytes(xv(None), L.desc))
+            shape = oshape
+        self.ws_bytes = ws_need
+        self.ws = alloc_bytes(ws_need)
+        torch.cuda.synchronize()
+
+    def run_layer(self, i, x_storage):
+        """Enqueue layer i alone on the given input storage; returns its output tensor."""
+        L, y, (xv, yv) = self.layers[i], self.acts[i], self.views[i]
+        if L.is_fc:
+            mb.mpq_gemm(xv(x_storage), L.packed, L.w_scale, L.w_zero, L.bias, yv, L.spec.relu, self.ws, self.ws_bytes)
+        else:
+            mb.mpq_conv2d(xv(x_storage), L.packed, L.w_scale, L.w_zero, L.bias, yv, L.desc, self.ws, self.ws_bytes)
+        return y
+
+    def forward(self, x_storage):
+        cur = x_storage
+        for i in range(len(self.layers)):
+            cur = self.run_layer(i, cur)
+        return cur
+
+    def input_storage(self, x_real_nchw):
+        return to_storage(x_real_nchw, self.dtype, self.s_in, 0)
+
+
+def nhwc_to_nchw(t):
+    """Device NHWC (or [M, N]) result -> host numpy in the logical N,C,H,W order."""
+    a = t.detach().cpu().numpy()
+    return a.transpose(0, 3, 1, 2) if a.ndim == 4 else a

@@ -1,0 +1,102 @@
+"""Helpers for the GPU parity tests: run single layers through the C ABI and compare with the
+CPU oracle.  No layer arithmetic here."""
+import numpy as np
+import torch
+
+from paper_2209_15427_amd import binding as mb
+from paper_2209_15427_amd import pipeline as pl
+
+NP_STORE = {mb.INT8: np.int8, mb.INT16: np.int16}
+NAME = {mb.INT8: "int8", mb.INT16: "int16", mb.FP16: "fp16"}
+
+
+def codes_to_dev(codes_nchw, dtype):
+    """Integer codes (logical N,C,H,W or M,K) -> device NHWC storage tensor."""
+    a = np.asarray(codes_nchw)
+    if a.ndim == 4:
+        a = a.transpose(0, 2, 3, 1)
+    return torch.from_numpy(np.ascontiguousarray(a.astype(NP_STORE[dtype]))).to("cuda")
+
+
+def half_to_dev(vals_nchw):
+    a = np.asarray(vals_nchw, np.float64)
+    if a.ndim == 4:
+        a = a.transpose(0, 2, 3, 1)
+    return torch.from_numpy(np.ascontiguousarray(a.astype(np.float16))).to("cuda")
+
+
+def pack(w_dev_kcrs, desc, dtype):
+    nbytes = mb.mpq_packed_weight_bytes(desc, dtype)
+    packed = pl.alloc_bytes(nbytes)
+    mb.mpq_pack_weights(w_dev_kcrs, desc, dtype, packed, nbytes)
+    return packed
+
+
+def run_conv(x_dev, xq, w_dev_kcrs, wq, bias_dev, desc, dtype, yq=(1.0, 0), out_dtype=None):
+    """x_dev: NHWC device tensor.  Returns the NHWC output tensor (host sync included)."""
+    out_dtype = dtype if out_dtype is None else out_dtype
+    n, h, w, c = x_dev.shape
+    packed = pack(w_dev_kcrs, desc, dtype)
+    P = (h + 2 * desc.pad_h - desc.r) // desc.stride_h + 1
+    Q = (w + 2 * desc.pad_w - desc.s) // desc.stride_w + 1
+    if desc.pool_k:
+        P, Q = (P - desc.pool_k) // desc.pool_s + 1, (Q - desc.pool_k) // desc.pool_s + 1
+    y = torch.full((n, P, Q, desc.k), 77, dtype=mb.TORCH_DTYPE[out_dtype], device="cuda")
+    xv = mb.tensor(x_dev, dtype, n, h, w, c, xq[0], xq[1])
+    yv = mb.tensor(y, out_dtype, n, P, Q, desc.k, yq[0], yq[1])
+    nws = mb.mpq_conv2d_workspace_bytes(xv, desc)
+    ws = pl.alloc_bytes(nws)
+    mb.mpq_conv2d(xv, packed, wq[0], wq[1], bias_dev, yv, desc, ws, nws)
+    torch.cuda.synchronize()
+    return y
+
+
+def run_gemm(x_dev, xq, w_dev, wq, bias_dev, relu, dtype, yq=(1.0, 0), out_dtype=None):
+    out_dtype = dtype if out_dtype is None else out_dtype
+    m, k = x_dev.shape
+    n = w_dev.shape[0]
+    desc = mb.gemm_desc(k, n, relu)
+    packed = pack(w_dev, desc, dtype)
+    y = torch.full((m, n), 77, dtype=mb.TORCH_DTYPE[out_dtype], device="cuda")
+    xv = mb.tensor(x_dev, dtype, m, 1, 1, k, xq[0], xq[1])
+    yv = mb.tensor(y, out_dtype, m, 1, 1, n, yq[0], yq[1])
+    mb.mpq_gemm(xv, packed, wq[0], wq[1], bias_dev, yv, relu, None, 0)
+    torch.cuda.synchronize()
+    return y
+
+
+def to_nchw(t):
+    a = t.cpu().numpy()
+    return a.transpose(0, 3, 1, 2) if a.ndim == 4 else a
+
+
+FLOOR_SAME_INPUT = 1e-2
+
+
+def check_fp16(got, ref64, what="", floor_frac=FLOOR_SAME_INPUT):
+    """got: fp16 (or fp32) device result as numpy; ref64: the fp64 oracle value.
+    Max relative error <= 1e-2 with the denominator floored at floor_frac * rms(ref); median error
+    <= 2 fp16 ulp measured at the reference's binade.
+
+    Relative error is unbounded where a sum cancels (or ReLU clips) to ~0, so small references are
+    compared absolutely.  On identical inputs floor_frac = 1e-2, an absolute slack of 1e-4 * rms:
+    fp32 accumulation of K products errs by about sqrt(K) 2^-24 sum|x w| ~ K 2^-24 rms, i.e.
+    1e-5..1e-4 rms for K = 10^2..10^3 (measured: 1.2e-5 rms at K = 800).  For the second and later
+    layers of a device chain compared end to end the floor is 0.1 per layer of depth (slack
+    1e-3 * rms ~ 2 fp16 ulp at the tensor's typical magnitude per layer): the two chains' inputs
+    differ wherever an earlier fp32-accumulated value and its fp64 value round to different fp16
+    neighbours, which moves every output by a fraction of 2^-11 * rms whatever its own size.
+    A dropped or misplaced tap moves outputs by ~rms / sqrt(K) >= 1e-2 * rms and fails either bar."""
+    g = np.asarray(got, np.float64)
+    r = np.asarray(ref64, np.float64)
+    assert g.shape == r.shape, (g.shape, r.shape)
+    assert np.all(np.isfinite(g)), what
+    rms = float(np.sqrt(np.mean(r * r)))
+    tau = floor_frac * rms if rms > 0 else 1e-30
+    rel = np.abs(g - r) / np.maximum(np.abs(r), tau)
+    assert rel.max() <= 1e-2, f"{what}: max rel err {rel.max():.3e}"
+    expo = np.floor(np.log2(np.maximum(np.abs(r), 2.0 ** -14)))
+    ulp = 2.0 ** (expo - 10)
+    med = float(np.median(np.abs(g - r) / ulp))
+    assert med <= 2.0, f"{what}: median {med} ulp"
+    return float(rel.max()), med

@@ -1,0 +1,304 @@
+"""GPU parity, layer by layer: every libmpq entry point against the CPU oracle on the same seeded
+inputs.  Integer paths must be bit-exact; fp16 within 1e-2 max relative error and 2 ulp median of
+the fp64 oracle (tests/gpu_util.check_fp16)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as o
+from paper_2209_15427_amd import binding as mb
+from paper_2209_15427_amd import pipeline as pl
+from tests import gpu_util as gu
+from workloads import configs as cf, gen
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+# ---------------------------------------------------------------------------------------------
+# quantizer conversions
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,zero", [(mb.INT8, 0), (mb.INT8, -17), (mb.INT16, 0), (mb.INT16, 1234), (mb.INT32, 0)])
+@pytest.mark.parametrize("count", [0, 1, 5, 4096, 1000003])
+def test_quantize_dequantize(dtype, zero, count):
+    _say("quantize", dtype, zero, count)
+    scale = np.float32(0.0371)
+    r = gen.normal(90 + count % 7, (max(count, 1),), 0.0, 3.0).astype(np.float32)[:count]
+    if count >= 5:
+        r[:5] = [np.inf, -np.inf, np.nan, 1e30, -1e30]
+    src = torch.from_numpy(r).to("cuda")
+    dst = torch.empty(count, dtype=mb.TORCH_DTYPE[dtype], device="cuda")
+    mb.mpq_quantize(src, dst, count, dtype, scale, zero)
+    torch.cuda.synchronize()
+    if dtype == mb.INT32:
+        ref = o.quantize_bias(r, scale) if count else np.zeros(0, np.int32)
+    else:
+        ref = o.quantize(r, scale, zero, gu.NAME[dtype]) if count else np.zeros(0, np.int32)
+    assert np.array_equal(dst.cpu().numpy().astype(np.int64), ref.astype(np.int64))
+    back = torch.empty(count, dtype=torch.float32, device="cuda")
+    mb.mpq_dequantize(dst, back, count, dtype, scale, zero)
+    torch.cuda.synchronize()
+    refb = o.dequantize(ref, scale, zero) if count else np.zeros(0, np.float32)
+    assert np.array_equal(back.cpu().numpy(), refb)
+
+
+def test_quantize_ties_and_unaligned():
+    scale = np.float32(0.25)
+    k = np.arange(-300, 300)
+    r = np.concatenate([(k + 0.5) * 0.25, k * 0.25]).astype(np.float32)
+    big = torch.from_numpy(np.concatenate([[0.0], r]).astype(np.float32)).to("cuda")
+    src = big[1:]                               # 4-byte aligned only: scalar path
+    dst = torch.empty(r.size + 1, dtype=torch.int8, device="cuda")[1:]
+    mb.mpq_quantize(src, dst, r.size, mb.INT8, scale, 3)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy(), o.quantize(r, scale, 3, "int8").astype(np.int8))
+
+
+def test_fp16_conversion():
+    v = np.concatenate([gen.normal(1, (10001,), 0, 1.0), gen.normal(2, (500,), 0, 1e-6),
+                        gen.normal(3, (500,), 0, 3e4)]).astype(np.float32)
+    src = torch.from_numpy(v).to("cuda")
+    dst = torch.empty(v.size, dtype=torch.float16, device="cuda")
+    mb.mpq_to_fp16(src, dst, v.size)
+    back = torch.empty(v.size, dtype=torch.float32, device="cuda")
+    mb.mpq_from_fp16(dst, back, v.size)
+    torch.cuda.synchronize()
+    ref = o.round_fp16(v.astype(np.float64))
+    assert np.array_equal(dst.cpu().numpy().astype(np.float64), ref)
+    assert np.array_equal(back.cpu().numpy().astype(np.float64), ref)
+
+
+# ---------------------------------------------------------------------------------------------
+# integer convolution
+# ---------------------------------------------------------------------------------------------
+def _int_conv_case(dtype, N, C, H, W, K, R, S, stride, pad, groups, relu, pool, zx, zw, zy, seed, raw=False):
+    name = gu.NAME[dtype]
+    qmin, qmax = o.QRANGE[name]
+    x = gen.integers(seed, (N, C, H, W), qmin, qmax)
+    w = gen.integers(seed + 1, (K, C // groups, R, S), max(qmin, -127 * (qmax // 127)), qmax)
+    b = gen.integers(seed + 2, (K,), -5000, 5000)
+    t = o.conv2d_acc(x, zx, w, zw, b, stride, pad, groups)
+    # output scale from the accumulator spread so that codes fill the range without all saturating
+    s_x, s_w = np.float32(0.021), np.float32(0.013)
+    s_y = np.float32(float(s_x) * float(s_w) * float(np.std(t)) * 3.0 / qmax + 1e-12)
+    desc = mb.conv_desc(C, K, R, S, stride, pad, groups, relu, pool[0], pool[1])
+    xd = gu.codes_to_dev(x, dtype)
+    wd = torch.from_numpy(np.ascontiguousarray(w.astype(gu.NP_STORE[dtype]))).to("cuda")
+    bd = torch.from_numpy(b.astype(np.int32)).to("cuda")
+    if raw:
+        y = gu.run_conv(xd, (s_x, zx), wd, (s_w, zw), bd, desc, dtype, out_dtype=mb.INT32)
+        assert np.array_equal(gu.to_nchw(y).astype(np.int64), t)
+        return
+    y = gu.run_conv(xd, (s_x, zx), wd, (s_w, zw), bd, desc, dtype, (s_y, zy))
+    mult, shift = o.scale_quant_vals(s_x, s_w, s_y, o.SHIFT_BITS[name])
+    ref = o.requant(t, mult, o.SHIFT_BITS[name], shift, zy, name, relu)
+    if pool[0]:
+        ref = o.maxpool_i32(ref, pool[0], pool[1])
+    got = gu.to_nchw(y).astype(np.int32)
+    assert got.shape == ref.shape
+    bad = np.argwhere(got != ref)
+    assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[tuple(bad[0])]} ref {ref[tuple(bad[0])]}"
+    # the check is meaningful: outputs are spread, not all clamped
+    assert len(np.unique(ref)) > 20
+
+
+def test_config1_single_int8_conv():
+    """Config 1: N=1, 3x32x32, 16 filters 3x3, stride 1, pad 1, bias + ReLU, scales 0.02/0.01/0.05."""
+    _say("config 1")
+    c1 = cf.Config1()
+    x, w, b = c1.tensors()
+    L = c1.layer
+    desc = mb.conv_desc(L.C, L.K, L.R, L.S, L.stride, L.pad, L.groups, L.relu)
+    xd = gu.codes_to_dev(x, mb.INT8)
+    wd = torch.from_numpy(w.astype(np.int8)).to("cuda")
+    bd = torch.from_numpy(b.astype(np.int32)).to("cuda")
+    y = gu.run_conv(xd, (c1.s_x, 0), wd, (c1.s_w, 0), bd, desc, mb.INT8, (c1.s_y, 0))
+    t = o.conv2d_acc(x, 0, w, 0, b, L.stride, L.pad, L.groups)
+    mult, shift = o.scale_quant_vals(c1.s_x, c1.s_w, c1.s_y, 31)
+    assert (mult, shift) == mb.mpq_scale_quant_vals(c1.s_x, c1.s_w, c1.s_y, mb.INT8)
+    ref = o.requant(t, mult, 31, shift, 0, "int8", True)
+    assert np.array_equal(gu.to_nchw(y).astype(np.int32), ref)
+    assert ref.max() == 127 and ref.min() == 0     # saturates by construction, ReLU clamps at 0
+
+
+CONV_CASES = [
+    # N, C, H, W, K, R, S, stride, pad, groups, relu, pool, zx, zw, zy
+    (3, 32, 19, 19, 192, 3, 3, 1, 1, 2, True, (0, 0), 0, 0, 0),        # MFMA tap path, 64-ch tiles, ragged pixels
+    (2, 64, 13, 13, 384, 3, 3, 1, 1, 1, True, (0, 0), 0, 0, 0),        # 128x128 tiles, 3 channel tiles
+    (2, 96, 27, 27, 256, 5, 5, 1, 2, 2, True, (3, 2), 0, 0, 0),        # conv2 shape (C/g = 48), fused pool
+    (2, 48, 9, 11, 72, 3, 3, 2, 1, 1, False, (0, 0), 5, 0, -3),        # ragged channels (72), zero-points, no relu
+    (1, 16, 7, 7, 8, 1, 1, 1, 0, 1, True, (0, 0), -128, 0, 10),        # 1x1, tiny, extreme z_x
+    (2, 3, 43, 43, 96, 11, 11, 4, 0, 1, True, (3, 2), 0, 0, 0),        # first-layer shape: row path + pool
+    (2, 3, 43, 43, 40, 11, 11, 4, 0, 1, True, (0, 0), 7, 0, 0),        # row path, ragged channels, z_x != 0
+    (2, 3, 12, 12, 16, 3, 3, 1, 1, 1, True, (0, 0), 0, 0, 0),          # generic path (C = 3 with padding)
+    (2, 20, 12, 12, 50, 5, 5, 1, 0, 1, False, (2, 2), 0, 0, 0),        # generic path (LeNet conv2)
+    (2, 32, 9, 9, 64, 3, 3, 1, 1, 2, True, (0, 0), 3, -4, 2),          # z_w != 0 -> generic path
+    (5, 256, 13, 13, 192, 3, 3, 1, 1, 1, True, (0, 0), 0, 0, 0),       # MoE expert conv3'
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES, ids=[f"c{i}" for i in range(len(CONV_CASES))])
+def test_int8_conv(case):
+    _say("int8 conv", case)
+    _int_conv_case(mb.INT8, *case, seed=1000 + 17 * CONV_CASES.index(case))
+
+
+@pytest.mark.parametrize("case", [CONV_CASES[i] for i in (0, 3, 5, 8, 9)], ids=["c0", "c3", "c5", "c8", "c9"])
+def test_int16_conv(case):
+    _say("int16 conv", case)
+    _int_conv_case(mb.INT16, *case, seed=2000 + 17 * CONV_CASES.index(case))
+
+
+def test_int8_conv_raw_accumulators():
+    _int_conv_case(mb.INT8, 2, 32, 9, 9, 64, 3, 3, 1, 1, 2, False, (0, 0), 3, 0, 0, seed=31, raw=True)
+    _int_conv_case(mb.INT8, 2, 20, 9, 9, 10, 3, 3, 1, 1, 1, False, (0, 0), 3, 2, 0, seed=32, raw=True)
+
+
+def test_conv_is_deterministic():
+    case = CONV_CASES[0]
+    N, C, H, W, K, R, S, stride, pad, groups = case[:10]
+    x = gen.integers(1, (N, C, H, W), -128, 127)
+    w = gen.integers(2, (K, C // groups, R, S), -127, 127)
+    desc = mb.conv_desc(C, K, R, S, stride, pad, groups, True)
+    xd = gu.codes_to_dev(x, mb.INT8)
+    wd = torch.from_numpy(w.astype(np.int8)).to("cuda")
+    a = gu.run_conv(xd, (0.02, 0), wd, (0.01, 0), None, desc, mb.INT8, (0.5, 0))
+    b = gu.run_conv(xd, (0.02, 0), wd, (0.01, 0), None, desc, mb.INT8, (0.5, 0))
+    assert torch.equal(a, b)
+
+
+# ---------------------------------------------------------------------------------------------
+# fp16 convolution
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("case", [CONV_CASES[i] for i in (0, 1, 2, 3, 5, 7, 8)],
+                         ids=["c0", "c1", "c2", "c3", "c5", "c7", "c8"])
+def test_fp16_conv(case):
+    _say("fp16 conv", case)
+    N, C, H, W, K, R, S, stride, pad, groups, relu, pool = case[:12]
+    seed = 3000 + 17 * CONV_CASES.index(case)
+    x = o.round_fp16(gen.normal(seed, (N, C, H, W)))
+    w = o.round_fp16(gen.normal(seed + 1, (K, C // groups, R, S), 0, float(np.sqrt(2.0 / (C // groups * R * S)))))
+    b = gen.normal(seed + 2, (K,), 0, 0.1).astype(np.float32)
+    desc = mb.conv_desc(C, K, R, S, stride, pad, groups, relu, pool[0], pool[1])
+    wd = torch.from_numpy(w.astype(np.float16)).to("cuda")
+    y = gu.run_conv(gu.half_to_dev(x), (1.0, 0), wd, (1.0, 0), torch.from_numpy(b).to("cuda"), desc, mb.FP16)
+    ref = o.conv2d_f64(x, w, b.astype(np.float64), stride, pad, groups, relu)
+    if pool[0]:
+        ref = o.maxpool_f64(ref, pool[0], pool[1])
+    gu.check_fp16(gu.to_nchw(y), ref, "fp16 conv")
+
+
+def test_fp16_conv_power_of_two_data_is_exact():
+    # sums of a few powers of two are exact in fp32 and representable in fp16: bit-exact result
+    N, C, H, W, K = 2, 16, 8, 8, 64
+    x = 2.0 ** gen.integers(5, (N, C, H, W), -3, 2).astype(np.float64)
+    w = 2.0 ** gen.integers(6, (K, C, 1, 1), -3, 0).astype(np.float64) * np.where(gen.integers(7, (K, C, 1, 1), 0, 1) > 0, 1, -1)
+    desc = mb.conv_desc(C, K, 1, 1, 1, 0, 1, False)
+    y = gu.run_conv(gu.half_to_dev(x), (1.0, 0), torch.from_numpy(w.astype(np.float16)).to("cuda"), (1.0, 0),
+                    None, desc, mb.FP16, out_dtype=mb.FP32)
+    ref = o.conv2d_f64(x, w)
+    assert np.array_equal(gu.to_nchw(y).astype(np.float64), ref)
+
+
+# ---------------------------------------------------------------------------------------------
+# fully connected
+# ---------------------------------------------------------------------------------------------
+FC_CASES = [  # M, K, N, relu, zx
+    (1, 4096, 1000, False, 0), (1, 1024, 4100, True, 0), (5, 800, 500, True, 4), (16, 2048, 2050, True, 0),
+    (256, 512, 384, True, 0), (100, 800, 500, True, -6), (64, 500, 10, False, 0), (256, 2304, 4, False, 0),
+    (3, 100, 7, False, 2),
+]
+
+
+@pytest.mark.parametrize("dtype", [mb.INT8, mb.INT16])
+@pytest.mark.parametrize("case", FC_CASES, ids=[f"f{i}" for i in range(len(FC_CASES))])
+def test_int_gemm(dtype, case):
+    _say("int gemm", dtype, case)
+    M, K, N, relu, zx = case
+    name = gu.NAME[dtype]
+    qmin, qmax = o.QRANGE[name]
+    seed = 4000 + 13 * FC_CASES.index(case)
+    x = gen.integers(seed, (M, K), qmin, qmax)
+    w = gen.integers(seed + 1, (N, K), -qmax, qmax)
+    b = gen.integers(seed + 2, (N,), -9000, 9000)
+    t = o.gemm_acc(x, zx, w, 0, b)
+    s_x, s_w = np.float32(0.02), np.float32(0.004)
+    s_y = np.float32(float(s_x) * float(s_w) * float(np.std(t)) * 3.0 / qmax)
+    xd = torch.from_numpy(x.astype(gu.NP_STORE[dtype])).to("cuda")
+    wd = torch.from_numpy(w.astype(gu.NP_STORE[dtype])).to("cuda")
+    bd = torch.from_numpy(b.astype(np.int32)).to("cuda")
+    y = gu.run_gemm(xd, (s_x, zx), wd, (s_w, 0), bd, relu, dtype, (s_y, 0))
+    mult, shift = o.scale_quant_vals(s_x, s_w, s_y, o.SHIFT_BITS[name])
+    ref = o.requant(t, mult, o.SHIFT_BITS[name], shift, 0, name, relu)
+    assert np.array_equal(y.cpu().numpy().astype(np.int32), ref)
+    if dtype == mb.INT8:      # raw accumulators (gating logits)
+        y = gu.run_gemm(xd, (s_x, zx), wd, (s_w, 0), bd, False, dtype, out_dtype=mb.INT32)
+        assert np.array_equal(y.cpu().numpy().astype(np.int64), t)
+
+
+def test_int16_gemm_accumulates_beyond_int32():
+    K = 4096
+    x = np.full((2, K), 32767, np.int64)
+    w = np.stack([np.full(K, 32767), np.full(K, -32768), np.full(K, 11)]).astype(np.int64)
+    t = o.gemm_acc(x, 0, w, 0)
+    assert abs(t).max() > 2 ** 31
+    s = (np.float32(1e-3), np.float32(1e-3), np.float32(400.0))
+    y = gu.run_gemm(torch.from_numpy(x.astype(np.int16)).to("cuda"), (s[0], 0),
+                    torch.from_numpy(w.astype(np.int16)).to("cuda"), (s[1], 0), None, False, mb.INT16, (s[2], 0))
+    mult, shift = o.scale_quant_vals(*s, 15)
+    ref = o.requant(t, mult, 15, shift, 0, "int16", False)
+    assert np.array_equal(y.cpu().numpy().astype(np.int32), ref)
+    assert abs(ref).max() < 32767
+
+
+@pytest.mark.parametrize("case", FC_CASES, ids=[f"f{i}" for i in range(len(FC_CASES))])
+def test_fp16_gemm(case):
+    _say("fp16 gemm", case)
+    M, K, N, relu, _ = case
+    seed = 5000 + 13 * FC_CASES.index(case)
+    x = o.round_fp16(np.abs(gen.normal(seed, (M, K))))
+    w = o.round_fp16(gen.normal(seed + 1, (N, K), 0, 0.01))
+    b = gen.normal(seed + 2, (N,), 0, 0.1).astype(np.float32)
+    y = gu.run_gemm(torch.from_numpy(x.astype(np.float16)).to("cuda"), (1.0, 0),
+                    torch.from_numpy(w.astype(np.float16)).to("cuda"), (1.0, 0),
+                    torch.from_numpy(b).to("cuda"), relu, mb.FP16)
+    ref = o.gemm_f64(x, w, b.astype(np.float64), relu)
+    gu.check_fp16(y.cpu().numpy(), ref, "fp16 gemm")
+
+
+# ---------------------------------------------------------------------------------------------
+# pooling
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [mb.INT8, mb.INT16, mb.FP16])
+@pytest.mark.parametrize("shape,k,s", [((2, 96, 55, 55), 3, 2), ((3, 20, 24, 24), 2, 2), ((1, 7, 5, 9), 3, 1)])
+def test_maxpool(dtype, shape, k, s):
+    N, C, H, W = shape
+    if dtype == mb.FP16:
+        x = o.round_fp16(gen.normal(3, shape))
+        xd = gu.half_to_dev(x)
+        ref = o.maxpool_f64(x, k, s)
+    else:
+        qmin, qmax = o.QRANGE[gu.NAME[dtype]]
+        x = gen.integers(3, shape, qmin, qmax)
+        xd = gu.codes_to_dev(x, dtype)
+        ref = o.maxpool_i32(x, k, s)
+    P, Q = (H - k) // s + 1, (W - k) // s + 1
+    y = torch.empty((N, P, Q, C), dtype=mb.TORCH_DTYPE[dtype], device="cuda")
+    mb.mpq_maxpool2d(mb.tensor(xd, dtype, N, H, W, C), mb.tensor(y, dtype, N, P, Q, C), k, s)
+    torch.cuda.synchronize()
+    assert np.array_equal(gu.to_nchw(y).astype(np.float64), ref.astype(np.float64))
+
+
+# ---------------------------------------------------------------------------------------------
+# empty batch and error paths that need a device pointer
+# ---------------------------------------------------------------------------------------------
+def test_empty_batch_is_a_noop():
+    desc = mb.conv_desc(16, 32, 3, 3, 1, 1, 1, True)
+    w = torch.zeros((32, 16, 3, 3), dtype=torch.int8, device="cuda")
+    packed = gu.pack(w, desc, mb.INT8)
+    xv = mb.tensor(None, mb.INT8, 0, 8, 8, 16, 0.1)
+    yv = mb.tensor(None, mb.INT8, 0, 8, 8, 32, 0.1)
+    mb.mpq_conv2d(xv, packed, 0.1, 0, None, yv, desc, None, 0)

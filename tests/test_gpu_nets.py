@@ -1,0 +1,219 @@
+"""GPU parity on the benchmark configurations: layer chains through the C ABI against the CPU
+oracle's chains on the same seeded inputs and the same calibrated scales."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import nets, oracle as o
+from paper_2209_15427_amd import binding as mb
+from paper_2209_15427_amd import pipeline as pl
+from tests import gpu_util as gu
+from workloads import calib, configs as cf, gen
+
+pytestmark = pytest.mark.gpu
+
+DT = {"int8": mb.INT8, "int16": mb.INT16, "fp16": mb.FP16}
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _chain_parity(specs, x, params, in_chw, dtype_name, s_in=None, scales=None):
+    dt = DT[dtype_name]
+    chain = pl.Chain(specs, params, dt, x.shape[0], in_chw, s_in or 1.0, scales)
+    y = chain.forward(chain.input_storage(x))
+    torch.cuda.synchronize()
+    outs_gpu = [pl.nhwc_to_nchw(a) for a in chain.acts]
+    if dtype_name == "fp16":
+        _, outs = nets.run_fp16_chain(specs, x, params, collect=True)
+        stats = []
+        # end to end: the device chain against the oracle chain.  One-ulp differences of earlier
+        # activations accumulate with depth, so the absolute slack grows with the layer index.
+        for i, (g, r) in enumerate(zip(outs_gpu, outs)):
+            stats.append(gu.check_fp16(g.reshape(r.shape), r, f"{specs[i].name} (chain)", gu.FLOOR_SAME_INPUT if i == 0 else 0.1 * i))
+        # layer by layer on identical inputs: layer i is fed the ORACLE's fp16-rounded layer i-1
+        # output, and must meet the single-layer bar
+        for i in range(1, len(specs)):
+            r_in = o.round_fp16(outs[i - 1])
+            xin = gu.half_to_dev(r_in)
+            g = pl.nhwc_to_nchw(chain.run_layer(i, xin))
+            torch.cuda.synchronize()
+            gu.check_fp16(g.reshape(outs[i].shape), outs[i], f"{specs[i].name} (layer)", gu.FLOOR_SAME_INPUT)
+        return stats
+    _, outs = nets.run_int_chain(specs, x, params, s_in, scales, dtype_name, collect=True)
+    for i, (g, r) in enumerate(zip(outs_gpu, outs)):
+        g = g.reshape(r.shape).astype(np.int32)
+        bad = np.argwhere(g != r)
+        assert bad.size == 0, f"{specs[i].name}: {len(bad)} mismatches of {r.size}, first {bad[0]}"
+        assert len(np.unique(r)) > 8, f"{specs[i].name}: degenerate output"
+    return None
+
+
+@pytest.mark.parametrize("dtype", ["int8", "int16", "fp16"])
+def test_lenet_batch64(dtype):
+    """Config 2: LeNet-shaped net, batch 64."""
+    _say("lenet", dtype)
+    x, params = cf.lenet_tensors(64)
+    sc = calib.load()["lenet"].get(dtype)
+    if dtype == "fp16":
+        _chain_parity(cf.LENET_LAYERS, x, params, cf.LENET_INPUT, dtype)
+    else:
+        _chain_parity(cf.LENET_LAYERS, x, params, cf.LENET_INPUT, dtype, sc["x"], sc["layers"])
+
+
+@pytest.mark.parametrize("dtype", ["int8", "int16", "fp16"])
+def test_alexnet_stack_batch2(dtype):
+    """Config 3 at a batch the oracle finishes in seconds: all five conv layers + pools."""
+    _say("alexnet batch 2", dtype)
+    x = cf.alexnet_input(2)
+    params = cf.alexnet_conv_params()
+    if dtype == "fp16":
+        _chain_parity(cf.ALEXNET_CONVS, x, params, cf.ALEXNET_INPUT, dtype)
+    else:
+        sc = calib.load()["alexnet"][dtype]
+        _chain_parity(cf.ALEXNET_CONVS, x, params, cf.ALEXNET_INPUT, dtype, sc["x"], sc["layers"])
+
+
+def test_alexnet_stack_batch1_int8():
+    _say("alexnet batch 1 int8")
+    sc = calib.load()["alexnet"]["int8"]
+    _chain_parity(cf.ALEXNET_CONVS, cf.alexnet_input(1), cf.alexnet_conv_params(), cf.ALEXNET_INPUT, "int8",
+                  sc["x"], sc["layers"])
+
+
+@pytest.mark.parametrize("dtype", ["int8", "int16", "fp16"])
+@pytest.mark.parametrize("batch", [1, 16])
+@pytest.mark.parametrize("layer", [0, 1, 2])
+def test_fc_layers(layer, batch, dtype):
+    """Config 4: AlexNet-shaped FC layers as standalone GEMMs (batch 256 is in the full-size test)."""
+    _say("fc", layer, batch, dtype)
+    L, x, w, b = cf.fc_case(layer, batch)
+    if dtype == "fp16":
+        _chain_parity([L], x, [(w, b)], (L.K, 1, 1), dtype)
+    else:
+        sc = calib.load()["fc"][L.name][dtype]
+        _chain_parity([L], x, [(w, b)], (L.K, 1, 1), dtype, sc["x"], sc["layers"])
+
+
+# ---------------------------------------------------------------------------------------------
+# mixture of experts
+# ---------------------------------------------------------------------------------------------
+def _moe_device(x_codes_nchw, s_x, logits, layers, params_q, scales, dtype, logits_dtype):
+    """params_q[e][i] = (w codes logical layout, bias codes); everything uploaded and packed per
+    expert into one buffer per layer with a uniform stride."""
+    E = len(params_q)
+    B, Cc, H, W = x_codes_nchw.shape
+    xd = gu.codes_to_dev(x_codes_nchw, dtype) if dtype != mb.FP16 else gu.half_to_dev(x_codes_nchw)
+    keep, mls = [], []
+    shape = (H, W, Cc)
+    for i, L in enumerate(layers):
+        if L.kind == "fc":
+            desc = mb.gemm_desc(L.K, L.N, L.relu)
+            kout = L.N
+        else:
+            desc = mb.conv_desc(L.C, L.K, L.R, L.S, L.stride, L.pad, L.groups, L.relu, L.pool_k, L.pool_s)
+            kout = L.K
+        nbytes = mb.mpq_packed_weight_bytes(desc, dtype)
+        stride = (nbytes + 255) // 256 * 256
+        packed = pl.alloc_bytes(stride * E)
+        bias_all = []
+        for e in range(E):
+            w, b = params_q[e][i]
+            w = np.asarray(w)
+            if L.kind == "fc":
+                if len(shape) == 3 and (shape[0] > 1 or shape[1] > 1):     # (c,h,w) columns -> (h,w,c)
+                    h_, w_, c_ = shape
+                    w = w.reshape(L.N, c_, h_, w_).transpose(0, 2, 3, 1).reshape(L.N, -1)
+                w = w.reshape(L.N, L.K, 1, 1)
+            npdt = np.float16 if dtype == mb.FP16 else gu.NP_STORE[dtype]
+            wd = torch.from_numpy(np.ascontiguousarray(w.astype(npdt))).to("cuda")
+            mb.mpq_pack_weights(wd, desc, dtype, packed[e * stride:], nbytes)
+            bias_all.append(np.asarray(b))
+        bnp = np.stack(bias_all)
+        bias = torch.from_numpy(bnp.astype(np.float32 if dtype == mb.FP16 else np.int32)).to("cuda")
+        wq = (mb.QParams * E)(*[mb.QParams(float(scales[e][i]["w"]), 0) for e in range(E)])
+        yq = (mb.QParams * E)(*[mb.QParams(float(scales[e][i]["y"]), 0) for e in range(E)])
+        keep += [packed, bias, wq, yq]
+        mls.append(mb.MoeLayer(desc, int(L.kind == "fc"), packed.data_ptr(), stride, bias.data_ptr(), wq, yq))
+        if L.kind == "fc":
+            shape = (1, 1, L.N)
+        else:
+            P, Q = L.out_hw(shape[0], shape[1])
+            if L.pool_k:
+                P, Q = (P - L.pool_k) // L.pool_s + 1, (Q - L.pool_k) // L.pool_s + 1
+            shape = (P, Q, L.K)
+    lg = torch.from_numpy(np.ascontiguousarray(logits)).to(torch.int32 if logits_dtype == mb.INT32 else torch.float32).to("cuda")
+    xv = mb.tensor(xd, dtype, B, H, W, Cc, s_x)
+    y = torch.full((B,) + shape, 55, dtype=mb.TORCH_DTYPE[dtype], device="cuda")
+    yv = mb.tensor(y, dtype, B, *shape)
+    nws = mb.mpq_moe_workspace_bytes(xv, E, mls)
+    ws = pl.alloc_bytes(nws)
+    idx = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((E,), -1, dtype=torch.int32, device="cuda")
+    mb.mpq_moe_forward(xv, lg, logits_dtype, E, 1, mls, yv, idx, cnt, ws, nws)
+    torch.cuda.synchronize()
+    return y, idx.cpu().numpy(), cnt.cpu().numpy()
+
+
+def _tiny_moe_case(dtype_name, B, seed):
+    layers = [cf.Conv("c", 64, 32, 3, 3, pad=1, groups=2, pool_k=3, pool_s=2), cf.FC("f", 40, 64 * 3 * 3)]
+    E = 3
+    qmax = 127 if dtype_name == "int8" else 32767
+    params, scales = [], []
+    for e in range(E):
+        ps = [(gen.integers(seed + e, (64, 16, 3, 3), -qmax, qmax), gen.integers(seed + 10 + e, (64,), -300, 300)),
+              (gen.integers(seed + 20 + e, (40, 576), -qmax, qmax), gen.integers(seed + 30 + e, (40,), -300, 300))]
+        params.append(ps)
+        f = (127.0 / qmax) ** 2
+        scales.append([{"w": 0.01 * f ** 0.5, "b": 1.0, "y": (6.0 + e) * 127.0 / qmax},
+                       {"w": 0.02 * f ** 0.5, "b": 1.0, "y": (40.0 + 3 * e) * 127.0 / qmax}])
+    x = gen.integers(seed + 40, (B, 32, 7, 7), -qmax - 1, qmax)
+    return layers, params, scales, x, E
+
+
+@pytest.mark.parametrize("dtype", ["int8", "int16"])
+@pytest.mark.parametrize("B", [1, 37, 300])
+def test_moe_small_int(dtype, B):
+    _say("moe small", dtype, B)
+    layers, params, scales, x, E = _tiny_moe_case(dtype, B, 700)
+    s_x = 0.02 * 127.0 / (127 if dtype == "int8" else 32767)
+    logits = gen.integers(5, (B, E), -1000, 1000)
+    if B >= 4:
+        logits[1] = logits[1, 0]          # a three-way tie: lowest index wins
+        logits[2, 1:] = logits[2, 2]      # tie between experts 1 and 2
+    y, idx, cnt = _moe_device(x, s_x, logits, layers, params, scales, DT[dtype], mb.INT32)
+    ref, e_ref, c_ref = nets.moe_int(x, s_x, logits.astype(np.float64), layers, params, scales, dtype)
+    assert np.array_equal(idx, e_ref) and np.array_equal(cnt, c_ref) and cnt.sum() == B
+    got = y.cpu().numpy().reshape(ref.shape).astype(np.int32)
+    assert np.array_equal(got, ref)
+    assert len(np.unique(ref)) > 8
+
+
+def test_moe_all_to_one_expert_and_empty_experts():
+    layers, params, scales, x, E = _tiny_moe_case("int8", 20, 800)
+    logits = gen.integers(6, (20, E), -50, 50)
+    logits[:, 2] += 1000
+    y, idx, cnt = _moe_device(x, 0.02, logits, layers, params, scales, mb.INT8, mb.INT32)
+    assert list(cnt) == [0, 0, 20] and (idx == 2).all()
+    ref, _, _ = nets.moe_int(x, 0.02, logits.astype(np.float64), layers, params, scales, "int8")
+    assert np.array_equal(y.cpu().numpy().reshape(ref.shape).astype(np.int32), ref)
+
+
+def test_moe_small_fp16():
+    layers = [cf.Conv("c", 64, 32, 3, 3, pad=1, groups=2, pool_k=3, pool_s=2), cf.FC("f", 40, 64 * 3 * 3)]
+    E, B = 4, 50
+    params = []
+    for e in range(E):
+        params.append([(o.round_fp16(gen.normal(900 + e, (64, 16, 3, 3), 0, 0.1)), gen.normal(910 + e, (64,), 0, 0.1).astype(np.float32)),
+                       (o.round_fp16(gen.normal(920 + e, (40, 576), 0, 0.05)), gen.normal(930 + e, (40,), 0, 0.1).astype(np.float32))])
+    x = o.round_fp16(gen.normal(940, (B, 32, 7, 7)))
+    logits = gen.normal(941, (B, E)).astype(np.float32)
+    scales = [[{"w": 1.0, "y": 1.0}] * 2] * E
+    y, idx, cnt = _moe_device(x, 1.0, logits, layers, params, scales, mb.FP16, mb.FP32)
+    p64 = [[(w, b.astype(np.float64)) for (w, b) in ps] for ps in params]
+    ref, e_ref, c_ref = nets.moe_fp16(x, logits.astype(np.float64), layers, p64)
+    assert np.array_equal(idx, e_ref) and np.array_equal(cnt, c_ref)
+    gu.check_fp16(y.cpu().numpy().reshape(ref.shape), ref, "moe fp16", 0.1)

@@ -1,0 +1,133 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares, and
+rejects bad arguments on the host before anything would be launched (no compute calls here)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import oracle as o
+from paper_2209_15427_amd import binding as mb
+from workloads import gen
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000   # a non-null, 256-aligned "device address": never dereferenced by the host checks
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "mpq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(mpq_[a-z0-9_]+)\s*\(", text))
+    assert declared, "no declarations parsed"
+    L = mb.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(mb.EXPORTS)
+    assert L.mpq_abi_version() == 1
+    assert L.mpq_status_string(0) == b"ok" and L.mpq_status_string(4).startswith(b"workspace")
+
+
+def test_scale_quant_vals_matches_oracle():
+    rng = gen.uniform(5, (300, 3), 1e-4, 3.0)
+    for sa, sw, sy in rng:
+        for dt, sb in ((mb.INT8, 31), (mb.INT16, 15)):
+            assert mb.mpq_scale_quant_vals(np.float32(sa), np.float32(sw), np.float32(sy), dt) == \
+                o.scale_quant_vals(sa, sw, sy, sb)
+    assert mb.mpq_scale_quant_vals(0.02, 0.01, 0.05, mb.INT8) == o.scale_quant_vals(0.02, 0.01, 0.05, 31)
+    for bad in [(0.0, 1.0, 1.0), (1.0, -1.0, 1.0), (1.0, 1.0, float("nan")), (float("inf"), 1.0, 1.0)]:
+        with pytest.raises(mb.MpqError) as e:
+            mb.mpq_scale_quant_vals(*bad, mb.INT8)
+        assert e.value.status == 1
+    with pytest.raises(mb.MpqError) as e:      # ratio >= 2^15
+        mb.mpq_scale_quant_vals(1000.0, 1000.0, 1.0, mb.INT8)
+    assert e.value.status == 3
+
+
+def _status(fn, *a, **k):
+    try:
+        fn(*a, **k)
+    except mb.MpqError as e:
+        return e.status
+    return 0
+
+
+def test_quantize_argument_errors():
+    assert _status(mb.mpq_quantize, FAKE, FAKE, 0, mb.INT8, 0.1, 0) == 0            # empty: no-op
+    assert _status(mb.mpq_quantize, None, FAKE, 4, mb.INT8, 0.1, 0) == 1
+    assert _status(mb.mpq_quantize, FAKE, FAKE, 4, mb.FP16, 0.1, 0) == 1
+    assert _status(mb.mpq_quantize, FAKE, FAKE, 4, mb.INT8, 0.0, 0) == 1
+    assert _status(mb.mpq_quantize, FAKE, FAKE, 4, mb.INT8, float("nan"), 0) == 1
+    assert _status(mb.mpq_quantize, FAKE, FAKE, 4, mb.INT8, 0.1, 200) == 1           # zero-point out of int8
+    assert _status(mb.mpq_dequantize, FAKE, None, 4, mb.INT16, 0.1, 0) == 1
+
+
+def test_conv_argument_errors():
+    d = mb.conv_desc(16, 32, 3, 3, 1, 1, 1, True)
+    x = mb.tensor(FAKE, mb.INT8, 2, 8, 8, 16, 0.1, 0)
+    y = mb.tensor(FAKE + 4096, mb.INT8, 2, 8, 8, 32, 0.1, 0)
+    call = lambda x=x, y=y, d=d, w=FAKE, ws=None, wsb=0, wsc=0.1: _status(mb.mpq_conv2d, x, w, wsc, 0, None, y, d, ws, wsb)
+    assert call(w=None) == 1
+    assert call(x=mb.tensor(FAKE, mb.INT8, 2, 8, 8, 8, 0.1, 0)) == 2                 # channels != desc
+    assert call(y=mb.tensor(FAKE + 4096, mb.INT8, 2, 8, 8, 31, 0.1, 0)) == 2         # wrong output channels
+    assert call(y=mb.tensor(FAKE + 4096, mb.INT8, 2, 7, 8, 32, 0.1, 0)) == 2         # wrong output height
+    assert call(y=mb.tensor(FAKE + 4096, mb.INT16, 2, 8, 8, 32, 0.1, 0)) == 3        # mixed storage types
+    assert call(y=mb.tensor(FAKE, mb.INT8, 2, 8, 8, 32, 0.1, 0)) == 1                # in place
+    assert call(x=mb.tensor(FAKE, mb.INT8, 2, 8, 8, 16, -1.0, 0)) == 1               # bad scale
+    assert call(x=mb.tensor(FAKE, mb.INT8, 2, 8, 8, 16, 0.1, 300)) == 1              # bad zero-point
+    assert call(wsc=0.0) == 1
+    assert call(d=mb.conv_desc(16, 32, 3, 3, 1, 1, 3, True)) == 1                    # c % groups
+    assert call(d=mb.conv_desc(16, 32, 3, 3, 0, 1, 1, True)) == 1                    # stride 0
+    assert call(x=mb.tensor(FAKE, mb.FP32, 2, 8, 8, 16)) == 1                        # unsupported input type
+    # kernel larger than the padded image
+    assert _status(mb.mpq_conv2d, mb.tensor(FAKE, mb.INT8, 1, 2, 2, 16, 0.1), FAKE, 0.1, 0, None,
+                   mb.tensor(FAKE + 4096, mb.INT8, 1, 1, 1, 32, 0.1), mb.conv_desc(16, 32, 7, 7), None, 0) == 2
+    # pooled layer without its workspace
+    dp = mb.conv_desc(16, 32, 3, 3, 1, 1, 1, True, 2, 2)
+    yp = mb.tensor(FAKE + 4096, mb.INT8, 2, 4, 4, 32, 0.1, 0)
+    assert mb.mpq_conv2d_workspace_bytes(x, dp) >= 2 * 8 * 8 * 32
+    assert call(y=yp, d=dp) == 4
+    assert call(y=yp, d=dp, ws=FAKE + 8192, wsb=16) == 4
+    # scale ratio beyond the supported left shift
+    assert call(x=mb.tensor(FAKE, mb.INT8, 2, 8, 8, 16, 1000.0, 0), wsc=1000.0) == 3
+
+
+def test_pack_and_pool_argument_errors():
+    d = mb.conv_desc(16, 32, 3, 3, 1, 1, 1, True)
+    n = mb.mpq_packed_weight_bytes(d, mb.INT8)
+    assert n >= 32 * 16 * 9 + 32 * 4 and n % 256 == 0
+    assert mb.mpq_packed_weight_bytes(d, mb.FP32) == 0
+    assert _status(mb.mpq_pack_weights, FAKE, d, mb.INT8, FAKE + 4096, n - 1) == 4
+    assert _status(mb.mpq_pack_weights, FAKE, d, mb.INT8, FAKE + 4100, n) == 4       # misaligned
+    assert _status(mb.mpq_pack_weights, None, d, mb.INT8, FAKE + 4096, n) == 1
+    x = mb.tensor(FAKE, mb.INT8, 1, 8, 8, 16)
+    assert _status(mb.mpq_maxpool2d, x, mb.tensor(FAKE + 4096, mb.INT8, 1, 4, 4, 16), 3, 2) == 2
+    assert _status(mb.mpq_maxpool2d, x, mb.tensor(FAKE + 4096, mb.INT16, 1, 3, 3, 16), 3, 2) == 3
+    assert _status(mb.mpq_maxpool2d, x, mb.tensor(FAKE + 4096, mb.INT8, 1, 3, 3, 16), 0, 2) == 1
+
+
+def test_gemm_desc_and_shape_errors():
+    d = mb.gemm_desc(800, 500, True)
+    assert (d.c, d.k, d.r, d.s, d.groups, d.relu, d.stride_h) == (800, 500, 1, 1, 1, 1, 1)
+    x = mb.tensor(FAKE, mb.INT8, 4, 1, 1, 800, 0.1)
+    assert _status(mb.mpq_gemm, mb.tensor(FAKE, mb.INT8, 4, 2, 1, 800, 0.1), FAKE, 0.1, 0, None,
+                   mb.tensor(FAKE + 8192, mb.INT8, 4, 1, 1, 500, 0.1), True) == 2
+    assert _status(mb.mpq_gemm, x, FAKE, 0.1, 0, None, mb.tensor(FAKE + 8192, mb.INT8, 5, 1, 1, 500, 0.1), True) == 2
+
+
+def test_moe_argument_errors():
+    d = mb.gemm_desc(64, 32, True)
+    q = (mb.QParams * 2)(mb.QParams(0.1, 0), mb.QParams(0.1, 0))
+    layer = mb.MoeLayer(d, 1, FAKE, 4096, None, q, q)
+    x = mb.tensor(FAKE, mb.INT8, 8, 2, 2, 16, 0.1)
+    y = mb.tensor(FAKE + 65536, mb.INT8, 8, 1, 1, 32, 0.1)
+    assert mb.mpq_moe_workspace_bytes(x, 2, [layer]) > 0
+    assert _status(mb.mpq_moe_forward, x, FAKE, mb.INT32, 2, 2, [layer], y) == 3          # top_k != 1
+    assert _status(mb.mpq_moe_forward, x, None, mb.INT32, 2, 1, [layer], y) == 1
+    assert _status(mb.mpq_moe_forward, x, FAKE, mb.INT8, 2, 1, [layer], y) == 1           # logits dtype
+    assert _status(mb.mpq_moe_forward, x, FAKE, mb.INT32, 2, 1, [layer], y) == 4          # no workspace
+    assert _status(mb.mpq_moe_forward, x, FAKE, mb.INT32, 99, 1, [layer], y) == 3         # too many experts
+    ybad = mb.tensor(FAKE + 65536, mb.INT8, 8, 1, 1, 31, 0.1)
+    assert _status(mb.mpq_moe_forward, x, FAKE, mb.INT32, 2, 1, [layer], ybad, ws=FAKE + (1 << 20), ws_bytes=1 << 20) == 2
+    small = mb.MoeLayer(d, 1, FAKE, 256, None, q, q)                                      # expert stride too small
+    assert _status(mb.mpq_moe_forward, x, FAKE, mb.INT32, 2, 1, [small], y) == 4
