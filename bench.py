@@ -1,0 +1,274 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-precision inference hot path on one MI355X.
+
+Headline workload (benchmark configs[2]): the AlexNet-shaped convolution stack at batch 256
+in int8 -- one "step" = quantize the fp32 NHWC input batch to int8, then conv1..conv5 with fused
+bias + ReLU + requantize and the three 3x3/2 max-pools, all through the libmpq C ABI, with the
+input batch already resident in HBM.  value = algorithmic int8 TOP/s of the convolutions
+(2 * 340.9 G MAC per step) over the whole step time; images/s is reported beside it.
+
+Also reported in the same JSON line: per-layer times, the roofline of the dominant kernel, the
+memory-bound batch-1 FC layers (cold weights: a rotation of copies larger than the 256 MB
+Infinity Cache), the MoE stage, and the CPU oracle timed on the host cores (a baseline, not a
+target).  Synthetic seeded inputs; nothing is read from outside the repository.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--dtype", default="int8", choices=["int8", "fp16", "int16"])
+    ap.add_argument("--eager", action="store_true", help="issue every call from the host instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the FC / MoE side measurements")
+    ap.add_argument("--cpu-images", type=int, default=256, help="images the oracle is timed on")
+    return ap.parse_args()
+
+
+PEAK = {"int8": 5000.0, "fp16": 2500.0, "int16": 1250.0}   # dense MFMA, TOP/s (int16: int8 peak / 4)
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path has no cross-GPU step; it shards by "
+              "batch with replicated weights). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2209_15427_amd import binding as mb
+    from paper_2209_15427_amd import pipeline as pl
+    from workloads import calib, configs as cf
+
+    mb.lib()    # fails loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    dt = mb.DTYPE_ID[args.dtype]
+    B = args.batch
+
+    # ---- inputs: seeded synthetic batch, fp32 NHWC, resident in HBM --------------------------
+    x_real = cf.alexnet_input(B)                                     # N,C,H,W fp64
+    x_dev = torch.from_numpy(np.ascontiguousarray(x_real.transpose(0, 2, 3, 1).astype(np.float32))).to("cuda")
+    params = cf.alexnet_conv_params()
+    if args.dtype == "fp16":
+        chain = pl.Chain(cf.ALEXNET_CONVS, params, dt, B, cf.ALEXNET_INPUT)
+    else:
+        sc = calib.load()["alexnet"][args.dtype]
+        chain = pl.Chain(cf.ALEXNET_CONVS, params, dt, B, cf.ALEXNET_INPUT, sc["x"], sc["layers"])
+    x_store = torch.empty(x_dev.shape, dtype=mb.TORCH_DTYPE[dt], device="cuda")
+    n_in = x_dev.numel()
+
+    def step():
+        if dt == mb.FP16:
+            mb.mpq_to_fp16(x_dev, x_store, n_in)
+        else:
+            mb.mpq_quantize(x_dev, x_store, n_in, dt, chain.s_in, 0)
+        return chain.forward(x_store)
+
+    H, W = cf.ALEXNET_INPUT[1:]
+    macs_layer, hw = [], (H, W)
+    for L in cf.ALEXNET_CONVS:
+        macs_layer.append(L.macs(*hw))
+        P, Q = L.out_hw(*hw)
+        if L.pool_k:
+            P, Q = (P - L.pool_k) // L.pool_s + 1, (Q - L.pool_k) // L.pool_s + 1
+        hw = (P, Q)
+    macs_img = sum(macs_layer)
+
+    # The step is ~10 short kernel launches; replaying it as a HIP graph keeps host launch
+    # latency out of the measurement (--eager issues the calls one by one instead).
+    y_eager = step().clone()
+    torch.cuda.synchronize()
+    if args.eager:
+        run_step = step
+    else:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            y_graph = step()
+        run_step = graph.replay
+        for _ in range(3):          # every replay must reproduce the eager result
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y_graph, y_eager), "graph replay differs from eager execution"
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    tops = 2.0 * macs_img * B / (ms_step * 1e-3) / 1e12
+    img_s = B / (ms_step * 1e-3)
+
+    # ---- per-call timing with events on the launch stream ----------------------------------
+    def time_call(fn, iters=10, reps=10):
+        return graph_time(torch, fn, iters, reps)
+
+    layer_us = {}
+    if dt == mb.FP16:
+        layer_us["convert_in"] = time_call(lambda: mb.mpq_to_fp16(x_dev, x_store, n_in))
+    else:
+        layer_us["quantize_in"] = time_call(lambda: mb.mpq_quantize(x_dev, x_store, n_in, dt, chain.s_in, 0))
+    ins = [x_store] + chain.acts[:-1]
+    for i, L in enumerate(cf.ALEXNET_CONVS):
+        layer_us[L.name] = time_call(lambda i=i: chain.run_layer(i, ins[i]))
+
+    # ---- dominant kernel: the convolution kernel of the slowest layer, timed alone -----------
+    # (same kernel, same launch shape; a layer with a fused pool is re-issued without its pool so
+    # that the events bracket exactly one kernel)
+    conv_only_us = {}
+    for i, L in enumerate(cf.ALEXNET_CONVS):
+        if L.name == "conv1":
+            continue      # conv1's call also runs the channel-padding copy; it is never dominant
+        lay = chain.layers[i]
+        n, h, w_, c = ins[i].shape
+        d = mb.conv_desc(L.C, L.K, L.R, L.S, L.stride, L.pad, L.groups, L.relu, 0, 0)
+        P, Q = L.out_hw(h, w_)
+        tmp = torch.empty((n, P, Q, L.K), dtype=mb.TORCH_DTYPE[dt], device="cuda")
+        s_x = chain.s_in if i == 0 else chain.layers[i - 1].y_scale
+        xv = mb.tensor(ins[i], dt, n, h, w_, c, s_x)
+        yv = mb.tensor(tmp, dt, n, P, Q, L.K, lay.y_scale)
+        conv_only_us[L.name] = time_call(lambda: mb.mpq_conv2d(xv, lay.packed, lay.w_scale, 0, lay.bias, yv, d, None, 0))
+    dom = max(conv_only_us, key=conv_only_us.get)
+    dom_i = [L.name for L in cf.ALEXNET_CONVS].index(dom)
+    dom_ops = 2.0 * macs_layer[dom_i] * B
+    dom_achieved = dom_ops / (conv_only_us[dom] * 1e-6) / 1e12
+    roofline = {"bound": "mfma", "kernel": f"conv_mfma_kernel ({dom}, batch {B}, {args.dtype})",
+                "achieved": round(dom_achieved, 2), "peak": PEAK[args.dtype], "unit": "TFLOP/s" if dt == mb.FP16 else "TOP/s",
+                "frac": round(dom_achieved / PEAK[args.dtype], 4), "traffic": None,
+                "kernel_us": round(conv_only_us[dom], 2)}
+
+    out = {
+        "metric": f"{args.dtype} conv TOPS + images/s (AlexNet-shape conv stack, batch {B})",
+        "value": round(tops, 3), "unit": "TFLOP/s" if dt == mb.FP16 else "TOP/s",
+        "images_per_s": round(img_s, 1),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"int8": "int8 (int32 acc)", "fp16": "fp16 (fp32 acc)", "int16": "int16 (int64 acc)"}[args.dtype],
+        "data": "synthetic",
+        "config": {"workload": f"alexnet_conv_stack_b{B}_{args.dtype}: quantize + conv1..conv5 + 3 max-pools, NHWC",
+                   "batch": B, "input": "3x227x227 N(0,1), seeded", "gop_per_image": round(2 * macs_img / 1e9, 4)},
+        "frac_of_mfma_peak": round(tops / PEAK[args.dtype], 4),
+        "layer_us": {k: round(v, 1) for k, v in layer_us.items()},
+        "conv_kernel_us": {k: round(v, 1) for k, v in conv_only_us.items()},
+        "conv_kernel_tops": {k: round(2.0 * macs_layer[[L.name for L in cf.ALEXNET_CONVS].index(k)] * B / (v * 1e-6) / 1e12, 1)
+                             for k, v in conv_only_us.items()},
+        "roofline": roofline,
+    }
+
+    if not args.no_extras:
+        out["fc_batch1"] = bench_fc(torch, mb, pl, cf, calib, args.dtype)
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cf, calib, args.dtype, args.cpu_images, macs_img)
+
+    print(json.dumps(out))
+
+
+def graph_time(torch, fn, iters=10, reps=10):
+    """Average duration (microseconds) of fn()'s device work: reps calls are captured into one HIP
+    graph, the graph is replayed iters times between two events on the launch stream."""
+    fn()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(reps):
+            fn()
+    g.replay()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        g.replay()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e3 / (iters * reps)
+
+
+def bench_fc(torch, mb, pl, cf, calib, dtype_name):
+    """Batch-1 FC layers, cold weights: every launch reads a different copy of the packed
+    weights, the copies together exceeding the 256 MB Infinity Cache."""
+    dt = mb.DTYPE_ID[dtype_name]
+    res = {}
+    for li, L in enumerate(cf.ALEXNET_FCS):
+        _, x, w, b = cf.fc_case(li, 1)
+        if dtype_name == "fp16":
+            lay = pl.Layer(L, w, b, dt)
+            s_x = 1.0
+        else:
+            sc = calib.load()["fc"][L.name][dtype_name]
+            lay = pl.Layer(L, w, b, dt, sc["layers"][0])
+            s_x = sc["x"]
+        xs = pl.to_storage(x, dt, s_x, 0)
+        es = 1 if dtype_name == "int8" else 2
+        wbytes = L.N * L.K * es
+        copies = max(2, int(320e6 // lay.packed_bytes) + 1)
+        stride = (lay.packed_bytes + 255) // 256 * 256
+        big = pl.alloc_bytes(stride * copies)
+        for c in range(copies):
+            big[c * stride:c * stride + lay.packed_bytes].copy_(lay.packed[:lay.packed_bytes])
+        y = torch.empty((1, L.N), dtype=mb.TORCH_DTYPE[dt], device="cuda")
+        xv = mb.tensor(xs, dt, 1, 1, 1, L.K, s_x)
+        yv = mb.tensor(y, dt, 1, 1, 1, L.N, lay.y_scale)
+        ptrs = [big.data_ptr() + c * stride for c in range(copies)]
+
+        def run(c):
+            mb.mpq_gemm(xv, ptrs[c], lay.w_scale, 0, lay.bias, yv, L.relu, None, 0)
+
+        # cold: one graph walks all copies once (> 256 MB of distinct weights per replay)
+        state = {"c": 0}
+
+        def run_next():
+            run(state["c"] % copies)
+            state["c"] += 1
+
+        cold_us = graph_time(torch, run_next, iters=5, reps=copies)
+        # warm: the same copy every time (fits the cache)
+        warm_us = graph_time(torch, lambda: run(0), iters=5, reps=20)
+        res[L.name] = {"weight_MB": round(wbytes / 1e6, 2), "cold_us": round(cold_us, 2),
+                       "cold_GBs": round(wbytes / cold_us / 1e3, 1),
+                       "cold_frac_hbm": round(wbytes / cold_us / 1e3 / HBM_PEAK_GBS, 4),
+                       "warm_us": round(warm_us, 2), "warm_GBs": round(wbytes / warm_us / 1e3, 1)}
+        del big
+    return res
+
+
+def cpu_baseline(cf, calib, dtype_name, images, macs_img):
+    """The CPU oracle, as it stands, on `images` images of the same batch (images are
+    independent, so throughput per image does not depend on the batch size)."""
+    from oracle import nets, oracle as o
+
+    x = cf.alexnet_input(images)
+    params = cf.alexnet_conv_params()
+    threads = o.max_threads()
+    t0 = time.perf_counter()
+    if dtype_name == "fp16":
+        nets.run_fp16_chain(cf.ALEXNET_CONVS, x, params)
+    else:
+        sc = calib.load()["alexnet"][dtype_name]
+        nets.run_int_chain(cf.ALEXNET_CONVS, x, params, sc["x"], sc["layers"], dtype_name)
+    dt = time.perf_counter() - t0
+    return {"value": round(2.0 * macs_img * images / dt / 1e12, 5), "unit": "TOP/s", "images_per_s": round(images / dt, 3),
+            "cores": threads, "kind": "oracle",
+            "sample": f"{images} images of the batch through quantize + conv1..conv5 + pools ({dt:.1f} s)"}
+
+
+if __name__ == "__main__":
+    main()

@@ -220,7 +220,10 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     if (seg && seg->w_stride % 256 != 0) use_mfma = false;
 
     hipError_t err = hipSuccess;
-    if (use_mfma) {
+    if (!seg && gemv_eligible(a)) {
+        // batch <= 16 (or <= 16 outputs): memory-bound, one pass over the larger matrix
+        err = launch_gemv(a, st);
+    } else if (use_mfma) {
         a.ksteps = (int)((size_t)pl.Kp * pl.esize / kStepBytes);
         a.cpt = pl.tap_elems * pl.esize / kChunkBytes;
         a.nchunks = pl.taps * a.cpt;
@@ -241,8 +244,6 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
             a.tap_px = 1;
         }
         err = launch_conv_mfma(a, st);
-    } else if (!seg && gemv_eligible(a)) {
-        err = launch_gemv(a, st);
     } else {
         err = launch_conv_generic(a, st);
     }
