@@ -227,6 +227,9 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
         a.ksteps = (int)((size_t)pl.Kp * pl.esize / kStepBytes);
         a.cpt = pl.tap_elems * pl.esize / kChunkBytes;
         a.nchunks = pl.taps * a.cpt;
+        a.y_vec16 = (((size_t)d.k * dtype_size(y_dtype)) % 16 == 0 && ((size_t)pl.Kg * dtype_size(y_dtype)) % 16 == 0 &&
+                     aligned16(conv_out)) ? 1 : 0;
+        a.phased = (pl.mode == kModeTap && a.cpt % 4 == 0 && a.cpt > 4 && pl.taps > 1) ? 1 : 0;
         unsigned zb = (unsigned)(epi.zx & 0xff);
         a.fill_word = x.dtype == MPQ_INT8 ? zb * 0x01010101u : 0u;
         if (pl.mode == kModeRow) {
@@ -243,7 +246,8 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
             a.s_eff = d.s;
             a.tap_px = 1;
         }
-        err = launch_conv_mfma(a, st);
+        a.x_bytes = (unsigned long long)a.N * a.H * a.W * a.C * pl.esize;
+        err = conv_mfma_dma_eligible(a) ? launch_conv_mfma_dma(a, st) : launch_conv_mfma(a, st);
     } else {
         err = launch_conv_generic(a, st);
     }
@@ -280,8 +284,6 @@ mpq_status check_conv_args(const mpq_tensor *x, const void *w_packed, const mpq_
 }
 
 }  // namespace
-
-bool mfma_eligible(const Plan &, const mpq_conv_desc &, int, const Epi &, int) { return false; }
 
 }  // namespace mpq
 

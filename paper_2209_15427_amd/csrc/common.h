@@ -95,14 +95,16 @@ struct ConvArgs {
     int ksteps;            // 64-byte steps along the packed reduction axis
     int tap_px;            // input pixels one tap spans (1, or the padded row length in row mode)
     int ptiles;            // pixel tiles in the grid (filled by the launcher)
+    int y_vec16;           // output rows and channel-tile origins are 16-byte aligned
+    int phased;            // walk the reduction axis channel block by channel block (see conv_mfma_dma.hip)
     unsigned fill_word;    // the input zero-point replicated over 32 bits (out-of-image taps)
+    unsigned long long x_bytes;   // size of the input tensor the kernel sees
     Plan plan;
     Epi epi;
     SegTable seg;
 };
 
 Plan make_plan(const mpq_conv_desc &d, int dtype, int in_w);
-bool mfma_eligible(const Plan &p, const mpq_conv_desc &d, int dtype, const Epi &e, int x_c);
 
 // launchers (each returns the hipError_t of its launch)
 hipError_t launch_quantize(const float *src, void *dst, size_t n, int dtype, float scale, int zp,
@@ -119,6 +121,8 @@ hipError_t launch_maxpool(const void *x, void *y, int N, int H, int W, int C, in
                           hipStream_t st);
 hipError_t launch_conv_generic(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
+bool conv_mfma_dma_eligible(const ConvArgs &a);
+hipError_t launch_conv_mfma_dma(const ConvArgs &a, hipStream_t st);
 bool gemv_eligible(const ConvArgs &a);
 hipError_t launch_gemv(const ConvArgs &a, hipStream_t st);
 

@@ -23,4 +23,23 @@ __device__ __forceinline__ int requant64(long long t, const Epi &e) {
     return (int)y;
 }
 
+// The same rule for an int32 accumulator with sb = 31 (8-bit storage), in 32-bit arithmetic:
+// t * mult is formed as a (high, low) pair; floor(p / 2^31) = (high << 1) | (low >> 31), and the
+// truncation adds one back when p is negative with a non-zero remainder.  |y| <= |t| fits int32.
+__device__ __forceinline__ int requant32(int t, const Epi &e) {
+    if (e.shift < 0 || e.sb != 31) return requant64((long long)t, e);
+    const int mult = (int)e.mult;
+    const int hi = __mulhi(t, mult);
+    const unsigned lo = (unsigned)t * (unsigned)mult;
+    int y = (int)(((unsigned)hi << 1) | (lo >> 31));
+    y += (hi < 0 && (lo & 0x7fffffffu) != 0u) ? 1 : 0;
+    const int sh = e.shift > 31 ? 31 : e.shift;
+    y >>= sh;
+    // clamp before adding the zero-point: the bounds are small, y may be anywhere in int32
+    const int lo_b = e.lo - e.zy, hi_b = e.hi - e.zy;
+    y = y < lo_b ? lo_b : y;
+    y = y > hi_b ? hi_b : y;
+    return y + e.zy;
+}
+
 }  // namespace mpq
