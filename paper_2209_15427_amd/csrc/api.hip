@@ -232,6 +232,12 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
         a.phased = (pl.mode == kModeTap && a.cpt % 4 == 0 && a.cpt > 4 && pl.taps > 1) ? 1 : 0;
         unsigned zb = (unsigned)(epi.zx & 0xff);
         a.fill_word = x.dtype == MPQ_INT8 ? zb * 0x01010101u : 0u;
+        if (pl.mode == kModeRow && aligned16(x.data) && aligned16(y_data)) {
+            // first-layer shape: weights and an input patch resident in LDS, pool fused
+            err = launch_conv_first(a, d.pool_k, d.pool_s, y_data, g.Po, g.Qo, st);
+            if (err == hipSuccess) return MPQ_OK;
+            if (err != hipErrorNotSupported) return MPQ_ERR_DEVICE;
+        }
         if (pl.mode == kModeRow) {
             void *xp = wsb + wl.pad_off;
             err = launch_pad_channels(x.data, xp, x.n, x.h, x.w, x.c, pl.Wp, pl.Cpad, pl.esize,

@@ -123,6 +123,8 @@ hipError_t launch_conv_generic(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
 bool conv_mfma_dma_eligible(const ConvArgs &a);
 hipError_t launch_conv_mfma_dma(const ConvArgs &a, hipStream_t st);
+hipError_t launch_conv_first(const ConvArgs &a, int pool_k, int pool_s, void *y_final, int Po, int Qo,
+                             hipStream_t st);
 bool gemv_eligible(const ConvArgs &a);
 hipError_t launch_gemv(const ConvArgs &a, hipStream_t st);
 

@@ -1,0 +1,346 @@
+// First-layer convolution (few input channels, large strided kernel) for int8, with the layer's
+// 3x3 / stride-2 max-pool fused in.  Same arithmetic as the other convolution kernels (expanded
+// form of section "Quantized Operations", then bias + ReLU + requantize; the max-pool commutes
+// with the monotone requantization and is taken on the int8 codes).
+//
+// Why a kernel of its own: with C = 3 the reduction axis of one output pixel is R short runs of
+// S * C bytes, the layer is bound by activation traffic rather than by the matrix cores, and its
+// output (the largest tensor of the network) is immediately pooled 4:1.  So one workgroup
+//   1. keeps the whole packed weight matrix (K <= 96 rows x R * 48 bytes) in LDS,
+//   2. copies the input rows a strip of output rows needs from HBM once, as raw N,H,W,3 bytes,
+//      and expands them in LDS to 4 bytes per pixel, so that every tap run starts 16-byte aligned
+//      (the 4th byte meets a zero weight),
+//   3. feeds the MFMA B operand straight from that patch -- an output pixel's run for kernel row r
+//      is 48 contiguous bytes at (stride * p + r) * pitch + stride * q * 4 -- and the A operand
+//      from the resident weights (row pitch 33 chunks: odd, hence bank-conflict free), with no
+//      barrier inside the reduction loop,
+//   4. requantizes into an LDS image of the strip's convolution output, pools it there, and
+//      writes only the pooled rows, channel-contiguous.
+// HBM traffic: input once (+ halo rows between strips), pooled output once.
+#include <type_traits>
+
+#include <cstring>
+
+#include "common.h"
+#include "epilogue.h"
+
+namespace mpq {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+#define MPQ_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+
+constexpr int kThreads = 512;          // 8 wavefronts
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxK = 96;              // output channels: 3 MFMA row tiles
+constexpr int kRowTiles = kMaxK / 32;
+constexpr int kColTiles = 2;           // 32-pixel tiles per wavefront
+constexpr int kMaxPixels = kWaves * kColTiles * 32;   // 512 convolution outputs per strip
+constexpr int kOutPitch = 100;         // bytes per pixel in the LDS output image (25 dwords: odd)
+
+struct FirstArgs {
+    const void *x;        // N,H,W,C int8
+    const void *w;        // packed weights (row mode), wsum behind
+    const void *bias;
+    void *y;
+    int N, H, W, C;
+    int K, R;
+    int P, Q;             // convolution output
+    int Po, Qo;           // final output (pooled or not)
+    int stride;
+    int pool;             // 1: 3x3 / 2 max-pool fused, 0: none
+    int rows_per_strip;   // final-output rows per workgroup
+    int strips;           // per image
+    int cpt, nchunks;     // chunks per kernel row (3), R * cpt
+    int Kp;               // packed weight row length in bytes
+    int pitch;            // bytes per expanded patch row (multiple of 16, > W * 4)
+    int max_in_rows;      // input rows a full strip needs
+    unsigned w_magic;     // ceil(2^32 / W)
+    unsigned long long x_bytes;
+    size_t wsum_off;
+    // LDS layout (bytes)
+    int lds_w, lds_patch, lds_stage;
+    Epi epi;
+};
+
+__device__ __forceinline__ v4i lds_read16(unsigned addr) {
+    v4i r;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(addr));
+    return r;
+}
+__device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void lds_arrived(v4i &f) { asm volatile("" : "+v"(f)); }
+
+// byte-wise signed max of two packed int8x4 words (v_pk_max_i16 on the bytes moved to the high
+// half of each 16-bit lane, where their sign bit is the lane's sign bit)
+__device__ __forceinline__ unsigned max_i8x4(unsigned a, unsigned b) {
+    typedef short v2s __attribute__((ext_vector_type(2)));
+    const unsigned ae = (a << 8) & 0xff00ff00u, be = (b << 8) & 0xff00ff00u;   // bytes 0, 2
+    const unsigned ao = a & 0xff00ff00u, bo = b & 0xff00ff00u;                 // bytes 1, 3
+    const v2s me = __builtin_elementwise_max(__builtin_bit_cast(v2s, ae), __builtin_bit_cast(v2s, be));
+    const v2s mo = __builtin_elementwise_max(__builtin_bit_cast(v2s, ao), __builtin_bit_cast(v2s, bo));
+    return (__builtin_bit_cast(unsigned, mo) & 0xff00ff00u) | ((__builtin_bit_cast(unsigned, me) >> 8) & 0x00ff00ffu);
+}
+
+__global__ void __launch_bounds__(kThreads, 2) conv_first_kernel(FirstArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    unsigned char *wl = lds;                       // [96][Kp] weights
+    unsigned char *patch = lds + a.lds_w;          // [in_rows][pitch] expanded input
+    unsigned char *stage = patch + a.lds_patch;    // raw input bytes, later the output image
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = blockIdx.x / a.strips, strip = blockIdx.x % a.strips;
+
+    // ---- strip geometry (uniform) -------------------------------------------------------------
+    const int o0 = strip * a.rows_per_strip;                                   // first final-output row
+    const int orows = min(a.rows_per_strip, a.Po - o0);
+    const int c0 = a.pool ? 2 * o0 : o0;                                       // first convolution row
+    const int crows = a.pool ? 2 * orows + 1 : orows;
+    const int npix = crows * a.Q;
+    const int h_first = c0 * a.stride;
+    const int in_rows = (crows - 1) * a.stride + a.R;
+
+    // ---- 1. weights and raw input rows -> LDS (direct-to-LDS loads, 16 bytes per lane) -----------
+    {
+        const __amdgpu_buffer_rsrc_t wrs =
+            __builtin_amdgcn_make_buffer_rsrc((void *)a.w, (short)0, a.K * a.Kp, 0x00020000);
+        const int wchunks = kMaxK * a.Kp / 16;
+        for (int c = wave * 64; c < wchunks; c += kThreads)      // rows >= K read past the buffer: zeros
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MPQ_LDS(wl + c * 16), 16, (c + lane) * 16, 0, 0, 0);
+    }
+    const long long start = ((long long)n * a.H + h_first) * a.W * a.C;        // first byte needed
+    const int sh16 = (int)(start & 15);
+    {
+        const __amdgpu_buffer_rsrc_t xrs =
+            __builtin_amdgcn_make_buffer_rsrc((void *)a.x, (short)0, (int)a.x_bytes, 0x00020000);
+        const unsigned base = (unsigned)(start - sh16);
+        const int rchunks = (sh16 + in_rows * a.W * a.C + 15) / 16;
+        unsigned tail_off = 0;      // a 16-byte chunk that straddles the end of the tensor is dropped
+        int tail_lds = -1;          // whole by the range check: its valid bytes are copied by hand
+        for (int c = wave * 64; c < rchunks; c += kThreads) {
+            const unsigned o = base + (unsigned)(c + lane) * 16;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, MPQ_LDS(stage + c * 16), 16, o, 0, 0, 0);
+            if (o < a.x_bytes && o + 16 > a.x_bytes) {
+                tail_off = o;
+                tail_lds = (c + lane) * 16;
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        if (tail_lds >= 0) {
+            const unsigned char *src = (const unsigned char *)a.x;
+            for (unsigned b = 0; tail_off + b < a.x_bytes; ++b) stage[tail_lds + b] = src[tail_off + b];
+        }
+    }
+    __syncthreads();
+
+    // ---- 2. expand C bytes per pixel to 4 (rows are contiguous in memory: pixel i of the strip's
+    // input sits at raw byte sh16 + i * C) ------------------------------------------------------
+    {
+        const int total = in_rows * a.W;
+        const unsigned mask = a.C >= 4 ? 0xffffffffu : ((1u << (8 * a.C)) - 1u);
+        for (int i = tid; i < total; i += kThreads) {
+            const int row = (int)(((unsigned long long)(unsigned)i * a.w_magic) >> 32);
+            const int col = i - row * a.W;
+            const unsigned off = (unsigned)(sh16 + i * a.C);
+            const unsigned lo = *reinterpret_cast<const unsigned *>(stage + (off & ~3u));
+            const unsigned hi = *reinterpret_cast<const unsigned *>(stage + (off & ~3u) + 4);
+            const unsigned v = __builtin_amdgcn_alignbyte(hi, lo, off & 3u) & mask;
+            *reinterpret_cast<unsigned *>(patch + row * a.pitch + col * 4) = v;
+        }
+        const int padw = a.pitch / 4 - a.W;        // zero the tail of every patch row
+        for (int i = tid; i < in_rows * padw; i += kThreads)
+            *reinterpret_cast<unsigned *>(patch + (i / padw) * a.pitch + (a.W + i % padw) * 4) = 0u;
+    }
+    __syncthreads();
+
+    // ---- 3. reduction: A from the resident weights, B from the patch ------------------------------
+    const int frow = lane & 31, fk = lane >> 5;
+    v16i acc[kRowTiles][kColTiles];
+#pragma unroll
+    for (int i = 0; i < kRowTiles; ++i)
+#pragma unroll
+        for (int j = 0; j < kColTiles; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    const unsigned wl_addr = (unsigned)(size_t)MPQ_LDS(wl) + (unsigned)(frow * a.Kp);
+    const unsigned patch_addr = (unsigned)(size_t)MPQ_LDS(patch);
+    unsigned bbase[kColTiles];
+    bool tile_live[kColTiles];
+#pragma unroll
+    for (int j = 0; j < kColTiles; ++j) {
+        const int tile = wave * kColTiles + j;
+        tile_live[j] = tile * 32 < npix;
+        int pix = tile * 32 + frow;
+        pix = pix < npix ? pix : 0;
+        const int py = pix / a.Q, px = pix - py * a.Q;
+        bbase[j] = patch_addr + (unsigned)(py * a.stride * a.pitch + px * a.stride * 4);
+    }
+    if (tile_live[0]) {      // uniform per wavefront: tiles are assigned in order
+        // this lane's chunk index advances by 2 per step: (kr, kj) = (kc / cpt, kc % cpt)
+        int kc = fk, kr = kc / a.cpt, kj = kc % a.cpt;
+        const int ksteps = (a.nchunks + 1) / 2;
+        for (int ks = 0; ks < ksteps; ++ks) {
+            const bool kval = kc < a.nchunks;
+            const unsigned aoff = (unsigned)(kc * 16);
+            const unsigned boff = (unsigned)(kr * a.pitch + kj * 16);
+            v4i af[kRowTiles], bf[kColTiles];
+#pragma unroll
+            for (int i = 0; i < kRowTiles; ++i) af[i] = lds_read16(wl_addr + (unsigned)(i * 32 * a.Kp) + (kval ? aoff : 0u));
+#pragma unroll
+            for (int j = 0; j < kColTiles; ++j) bf[j] = lds_read16(bbase[j] + (kval ? boff : 0u));
+            lds_wait();
+#pragma unroll
+            for (int i = 0; i < kRowTiles; ++i) lds_arrived(af[i]);
+#pragma unroll
+            for (int j = 0; j < kColTiles; ++j) {
+                lds_arrived(bf[j]);
+                if (!kval) bf[j] = v4i{0, 0, 0, 0};          // odd chunk count: the last half step is empty
+            }
+#pragma unroll
+            for (int i = 0; i < kRowTiles; ++i)
+#pragma unroll
+                for (int j = 0; j < kColTiles; ++j)
+                    if (j == 0 || tile_live[j])
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+            kc += 2;
+            kj += 2;
+            if (kj >= a.cpt) {
+                kj -= a.cpt;
+                ++kr;
+            }
+        }
+    }
+
+    // ---- 4. bias + requantize into the LDS output image [pixel][kOutPitch] ----------------------
+    // (register v of lane l in a 32x32 tile: channel 8*(v/4) + 4*(l/32) + v%4, pixel l%32)
+    const Epi epi = a.epi;
+    const int *wsum = reinterpret_cast<const int *>((const char *)a.w + a.wsum_off);
+    auto requantize = [&](auto fast_tag) {
+        constexpr bool FAST = decltype(fast_tag)::value;
+        const FastRequant fr = make_fast_requant(epi);
+#pragma unroll
+        for (int i = 0; i < kRowTiles; ++i) {
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int ch = i * 32 + vq * 8 + fk * 4;
+                if (ch >= a.K) continue;
+                v4i b4 = {0, 0, 0, 0};
+                if (a.bias) b4 = *reinterpret_cast<const v4i *>((const int *)a.bias + ch);
+                if (epi.zx != 0) b4 -= *reinterpret_cast<const v4i *>(wsum + ch) * epi.zx;
+#pragma unroll
+                for (int j = 0; j < kColTiles; ++j) {
+                    const int pix = (wave * kColTiles + j) * 32 + frow;
+                    if (pix >= npix) continue;
+                    int t[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u] + b4[u];
+                    unsigned packed = 0;
+                    if constexpr (FAST) {
+                        packed = requant4_fast(t[0], t[1], t[2], t[3], fr);
+                    } else {
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) packed |= ((unsigned)requant32(t[u], epi) & 0xffu) << (8 * u);
+                    }
+                    *reinterpret_cast<unsigned *>(stage + pix * kOutPitch + ch) = packed;
+                }
+            }
+        }
+    };
+    if (fast_requant_ok(epi)) requantize(std::true_type{});
+    else requantize(std::false_type{});
+    __syncthreads();
+
+    // ---- 5. (pool and) store, channel-contiguous -----------------------------------------------
+    const int kd = a.K / 4;                           // dwords per pixel
+    const int total = orows * a.Qo * kd;
+    int8_t *y = (int8_t *)a.y;
+    for (int idx = tid; idx < total; idx += kThreads) {
+        const int cd = idx % kd;
+        const int op = idx / kd;
+        const int oq = op % a.Qo, orow = op / a.Qo;
+        unsigned v;
+        if (a.pool) {
+            const unsigned char *src = stage + ((2 * orow) * a.Q + 2 * oq) * kOutPitch + cd * 4;
+            v = *reinterpret_cast<const unsigned *>(src);
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+                    if (r + s > 0) v = max_i8x4(v, *reinterpret_cast<const unsigned *>(src + (r * a.Q + s) * kOutPitch));
+        } else {
+            v = *reinterpret_cast<const unsigned *>(stage + (orow * a.Q + oq) * kOutPitch + cd * 4);
+        }
+        *reinterpret_cast<unsigned *>(y + (((size_t)n * a.Po + o0 + orow) * a.Qo + oq) * a.K + cd * 4) = v;
+    }
+}
+
+}  // namespace
+
+// Host side: eligibility and launch.  Returns hipErrorNotSupported when the layer does not fit;
+// the caller then uses the general kernels.
+hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_final, int Po, int Qo,
+                             hipStream_t st) {
+    const Plan &pl = c.plan;
+    if (c.in_dtype != MPQ_INT8 || c.out_dtype != MPQ_INT8 || pl.mode != kModeRow) return hipErrorNotSupported;
+    if (c.epi.kind != kEpiRequant || c.epi.zw != 0 || c.seg.offsets) return hipErrorNotSupported;
+    if (c.K > kMaxK || c.K % 4 != 0 || c.stride_h != c.stride_w || c.groups != 1) return hipErrorNotSupported;
+    if (!((pool_k == 3 && pool_s == 2) || pool_k == 0)) return hipErrorNotSupported;
+    if ((reinterpret_cast<uintptr_t>(c.bias) % 16) != 0 || (reinterpret_cast<uintptr_t>(y_final) % 4) != 0)
+        return hipErrorNotSupported;
+    FirstArgs a;
+    memset(&a, 0, sizeof(a));
+    a.x = c.x; a.w = c.w; a.bias = c.bias; a.y = y_final;
+    a.N = c.N; a.H = c.H; a.W = c.W; a.C = c.C;
+    a.K = c.K; a.R = c.R; a.P = c.P; a.Q = c.Q; a.Po = Po; a.Qo = Qo;
+    a.stride = c.stride_w;
+    a.pool = pool_k == 3;
+    a.cpt = pl.tap_elems / kChunkBytes;
+    a.nchunks = c.R * a.cpt;
+    a.Kp = pl.Kp;
+    a.x_bytes = (unsigned long long)c.N * c.H * c.W * c.C;
+    if (a.x_bytes >= 0x7ffffff0ull || c.W > 4096) return hipErrorNotSupported;
+    a.wsum_off = pl.wsum_off;
+    a.epi = c.epi;
+    a.w_magic = (unsigned)(((1ull << 32) + c.W - 1) / c.W);
+    // the patch row must hold the last output pixel's run: (Q - 1) * stride + tap pixels
+    int need_px = (c.Q - 1) * a.stride + pl.tap_elems / 4;
+    if (need_px < c.W + 1) need_px = c.W + 1;
+    a.pitch = (int)round_up((size_t)need_px * 4, 16);
+    if ((a.pitch / 16) % 2 == 0) a.pitch += 16;          // odd number of 16-byte chunks per row
+    // rows per strip: as many final rows as keep the strip within 512 convolution outputs
+    int rps = a.pool ? (kMaxPixels / c.Q - 1) / 2 : kMaxPixels / c.Q;
+    if (rps < 1) return hipErrorNotSupported;
+    if (rps > Po) rps = Po;
+    for (;; --rps) {
+        if (rps < 1) return hipErrorNotSupported;
+        const int crows = a.pool ? 2 * rps + 1 : rps;
+        a.max_in_rows = (crows - 1) * a.stride + c.R;
+        a.lds_w = (int)round_up((size_t)kMaxK * a.Kp + 16, 1024);
+        a.lds_patch = (int)round_up((size_t)a.max_in_rows * a.pitch + 64, 1024);
+        const size_t raw = (size_t)a.max_in_rows * c.W * c.C + 64;
+        const size_t img = (size_t)crows * c.Q * kOutPitch + 16;
+        // + 1 KiB: the last wavefront-wide raw copy may run up to 63 chunks past the data
+        a.lds_stage = (int)round_up((raw > img ? raw : img) + 1024, 1024);
+        if (a.lds_w + a.lds_patch + a.lds_stage <= 160 * 1024) break;
+    }
+    a.rows_per_strip = rps;
+    a.strips = (Po + rps - 1) / rps;
+    const size_t lds_bytes = (size_t)a.lds_w + a.lds_patch + a.lds_stage;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)conv_first_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const long long blocks = (long long)c.N * a.strips;
+    if (blocks <= 0) return hipSuccess;
+    conv_first_kernel<<<(unsigned)blocks, kThreads, lds_bytes, st>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace mpq

@@ -313,9 +313,7 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
     // floor(t * mult / 2^(31 + shift)) = mulhi(t, mult) >> (shift - 1).
     auto run_epilogue = [&](auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
-        const int fmult = (int)epi.mult;
-        const int fsh = epi.shift - 1 > 31 ? 31 : epi.shift - 1;
-        const int lo_b = epi.lo - epi.zy, hi_b = epi.hi - epi.zy;
+        const FastRequant fr = make_fast_requant(epi);
 #pragma unroll
         for (int i = 0; i < TC; ++i) {
 #pragma unroll
@@ -353,18 +351,11 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
                                 *reinterpret_cast<v4i *>((int *)a.y + (size_t)m * a.K + kabs) = v4i{t[0], t[1], t[2], t[3]};
                         } else {
                             unsigned packed = 0;
+                            if constexpr (FAST) {
+                                packed = requant4_fast(t[0], t[1], t[2], t[3], fr);
+                            } else {
 #pragma unroll
-                            for (int u = 0; u < 4; ++u) {
-                                int q;
-                                if constexpr (FAST) {
-                                    q = __mulhi(t[u], fmult) >> fsh;
-                                    q = q < lo_b ? lo_b : q;
-                                    q = q > hi_b ? hi_b : q;
-                                    q += epi.zy;
-                                } else {
-                                    q = requant32(t[u], epi);
-                                }
-                                packed |= ((unsigned)q & 0xffu) << (8 * u);
+                                for (int u = 0; u < 4; ++u) packed |= ((unsigned)requant32(t[u], epi) & 0xffu) << (8 * u);
                             }
                             *reinterpret_cast<unsigned *>(lds + la) = packed;
                         }
@@ -389,7 +380,7 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
             }
         }
     };
-    const bool fast = ES == 1 && !raw && epi.relu && epi.shift >= 1 && epi.sb == 31;
+    const bool fast = ES == 1 && fast_requant_ok(epi);
     if (fast) run_epilogue(std::true_type{});
     else run_epilogue(std::false_type{});
     if (raw) return;

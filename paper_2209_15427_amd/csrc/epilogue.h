@@ -42,4 +42,43 @@ __device__ __forceinline__ int requant32(int t, const Epi &e) {
     return y + e.zy;
 }
 
+// Four accumulators -> four packed int8 codes on the fast path (8-bit storage, ReLU, right shift
+// of at least one bit): a negative accumulator clamps to the zero-point whatever its rounding, and
+// for t >= 0 truncate-then-floor equals floor(t * mult / 2^(31 + shift)) = mulhi(t, mult) >>
+// (shift - 1).  The values are narrowed to 16 bits with saturation (the clamp bounds lie well
+// inside), clamped and offset two at a time with packed 16-bit ops, and their low bytes gathered.
+struct FastRequant {
+    int mult, sh;
+    unsigned lo2, hi2, zy2;     // clamp bounds minus zero-point, and the zero-point, in both halves
+};
+
+__device__ __forceinline__ FastRequant make_fast_requant(const Epi &e) {
+    FastRequant f;
+    f.mult = (int)e.mult;
+    f.sh = e.shift - 1 > 31 ? 31 : e.shift - 1;
+    const unsigned lo = (unsigned)(e.lo - e.zy) & 0xffffu, hi = (unsigned)(e.hi - e.zy) & 0xffffu;
+    const unsigned zy = (unsigned)e.zy & 0xffffu;
+    f.lo2 = lo | (lo << 16);
+    f.hi2 = hi | (hi << 16);
+    f.zy2 = zy | (zy << 16);
+    return f;
+}
+
+__device__ __forceinline__ bool fast_requant_ok(const Epi &e) {
+    return e.kind == kEpiRequant && e.relu && e.shift >= 1 && e.sb == 31;
+}
+
+__device__ __forceinline__ unsigned requant4_fast(int t0, int t1, int t2, int t3, const FastRequant &f) {
+    typedef short v2s __attribute__((ext_vector_type(2)));
+    const int q0 = __mulhi(t0, f.mult) >> f.sh, q1 = __mulhi(t1, f.mult) >> f.sh;
+    const int q2 = __mulhi(t2, f.mult) >> f.sh, q3 = __mulhi(t3, f.mult) >> f.sh;
+    v2s a = __builtin_amdgcn_cvt_pk_i16(q0, q1), b = __builtin_amdgcn_cvt_pk_i16(q2, q3);
+    const v2s lo = __builtin_bit_cast(v2s, f.lo2), hi = __builtin_bit_cast(v2s, f.hi2);
+    const v2s zy = __builtin_bit_cast(v2s, f.zy2);
+    a = __builtin_elementwise_min(__builtin_elementwise_max(a, lo), hi) + zy;
+    b = __builtin_elementwise_min(__builtin_elementwise_max(b, lo), hi) + zy;
+    // low bytes of the four 16-bit lanes: (a.lo, a.hi, b.lo, b.hi) -> bytes 0..3
+    return __builtin_amdgcn_perm(__builtin_bit_cast(unsigned, b), __builtin_bit_cast(unsigned, a), 0x06040200u);
+}
+
 }  // namespace mpq
