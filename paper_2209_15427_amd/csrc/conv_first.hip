@@ -158,13 +158,27 @@ __global__ void __launch_bounds__(kThreads, 2) conv_first_kernel(FirstArgs a) {
 
     // ---- 3. reduction: A from the resident weights, B from the patch ------------------------------
     const int frow = lane & 31, fk = lane >> 5;
+    // accumulators start at the epilogue's per-channel constant: bias - z_x * sum(w)
+    // (register v of lane l in a 32x32 tile: channel 8*(v/4) + 4*(l/32) + v%4, pixel l%32)
+    const Epi epi = a.epi;
+    const int *wsum = reinterpret_cast<const int *>((const char *)a.w + a.wsum_off);
     v16i acc[kRowTiles][kColTiles];
 #pragma unroll
-    for (int i = 0; i < kRowTiles; ++i)
+    for (int i = 0; i < kRowTiles; ++i) {
 #pragma unroll
-        for (int j = 0; j < kColTiles; ++j)
+        for (int vq = 0; vq < 4; ++vq) {
+            const int ch = i * 32 + vq * 8 + fk * 4;
+            v4i b4 = {0, 0, 0, 0};
+            if (ch < a.K) {
+                if (a.bias) b4 = *reinterpret_cast<const v4i *>((const int *)a.bias + ch);
+                if (epi.zx != 0) b4 -= *reinterpret_cast<const v4i *>(wsum + ch) * epi.zx;
+            }
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+            for (int j = 0; j < kColTiles; ++j)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc[i][j][vq * 4 + u] = b4[u];
+        }
+    }
 
     const unsigned wl_addr = (unsigned)(size_t)MPQ_LDS(wl) + (unsigned)(frow * a.Kp);
     const unsigned patch_addr = (unsigned)(size_t)MPQ_LDS(patch);
@@ -180,45 +194,55 @@ __global__ void __launch_bounds__(kThreads, 2) conv_first_kernel(FirstArgs a) {
         bbase[j] = patch_addr + (unsigned)(py * a.stride * a.pitch + px * a.stride * 4);
     }
     if (tile_live[0]) {      // uniform per wavefront: tiles are assigned in order
-        // this lane's chunk index advances by 2 per step: (kr, kj) = (kc / cpt, kc % cpt)
+        // this lane's chunk index advances by 2 per step: (kr, kj) = (kc / cpt, kc % cpt); the
+        // fragments of step ks + 1 are requested before step ks is multiplied
         int kc = fk, kr = kc / a.cpt, kj = kc % a.cpt;
         const int ksteps = (a.nchunks + 1) / 2;
-        for (int ks = 0; ks < ksteps; ++ks) {
-            const bool kval = kc < a.nchunks;
-            const unsigned aoff = (unsigned)(kc * 16);
-            const unsigned boff = (unsigned)(kr * a.pitch + kj * 16);
-            v4i af[kRowTiles], bf[kColTiles];
+        v4i af[2][kRowTiles], bf[2][kColTiles];
+        auto fetch = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles]) {
+            const bool kval = kc < a.nchunks;       // odd chunk count: the last half step reads chunk 0
+            const unsigned aoff = kval ? (unsigned)(kc * 16) : 0u;
+            const unsigned boff = kval ? (unsigned)(kr * a.pitch + kj * 16) : 0u;
 #pragma unroll
-            for (int i = 0; i < kRowTiles; ++i) af[i] = lds_read16(wl_addr + (unsigned)(i * 32 * a.Kp) + (kval ? aoff : 0u));
+            for (int i = 0; i < kRowTiles; ++i) fa[i] = lds_read16(wl_addr + (unsigned)(i * 32 * a.Kp) + aoff);
 #pragma unroll
-            for (int j = 0; j < kColTiles; ++j) bf[j] = lds_read16(bbase[j] + (kval ? boff : 0u));
-            lds_wait();
-#pragma unroll
-            for (int i = 0; i < kRowTiles; ++i) lds_arrived(af[i]);
-#pragma unroll
-            for (int j = 0; j < kColTiles; ++j) {
-                lds_arrived(bf[j]);
-                if (!kval) bf[j] = v4i{0, 0, 0, 0};          // odd chunk count: the last half step is empty
-            }
-#pragma unroll
-            for (int i = 0; i < kRowTiles; ++i)
-#pragma unroll
-                for (int j = 0; j < kColTiles; ++j)
-                    if (j == 0 || tile_live[j])
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < kColTiles; ++j) fb[j] = lds_read16(bbase[j] + boff);
             kc += 2;
             kj += 2;
             if (kj >= a.cpt) {
                 kj -= a.cpt;
                 ++kr;
             }
+        };
+        auto multiply = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles], bool kval) {
+#pragma unroll
+            for (int i = 0; i < kRowTiles; ++i) lds_arrived(fa[i]);
+#pragma unroll
+            for (int j = 0; j < kColTiles; ++j) {
+                lds_arrived(fb[j]);
+                if (!kval) fb[j] = v4i{0, 0, 0, 0};      // ... and contributes nothing
+            }
+#pragma unroll
+            for (int i = 0; i < kRowTiles; ++i)
+#pragma unroll
+                for (int j = 0; j < kColTiles; ++j)
+                    if (j == 0 || tile_live[j])
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        };
+        fetch(af[0], bf[0]);
+        for (int ks = 0; ks < ksteps; ks += 2) {
+            lds_wait();
+            if (ks + 1 < ksteps) fetch(af[1], bf[1]);
+            multiply(af[0], bf[0], 2 * ks + fk < a.nchunks);
+            if (ks + 1 < ksteps) {
+                lds_wait();
+                if (ks + 2 < ksteps) fetch(af[0], bf[0]);
+                multiply(af[1], bf[1], 2 * (ks + 1) + fk < a.nchunks);
+            }
         }
     }
 
-    // ---- 4. bias + requantize into the LDS output image [pixel][kOutPitch] ----------------------
-    // (register v of lane l in a 32x32 tile: channel 8*(v/4) + 4*(l/32) + v%4, pixel l%32)
-    const Epi epi = a.epi;
-    const int *wsum = reinterpret_cast<const int *>((const char *)a.w + a.wsum_off);
+    // ---- 4. requantize into the LDS output image [pixel][kOutPitch] ------------------------------
     auto requantize = [&](auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
         const FastRequant fr = make_fast_requant(epi);
@@ -228,16 +252,13 @@ __global__ void __launch_bounds__(kThreads, 2) conv_first_kernel(FirstArgs a) {
             for (int vq = 0; vq < 4; ++vq) {
                 const int ch = i * 32 + vq * 8 + fk * 4;
                 if (ch >= a.K) continue;
-                v4i b4 = {0, 0, 0, 0};
-                if (a.bias) b4 = *reinterpret_cast<const v4i *>((const int *)a.bias + ch);
-                if (epi.zx != 0) b4 -= *reinterpret_cast<const v4i *>(wsum + ch) * epi.zx;
 #pragma unroll
                 for (int j = 0; j < kColTiles; ++j) {
                     const int pix = (wave * kColTiles + j) * 32 + frow;
                     if (pix >= npix) continue;
                     int t[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u] + b4[u];
+                    for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u];
                     unsigned packed = 0;
                     if constexpr (FAST) {
                         packed = requant4_fast(t[0], t[1], t[2], t[3], fr);

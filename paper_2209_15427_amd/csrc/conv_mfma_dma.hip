@@ -225,13 +225,37 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
         }
     };
 
+    // Accumulators start at the epilogue's per-channel constant: the bias, minus z_x * sum(w) for
+    // int8 (register v of lane l in a 32x32 tile holds channel 8*(v/4) + 4*(l/32) + v%4).
+    const int *wsum = reinterpret_cast<const int *>(wbase + pl.wsum_off);
     Acc acc[TC][TP];
 #pragma unroll
-    for (int i = 0; i < TC; ++i)
+    for (int i = 0; i < TC; ++i) {
 #pragma unroll
-        for (int j = 0; j < TP; ++j)
+        for (int vq = 0; vq < 4; ++vq) {
+            const int ch = ch0 + wc * WTC + i * 32 + vq * 8 + (lane >> 5) * 4;
+            const int kabs = g * pl.Kg + (ch < pl.Kg ? ch : 0);
+            if constexpr (ES == 1) {
+                v4i b4 = {0, 0, 0, 0};
+                if (bias) b4 = *reinterpret_cast<const v4i *>(bias + (size_t)kabs * 4);
+                if (epi.zx != 0) b4 -= *reinterpret_cast<const v4i *>(wsum + kabs) * epi.zx;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+                for (int j = 0; j < TP; ++j)
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) acc[i][j][vq * 4 + u] = b4[u];
+            } else {
+                float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (bias) bb = *reinterpret_cast<const float4 *>(bias + (size_t)kabs * 4);
+#pragma unroll
+                for (int j = 0; j < TP; ++j) {
+                    acc[i][j][vq * 4 + 0] = bb.x;
+                    acc[i][j][vq * 4 + 1] = bb.y;
+                    acc[i][j][vq * 4 + 2] = bb.z;
+                    acc[i][j][vq * 4 + 3] = bb.w;
+                }
+            }
+        }
+    }
 
     // fragment addresses: lane l reads row l % 32 of a 32-row sub-tile, chunk (2 ks + l / 32) at its
     // swizzled slot; sub-tiles are 32 rows = 2048 bytes apart (an immediate offset)
@@ -303,7 +327,6 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
     // written with 16-byte stores in which consecutive lanes cover consecutive channels of a
     // pixel, so that every store instruction fills whole cache lines.  Raw accumulator outputs
     // (gating logits) are stored directly.
-    const int *wsum = reinterpret_cast<const int *>(wbase + pl.wsum_off);
     const bool raw = epi.kind == kEpiRawI32 || epi.kind == kEpiRawF32;
     constexpr int ROWB = BC * ES, CH16 = ROWB / 16;
     static_assert(BP * ROWB <= NST * STAGE, "output tile must fit the stage buffers");
@@ -323,20 +346,6 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
                 const bool chv = ch < pl.Kg;
                 const int kabs = g * pl.Kg + (chv ? ch : 0);
                 const unsigned cb = (unsigned)(chl * ES);
-                v4i b4 = {0, 0, 0, 0};
-                float f4[4] = {0.f, 0.f, 0.f, 0.f};
-                if constexpr (ES == 1) {
-                    if (bias) b4 = *reinterpret_cast<const v4i *>(bias + (size_t)kabs * 4);
-                    if (epi.zx != 0) {
-                        v4i s4 = *reinterpret_cast<const v4i *>(wsum + kabs);
-                        b4 -= s4 * epi.zx;
-                    }
-                } else {
-                    if (bias) {
-                        float4 bb = *reinterpret_cast<const float4 *>(bias + (size_t)kabs * 4);
-                        f4[0] = bb.x; f4[1] = bb.y; f4[2] = bb.z; f4[3] = bb.w;
-                    }
-                }
 #pragma unroll
                 for (int j = 0; j < TP; ++j) {
                     const int row = wp * WTP + j * 32 + frow;
@@ -345,7 +354,7 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
                     if constexpr (ES == 1) {
                         int t[4];
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u] + b4[u];
+                        for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u];
                         if (raw) {
                             if (chv && m < m_end)
                                 *reinterpret_cast<v4i *>((int *)a.y + (size_t)m * a.K + kabs) = v4i{t[0], t[1], t[2], t[3]};
@@ -363,7 +372,7 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
                         float t[4];
 #pragma unroll
                         for (int u = 0; u < 4; ++u) {
-                            t[u] = acc[i][j][vq * 4 + u] + f4[u];
+                            t[u] = acc[i][j][vq * 4 + u];
                             if (epi.relu) t[u] = t[u] > 0.f ? t[u] : 0.f;
                         }
                         if (raw) {
