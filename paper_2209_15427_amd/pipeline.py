@@ -146,3 +146,80 @@ def nhwc_to_nchw(t):
     """Device NHWC (or [M, N]) result -> host numpy in the logical N,C,H,W order."""
     a = t.detach().cpu().numpy()
     return a.transpose(0, 3, 1, 2) if a.ndim == 4 else a
+
+
+class MoE:
+    """Expert stage resident on the device: per layer one buffer holding every expert's packed
+    weights at a uniform stride, biases [E][K], per-expert quantization parameters; forward()
+    enqueues mpq_moe_forward.  params[e][i] = (w, b) real-valued (converted by the library) or,
+    with codes=True, already storage codes / int32 bias codes."""
+
+    def __init__(self, specs, params, dtype, batch, in_hwc, s_in=1.0, scales=None, codes=False):
+        import ctypes as C
+        self.dtype, self.batch, self.E = dtype, batch, len(params)
+        E = self.E
+        h, w, c = in_hwc
+        self.in_shape = (batch, h, w, c)
+        self.s_in = s_in
+        self.keep, self.layers = [], []
+        shape = (h, w, c)
+        for i, L in enumerate(specs):
+            is_fc = L.kind == "fc"
+            if is_fc:
+                desc = mb.gemm_desc(L.K, L.N, L.relu)
+                kout = L.N
+            else:
+                desc = mb.conv_desc(L.C, L.K, L.R, L.S, L.stride, L.pad, L.groups, L.relu, L.pool_k, L.pool_s)
+                kout = L.K
+            nbytes = mb.mpq_packed_weight_bytes(desc, dtype)
+            stride = (nbytes + 255) // 256 * 256
+            packed = alloc_bytes(stride * E)
+            biases = torch.empty((E, kout), dtype=torch.float32 if dtype == mb.FP16 else torch.int32, device=DEV)
+            for e in range(E):
+                wr, br = params[e][i]
+                wr = np.asarray(wr)
+                if is_fc:
+                    if shape[0] > 1 or shape[1] > 1:          # (c,h,w) columns -> (h,w,c)
+                        wr = wr.reshape(L.N, shape[2], shape[0], shape[1]).transpose(0, 2, 3, 1).reshape(L.N, -1)
+                    wr = wr.reshape(L.N, L.K, 1, 1)
+                sc = None if scales is None else scales[e][i]
+                if codes:
+                    npdt = {mb.INT8: np.int8, mb.INT16: np.int16, mb.FP16: np.float16}[dtype]
+                    wd = torch.from_numpy(np.ascontiguousarray(wr.astype(npdt))).to(DEV)
+                    bd = torch.from_numpy(np.asarray(br).astype(np.float32 if dtype == mb.FP16 else np.int32)).to(DEV)
+                else:
+                    wd = to_storage(wr, dtype, 1.0 if sc is None else sc["w"], 0, nhwc=False)
+                    b32 = _dev(np.asarray(br, np.float32))
+                    if dtype == mb.FP16:
+                        bd = b32
+                    else:
+                        bd = torch.empty(b32.shape, dtype=torch.int32, device=DEV)
+                        mb.mpq_quantize(b32, bd, b32.numel(), mb.INT32, sc["b"], 0)
+                mb.mpq_pack_weights(wd, desc, dtype, packed[e * stride:], nbytes)
+                biases[e].copy_(bd)
+            wq = (mb.QParams * E)(*[mb.QParams(1.0 if scales is None else float(scales[e][i]["w"]), 0) for e in range(E)])
+            yq = (mb.QParams * E)(*[mb.QParams(1.0 if scales is None else float(scales[e][i]["y"]), 0) for e in range(E)])
+            self.keep += [packed, biases, wq, yq]
+            self.layers.append(mb.MoeLayer(desc, int(is_fc), packed.data_ptr(), stride, biases.data_ptr(), wq, yq))
+            if is_fc:
+                shape = (1, 1, L.N)
+            else:
+                P, Q = L.out_hw(shape[0], shape[1])
+                if L.pool_k:
+                    P, Q = (P - L.pool_k) // L.pool_s + 1, (Q - L.pool_k) // L.pool_s + 1
+                shape = (P, Q, L.K)
+        self.out_shape = (batch,) + shape
+        self.y = torch.empty(self.out_shape, dtype=mb.TORCH_DTYPE[dtype], device=DEV)
+        self.expert_index = torch.empty((batch,), dtype=torch.int32, device=DEV)
+        self.expert_counts = torch.empty((E,), dtype=torch.int32, device=DEV)
+        xv = mb.tensor(None, dtype, *self.in_shape, scale=s_in)
+        self.ws_bytes = mb.mpq_moe_workspace_bytes(xv, E, self.layers)
+        self.ws = alloc_bytes(self.ws_bytes)
+        torch.cuda.synchronize()
+
+    def forward(self, x_storage, logits, logits_dtype):
+        xv = mb.tensor(x_storage, self.dtype, *self.in_shape, scale=self.s_in)
+        yv = mb.tensor(self.y, self.dtype, *self.out_shape)
+        mb.mpq_moe_forward(xv, logits, logits_dtype, self.E, 1, self.layers, yv, self.expert_index,
+                           self.expert_counts, self.ws, self.ws_bytes)
+        return self.y

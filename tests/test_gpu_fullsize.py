@@ -1,0 +1,179 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times: the
+whole batch runs on the device; the oracle computes a sample of the outputs one by one (whole
+images / rows / samples, which are independent of the rest of the batch)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import nets, oracle as o
+from paper_2209_15427_amd import binding as mb
+from paper_2209_15427_amd import pipeline as pl
+from tests import gpu_util as gu
+from workloads import calib, configs as cf, gen
+
+pytestmark = pytest.mark.gpu
+DT = {"int8": mb.INT8, "int16": mb.INT16, "fp16": mb.FP16}
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+_ALEX = {}
+
+
+def _alexnet_batch(B):
+    if B not in _ALEX:
+        _ALEX[B] = cf.alexnet_input(B)
+    return _ALEX[B]
+
+
+@pytest.mark.parametrize("dtype", ["int8", "fp16"])
+def test_alexnet_stack_batch256_sampled_images(dtype):
+    """Config 3 at batch 256: every layer's output for images 0, 97 and 255 against the oracle."""
+    _say("alexnet b256", dtype)
+    B, sample = 256, [0, 97, 255]
+    x = _alexnet_batch(B)
+    params = cf.alexnet_conv_params()
+    if dtype == "fp16":
+        chain = pl.Chain(cf.ALEXNET_CONVS, params, DT[dtype], B, cf.ALEXNET_INPUT)
+    else:
+        sc = calib.load()["alexnet"][dtype]
+        chain = pl.Chain(cf.ALEXNET_CONVS, params, DT[dtype], B, cf.ALEXNET_INPUT, sc["x"], sc["layers"])
+    chain.forward(chain.input_storage(x))
+    torch.cuda.synchronize()
+    gpu = [pl.nhwc_to_nchw(a[sample]) for a in chain.acts]
+    xs = x[sample]
+    if dtype == "fp16":
+        _, outs = nets.run_fp16_chain(cf.ALEXNET_CONVS, xs, params, collect=True)
+        for i, (g, r) in enumerate(zip(gpu, outs)):
+            gu.check_fp16(g, r, f"{cf.ALEXNET_CONVS[i].name} (chain)", gu.FLOOR_SAME_INPUT if i == 0 else 0.1 * i)
+    else:
+        _, outs = nets.run_int_chain(cf.ALEXNET_CONVS, xs, params, sc["x"], sc["layers"], dtype, collect=True)
+        for i, (g, r) in enumerate(zip(gpu, outs)):
+            assert np.array_equal(g.astype(np.int32), r), cf.ALEXNET_CONVS[i].name
+            assert len(np.unique(r)) > 8
+
+
+def test_alexnet_stack_batch8_int16():
+    """int16 runs on the direct kernel; batch 8 keeps the oracle and the device in seconds."""
+    x = _alexnet_batch(256)[:8]
+    params = cf.alexnet_conv_params()
+    sc = calib.load()["alexnet"]["int16"]
+    chain = pl.Chain(cf.ALEXNET_CONVS, params, mb.INT16, 8, cf.ALEXNET_INPUT, sc["x"], sc["layers"])
+    chain.forward(chain.input_storage(x))
+    torch.cuda.synchronize()
+    sample = [0, 7]
+    _, outs = nets.run_int_chain(cf.ALEXNET_CONVS, x[sample], params, sc["x"], sc["layers"], "int16", collect=True)
+    for i, r in enumerate(outs):
+        assert np.array_equal(pl.nhwc_to_nchw(chain.acts[i][sample]).astype(np.int32), r)
+
+
+@pytest.mark.parametrize("dtype", ["int8", "int16", "fp16"])
+@pytest.mark.parametrize("layer", [0, 1, 2])
+def test_fc_batch256_sampled_rows(layer, dtype):
+    """Config 4 at batch 256: rows 0, 31, 200, 255 against the oracle."""
+    _say("fc b256", layer, dtype)
+    L, x, w, b = cf.fc_case(layer, 256)
+    rows = [0, 31, 200, 255]
+    if dtype == "fp16":
+        chain = pl.Chain([L], [(w, b)], mb.FP16, 256, (L.K, 1, 1))
+        y = chain.forward(chain.input_storage(x))
+        torch.cuda.synchronize()
+        ref = nets.run_fp16_chain([L], x[rows], [(w, b)])
+        gu.check_fp16(y[rows].cpu().numpy().reshape(ref.shape), ref, L.name)
+    else:
+        sc = calib.load()["fc"][L.name][dtype]
+        chain = pl.Chain([L], [(w, b)], DT[dtype], 256, (L.K, 1, 1), sc["x"], sc["layers"])
+        y = chain.forward(chain.input_storage(x))
+        torch.cuda.synchronize()
+        ref = nets.run_int_chain([L], x[rows], [(w, b)], sc["x"], sc["layers"], dtype)
+        assert np.array_equal(y[rows].cpu().numpy().reshape(ref.shape).astype(np.int32), ref)
+        assert len(np.unique(ref)) > 8
+
+
+# ---------------------------------------------------------------------------------------------
+# config 5: mixture of experts at batch 256
+# ---------------------------------------------------------------------------------------------
+def _moe_setup(dtype, B):
+    trunk_p, gate_w, experts_p = cf.moe_params()
+    x = _alexnet_batch(256)[:B]
+    cal = calib.load()
+    if dtype == "fp16":
+        trunk = pl.Chain(cf.MOE_TRUNK, trunk_p, mb.FP16, B, cf.ALEXNET_INPUT)
+        gate = pl.Chain([cf.MOE_GATE], [(gate_w, None)], mb.FP16, B, (256, 13, 13), raw_last=True)
+        moe = pl.MoE(cf.MOE_EXPERT_LAYERS, experts_p, mb.FP16, B, (13, 13, 256))
+        return x, trunk_p, gate_w, experts_p, trunk, gate, moe, None, None
+    sa, sm = cal["alexnet"][dtype], cal["moe"][dtype]
+    s_trunk = sa["layers"][1]["y"]
+    trunk = pl.Chain(cf.MOE_TRUNK, trunk_p, DT[dtype], B, cf.ALEXNET_INPUT, sa["x"], sa["layers"][:2])
+    gsc = [{"w": sm["gate_w"], "b": 1.0, "y": 1.0}]
+    gate = pl.Chain([cf.MOE_GATE], [(gate_w, None)], DT[dtype], B, (256, 13, 13), s_trunk, gsc, raw_last=True)
+    moe = pl.MoE(cf.MOE_EXPERT_LAYERS, experts_p, DT[dtype], B, (13, 13, 256), s_trunk, sm["experts"])
+    return x, trunk_p, gate_w, experts_p, trunk, gate, moe, sa, sm
+
+
+def _oracle_moe_samples(dtype, xs, logits_s, trunk_p, experts_p, sa, sm):
+    """Oracle: trunk for the sampled images, then each sample through its arg-max expert."""
+    if dtype == "fp16":
+        t64 = nets.run_fp16_chain(cf.MOE_TRUNK, xs, trunk_p)
+        e16 = [[nets.fp16_params(w, b) for (w, b) in ps] for ps in experts_p]
+        return nets.moe_fp16(o.round_fp16(t64), logits_s, cf.MOE_EXPERT_LAYERS, e16)
+    tq = nets.run_int_chain(cf.MOE_TRUNK, xs, trunk_p, sa["x"], sa["layers"][:2], dtype)
+    eq = [[nets.quantize_params(w, b, sc, dtype) for (w, b), sc in zip(ps, scs)] for ps, scs in zip(experts_p, sm["experts"])]
+    return nets.moe_int(tq, sa["layers"][1]["y"], logits_s, cf.MOE_EXPERT_LAYERS, eq, sm["experts"], dtype)
+
+
+@pytest.mark.parametrize("dtype", ["int8", "fp16"])
+def test_moe_config5_batch256_benchmark_routing(dtype):
+    """Config 5, batch 256, the prescribed 102/77/51/26 routing: ids and counts for every sample,
+    expert outputs for twelve samples (three per expert) against the oracle."""
+    _say("moe b256", dtype)
+    B = 256
+    x, trunk_p, gate_w, experts_p, trunk, gate, moe, sa, sm = _moe_setup(dtype, B)
+    t = trunk.forward(trunk.input_storage(x))
+    gate.forward(t)                      # the gating FC runs (raw accumulators); its routing is checked below
+    logits = cf.moe_benchmark_logits(B)
+    lg = torch.from_numpy(logits.astype(np.float32)).to("cuda")
+    y = moe.forward(t, lg, mb.FP32)
+    torch.cuda.synchronize()
+    e_ref, c_ref = o.route_top1(logits.astype(np.float32).astype(np.float64))
+    assert np.array_equal(moe.expert_index.cpu().numpy(), e_ref)
+    assert tuple(moe.expert_counts.cpu().numpy()) == cf.MOE_COUNTS_256 == tuple(c_ref)
+    sample = sorted(sum([list(np.where(e_ref == e)[0][[0, 1, -1]]) for e in range(cf.MOE_EXPERTS)], []))
+    ref, e_s, _ = _oracle_moe_samples(dtype, x[sample], logits[sample].astype(np.float32).astype(np.float64),
+                                      trunk_p, experts_p, sa, sm)
+    assert np.array_equal(e_s, e_ref[sample])
+    got = y[sample].cpu().numpy().reshape(ref.shape)
+    if dtype == "fp16":
+        gu.check_fp16(got, ref, "moe experts", 0.1 * 5)     # 2 trunk + 4 expert layers deep
+    else:
+        assert np.array_equal(got.astype(np.int32), ref)
+        assert len(np.unique(ref)) > 8
+    # gating logits themselves, for the sampled images
+    g = gate.acts[0][sample].cpu().numpy().reshape(len(sample), -1)
+    if dtype == "int8":
+        tq = nets.run_int_chain(cf.MOE_TRUNK, x[sample], trunk_p, sa["x"], sa["layers"][:2], dtype)
+        gq = o.quantize(np.asarray(gate_w, np.float32), sm["gate_w"], 0, dtype)
+        assert np.array_equal(g.astype(np.int64), o.gemm_acc(tq.reshape(len(sample), -1), 0, gq, 0))
+
+
+def test_moe_config5_parity_routing_batch16_int8():
+    """Routing by the real gating layer (raw int32 logits from mpq_gemm), batch 16, every sample."""
+    B, dtype = 16, "int8"
+    x, trunk_p, gate_w, experts_p, trunk, gate, moe, sa, sm = _moe_setup(dtype, B)
+    t = trunk.forward(trunk.input_storage(x))
+    lg = gate.forward(t)
+    y = moe.forward(t, lg, mb.INT32)
+    torch.cuda.synchronize()
+    tq = nets.run_int_chain(cf.MOE_TRUNK, x, trunk_p, sa["x"], sa["layers"][:2], dtype)
+    gq = o.quantize(np.asarray(gate_w, np.float32), sm["gate_w"], 0, dtype)
+    # gating weights arrive on the device in (h,w,c) column order; the logits are layout independent
+    logits = o.gemm_acc(tq.reshape(B, -1), 0, gq, 0)
+    assert np.array_equal(lg.cpu().numpy().reshape(B, -1).astype(np.int64), logits)
+    eq = [[nets.quantize_params(w, b, sc, dtype) for (w, b), sc in zip(ps, scs)] for ps, scs in zip(experts_p, sm["experts"])]
+    ref, e_ref, c_ref = nets.moe_int(tq, sa["layers"][1]["y"], logits.astype(np.float64), cf.MOE_EXPERT_LAYERS, eq,
+                                     sm["experts"], dtype)
+    assert np.array_equal(moe.expert_index.cpu().numpy(), e_ref)
+    assert np.array_equal(moe.expert_counts.cpu().numpy(), c_ref)
+    assert np.array_equal(y.cpu().numpy().reshape(ref.shape).astype(np.int32), ref)
