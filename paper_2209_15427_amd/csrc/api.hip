@@ -253,7 +253,8 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
             a.tap_px = 1;
         }
         a.x_bytes = (unsigned long long)a.N * a.H * a.W * a.C * pl.esize;
-        err = conv_mfma_dma_eligible(a) ? launch_conv_mfma_dma(a, st) : launch_conv_mfma(a, st);
+        if (conv_patch_prepare(a)) err = launch_conv_patch(a, st);
+        else err = conv_mfma_dma_eligible(a) ? launch_conv_mfma_dma(a, st) : launch_conv_mfma(a, st);
     } else {
         err = launch_conv_generic(a, st);
     }

@@ -97,6 +97,10 @@ struct ConvArgs {
     int ptiles;            // pixel tiles in the grid (filled by the launcher)
     int y_vec16;           // output rows and channel-tile origins are 16-byte aligned
     int phased;            // walk the reduction axis channel block by channel block (see conv_mfma_dma.hip)
+    // patch kernel (conv_patch.hip): chunks per pixel per channel block, channel blocks, steps per
+    // block, and ceil(2^32 / d) for d = Wv, Hv * Wv, cbc
+    int cbc, nphase, ksp;
+    unsigned magic_wv, magic_hw, magic_cbc;
     unsigned fill_word;    // the input zero-point replicated over 32 bits (out-of-image taps)
     unsigned long long x_bytes;   // size of the input tensor the kernel sees
     Plan plan;
@@ -123,6 +127,8 @@ hipError_t launch_conv_generic(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
 bool conv_mfma_dma_eligible(const ConvArgs &a);
 hipError_t launch_conv_mfma_dma(const ConvArgs &a, hipStream_t st);
+bool conv_patch_prepare(ConvArgs &a);
+hipError_t launch_conv_patch(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_first(const ConvArgs &a, int pool_k, int pool_s, void *y_final, int Po, int Qo,
                              hipStream_t st);
 bool gemv_eligible(const ConvArgs &a);

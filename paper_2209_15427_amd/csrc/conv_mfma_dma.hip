@@ -1,6 +1,5 @@
-// Implicit-GEMM convolution / fully-connected kernel on the gfx950 matrix cores, fast variant:
-// operand tiles travel HBM/L2 -> LDS directly (buffer_load ... lds), several reduction steps in
-// flight, so that the MFMA pipe only ever waits on LDS.
+// Implicit-GEMM convolution / fully-connected kernel on the gfx950 matrix cores: operand tiles
+// travel HBM/L2 -> LDS directly (buffer_load ... lds), several reduction steps in flight.
 //
 // Same arithmetic as conv_mfma.hip (expanded-form accumulate of section "Quantized Operations",
 // then the fused bias + ReLU + requantize epilogue); this file differs in data movement only:
@@ -15,71 +14,25 @@
 //     right padding value only when the input zero-point is 0 (or the layer has no padding);
 //     other cases run on the register-staged kernel.
 //   - synchronisation is explicit: a wavefront counts its own outstanding loads (s_waitcnt
-//     vmcnt), then a bare s_barrier makes every wavefront's loads of that step visible.  The
-//     fragment reads are issued as inline ds_read_b128 so that the compiler, which cannot tell
-//     the stages apart, does not drain all outstanding loads in front of them.
-#include <type_traits>
-
-#include "common.h"
-#include "epilogue.h"
+//     vmcnt), then a bare s_barrier makes every wavefront's loads of that step visible.
+#include "mfma_tile.h"
 
 namespace mpq {
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-typedef _Float16 v8h __attribute__((ext_vector_type(8)));
-
-#define MPQ_LDS(p) ((__attribute__((address_space(3))) void *)(p))
-
-template <typename T> struct Mma;
-template <> struct Mma<int8_t> {
-    typedef v16i Acc;
-    static __device__ __forceinline__ Acc run(v4i a, v4i b, Acc c) {
-        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
-    }
-};
-template <> struct Mma<_Float16> {
-    typedef v16f Acc;
-    static __device__ __forceinline__ Acc run(v4i a, v4i b, Acc c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c,
-                                                      0, 0, 0);
-    }
-};
-
-constexpr int kThreads = 256;
-constexpr unsigned kOob = 0x7ffffff0u;   // beyond any buffer this kernel accepts (< 2 GiB)
-
-// LDS fragment read the compiler does not model as a memory access (see the header).  The value
-// arrives asynchronously: lds_arrived() must come between the read and the first use.
-template <int OFF> __device__ __forceinline__ v4i lds_read(unsigned addr) {
-    v4i r;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-    return r;
-}
-__device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-// ties a fragment's uses to the wait that precedes this statement
-__device__ __forceinline__ void lds_arrived(v4i &f) { asm volatile("" : "+v"(f)); }
-
-// wait until at most n of this wavefront's vector-memory operations are outstanding
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((N & 0xf) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
+using namespace tile;
 
 template <typename T, int BC, int BP, int WGC, int WGP, int NST, int WPE>
 __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a) {
-    static_assert(WGC * WGP == 4, "four wavefronts per workgroup");
+    typedef Tile<T, BC, BP, WGC, WGP> TL;
     static_assert(BC % 64 == 0 && BP % 64 == 0, "tile rows come in groups of 64");
-    static_assert(NST == 3 || NST == 4, "three or four stages");
-    constexpr int WTC = BC / WGC, WTP = BP / WGP;
-    constexpr int TC = WTC / 32, TP = WTP / 32;
+    constexpr int WTC = TL::WTC, WTP = TL::WTP, TC = TL::TC, TP = TL::TP, ES = TL::ES;
     constexpr int LW = BC / 64, LX = BP / 64;        // loads per thread and step: weights, input
     constexpr int LPT = LW + LX;
     constexpr int STAGE = (BC + BP) * kStepBytes;
-    constexpr int ES = (int)sizeof(T);
-    typedef typename Mma<T>::Acc Acc;
+    static_assert(TL::kImageBytes <= NST * STAGE, "output tile must fit the stage buffers");
+    typedef typename TL::Acc Acc;
 
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NST * STAGE];
 
@@ -88,50 +41,12 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
     const Plan &pl = a.plan;
     const int PQ = a.P * a.Q;
 
-    // ---- which tile: consecutive workgroups land on different XCDs, so hand each XCD a
-    // contiguous range of tiles (neighbouring tiles share input rows and weights in its L2) ----
-    const int ctiles = (pl.Kg + BC - 1) / BC;
-    const int nblk = gridDim.x;
-    int bid = blockIdx.x;
-    {
-        const int per = nblk / 8, rem = nblk % 8, x = bid % 8, j = bid / 8;
-        bid = x * per + (x < rem ? x : rem) + j;
-    }
-    const int ct = bid % ctiles;
-    bid /= ctiles;
-    int pt = bid % a.ptiles;
-    const int g = bid / a.ptiles;
-
-    int m_begin = 0, m_end = a.N * PQ;
-    const char *wbase = (const char *)a.w;
-    const char *bias = (const char *)a.bias;
-    Epi epi = a.epi;
-    if (a.seg.offsets) {
-        int e = 0, tile_base = 0;
-        bool found = false;
-        for (; e < a.seg.num_experts; ++e) {
-            int lo = a.seg.offsets[e], hi = a.seg.offsets[e + 1];
-            int tiles = ((hi - lo) * PQ + BP - 1) / BP;
-            if (pt < tile_base + tiles) {
-                m_begin = lo * PQ;
-                m_end = hi * PQ;
-                pt -= tile_base;
-                found = true;
-                break;
-            }
-            tile_base += tiles;
-        }
-        if (!found) return;
-        wbase += (size_t)e * a.seg.w_stride;
-        if (bias) bias += (size_t)e * a.seg.bias_stride * 4;
-        epi = a.seg.epi[e];
-    }
-    const int m0 = m_begin + pt * BP;
-    const int ch0 = ct * BC;
-    if (m0 >= m_end) return;
+    TileCtx t;
+    if (!decode_tile<BC, BP>(a, t)) return;      // uniform over the workgroup, before any barrier
+    const int g = t.g, m0 = t.m0, m_begin = t.m_begin, m_end = t.m_end, ch0 = t.ch0;
 
     const __amdgpu_buffer_rsrc_t wrs =
-        __builtin_amdgcn_make_buffer_rsrc((void *)wbase, (short)0, (int)pl.wsum_off, 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc((void *)t.wbase, (short)0, (int)pl.wsum_off, 0x00020000);
     const __amdgpu_buffer_rsrc_t xrs =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.x, (short)0, (int)a.x_bytes, 0x00020000);
 
@@ -169,11 +84,9 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
     int tr = tap / S_eff, ts = tap % S_eff;
     const int tap_stride_r = a.W * a.C * ES, tap_stride_s = a.C * ES;
     // phased order (taps wider than one step): the reduction axis is walked 64-byte channel block
-    // by channel block, all taps inside a block, so that consecutive steps re-read the lines the
-    // neighbouring pixels just fetched (they are still in the vector L1) instead of coming back
-    // to them R*S*C/64 steps later.  The packed weights are addressed in the same order.
+    // by channel block, all taps inside a block; the packed weights are addressed in the same order
     const bool phased = a.phased != 0;
-    int ph = 0;    // uniform counters of the phased walk: channel block; (tr, ts) is the tap
+    int ph = 0;
     if (phased) {
         tr = 0;
         ts = 0;
@@ -225,37 +138,8 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
         }
     };
 
-    // Accumulators start at the epilogue's per-channel constant: the bias, minus z_x * sum(w) for
-    // int8 (register v of lane l in a 32x32 tile holds channel 8*(v/4) + 4*(l/32) + v%4).
-    const int *wsum = reinterpret_cast<const int *>(wbase + pl.wsum_off);
     Acc acc[TC][TP];
-#pragma unroll
-    for (int i = 0; i < TC; ++i) {
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-            const int ch = ch0 + wc * WTC + i * 32 + vq * 8 + (lane >> 5) * 4;
-            const int kabs = g * pl.Kg + (ch < pl.Kg ? ch : 0);
-            if constexpr (ES == 1) {
-                v4i b4 = {0, 0, 0, 0};
-                if (bias) b4 = *reinterpret_cast<const v4i *>(bias + (size_t)kabs * 4);
-                if (epi.zx != 0) b4 -= *reinterpret_cast<const v4i *>(wsum + kabs) * epi.zx;
-#pragma unroll
-                for (int j = 0; j < TP; ++j)
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) acc[i][j][vq * 4 + u] = b4[u];
-            } else {
-                float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (bias) bb = *reinterpret_cast<const float4 *>(bias + (size_t)kabs * 4);
-#pragma unroll
-                for (int j = 0; j < TP; ++j) {
-                    acc[i][j][vq * 4 + 0] = bb.x;
-                    acc[i][j][vq * 4 + 1] = bb.y;
-                    acc[i][j][vq * 4 + 2] = bb.z;
-                    acc[i][j][vq * 4 + 3] = bb.w;
-                }
-            }
-        }
-    }
+    TL::init_acc(acc, a, t);
 
     // fragment addresses: lane l reads row l % 32 of a 32-row sub-tile, chunk (2 ks + l / 32) at its
     // swizzled slot; sub-tiles are 32 rows = 2048 bytes apart (an immediate offset)
@@ -285,8 +169,8 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
         const unsigned base = (unsigned)(size_t)MPQ_LDS(src);
         v4i a0[TC], b0[TP], a1[TC], b1[TP];
         read_frags(base, fa0, fb0, a0, b0);
-        read_frags(base, fa1, fb1, a1, b1);      // second half in flight while the first multiplies
-        arrived(a0, b0);                         // (reads return in order; one wait covers both)
+        read_frags(base, fa1, fb1, a1, b1);
+        arrived(a0, b0);
         arrived(a1, b1);
 #pragma unroll
         for (int i = 0; i < TC; ++i)
@@ -298,121 +182,24 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_mfma_dma_kernel(ConvArgs a
             for (int j = 0; j < TP; ++j) acc[i][j] = Mma<T>::run(a1[i], b1[j], acc[i][j]);
     };
 
-    // one pipeline step: stage `cur` holds step kt; `refill` (the stage multiplied one step ago)
-    // receives step kt + NST - 1
-    auto step = [&](unsigned char *cur, unsigned char *refill, int kt) {
-        wait_vmcnt<LPT *(NST - 2)>();    // this wavefront's loads of step kt have landed
-        asm volatile("s_barrier" ::: "memory");   // everyone's have, and everyone is done with `refill`
-        request(refill, kt + NST - 1);
-        multiply(cur);
-    };
-
+    // pipeline: stage `cur` holds step kt; `refill` (the stage multiplied one step ago) receives
+    // step kt + NST - 1
     const int ksteps = a.ksteps;
 #pragma unroll
     for (int p = 0; p < NST - 1; ++p) request(lds + p * STAGE, p);
     int cur = 0, refill = NST - 1;
     for (int kt = 0; kt < ksteps; ++kt) {
-        step(lds + cur * STAGE, lds + refill * STAGE, kt);
+        wait_vmcnt<LPT *(NST - 2)>();    // this wavefront's loads of step kt have landed
+        bare_barrier();                  // everyone's have, and everyone is done with `refill`
+        request(lds + refill * STAGE, kt + NST - 1);
+        multiply(lds + cur * STAGE);
         cur = cur + 1 == NST ? 0 : cur + 1;
         refill = refill + 1 == NST ? 0 : refill + 1;
     }
-    wait_vmcnt<0>();    // drain the trailing all-zero requests before the LDS is released
+    wait_vmcnt<0>();     // drain the trailing requests before the LDS is reused
+    bare_barrier();      // every wavefront is done with the stages
 
-    asm volatile("s_barrier" ::: "memory");   // every wavefront is done with the stages
-
-    // ---- epilogue ---------------------------------------------------------------------------
-    // Register v of lane l in a 32x32 tile holds channel 8*(v/4) + 4*(l/32) + v%4 of pixel l%32:
-    // four consecutive channels of one pixel.  Storage-type outputs are first laid out in LDS as
-    // the tile's [pixel][channel] image (16-byte chunks XOR-swizzled by the pixel index), then
-    // written with 16-byte stores in which consecutive lanes cover consecutive channels of a
-    // pixel, so that every store instruction fills whole cache lines.  Raw accumulator outputs
-    // (gating logits) are stored directly.
-    const bool raw = epi.kind == kEpiRawI32 || epi.kind == kEpiRawF32;
-    constexpr int ROWB = BC * ES, CH16 = ROWB / 16;
-    static_assert(BP * ROWB <= NST * STAGE, "output tile must fit the stage buffers");
-    static_assert((CH16 & (CH16 - 1)) == 0, "chunks per row must be a power of two");
-    // FAST: int8 with ReLU and a right shift of at least one bit.  Negative accumulators clamp to
-    // the zero-point whatever their rounding, and for t >= 0 truncate-then-floor is one floor:
-    // floor(t * mult / 2^(31 + shift)) = mulhi(t, mult) >> (shift - 1).
-    auto run_epilogue = [&](auto fast_tag) {
-        constexpr bool FAST = decltype(fast_tag)::value;
-        const FastRequant fr = make_fast_requant(epi);
-#pragma unroll
-        for (int i = 0; i < TC; ++i) {
-#pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const int chl = wc * WTC + i * 32 + vq * 8 + fk * 4;     // channel within the tile
-                const int ch = ch0 + chl;
-                const bool chv = ch < pl.Kg;
-                const int kabs = g * pl.Kg + (chv ? ch : 0);
-                const unsigned cb = (unsigned)(chl * ES);
-#pragma unroll
-                for (int j = 0; j < TP; ++j) {
-                    const int row = wp * WTP + j * 32 + frow;
-                    const int m = m0 + row;
-                    const unsigned la = (unsigned)(row * ROWB) + (((cb >> 4) ^ (unsigned)(row & (CH16 - 1))) << 4) + (cb & 15u);
-                    if constexpr (ES == 1) {
-                        int t[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u];
-                        if (raw) {
-                            if (chv && m < m_end)
-                                *reinterpret_cast<v4i *>((int *)a.y + (size_t)m * a.K + kabs) = v4i{t[0], t[1], t[2], t[3]};
-                        } else {
-                            unsigned packed = 0;
-                            if constexpr (FAST) {
-                                packed = requant4_fast(t[0], t[1], t[2], t[3], fr);
-                            } else {
-#pragma unroll
-                                for (int u = 0; u < 4; ++u) packed |= ((unsigned)requant32(t[u], epi) & 0xffu) << (8 * u);
-                            }
-                            *reinterpret_cast<unsigned *>(lds + la) = packed;
-                        }
-                    } else {
-                        float t[4];
-#pragma unroll
-                        for (int u = 0; u < 4; ++u) {
-                            t[u] = acc[i][j][vq * 4 + u];
-                            if (epi.relu) t[u] = t[u] > 0.f ? t[u] : 0.f;
-                        }
-                        if (raw) {
-                            if (chv && m < m_end)
-                                *reinterpret_cast<float4 *>((float *)a.y + (size_t)m * a.K + kabs) =
-                                    make_float4(t[0], t[1], t[2], t[3]);
-                        } else {
-                            typedef _Float16 v4h __attribute__((ext_vector_type(4)));
-                            v4h hv = {(_Float16)t[0], (_Float16)t[1], (_Float16)t[2], (_Float16)t[3]};
-                            *reinterpret_cast<v4h *>(lds + la) = hv;
-                        }
-                    }
-                }
-            }
-        }
-    };
-    const bool fast = ES == 1 && fast_requant_ok(epi);
-    if (fast) run_epilogue(std::true_type{});
-    else run_epilogue(std::false_type{});
-    if (raw) return;
-    __syncthreads();
-    constexpr int CHUNK_ELEMS = 16 / ES;
-    char *yb = (char *)a.y;
-#pragma unroll 4
-    for (int idx = tid; idx < BP * CH16; idx += kThreads) {
-        const int row = idx / CH16, c16 = idx % CH16;
-        const int m = m0 + row;
-        const int ch = ch0 + c16 * CHUNK_ELEMS;
-        if (m >= m_end || ch >= pl.Kg) continue;
-        const v4i v = *reinterpret_cast<const v4i *>(lds + row * ROWB + ((c16 ^ (row & (CH16 - 1))) << 4));
-        char *dst = yb + ((size_t)m * a.K + (size_t)(g * pl.Kg + ch)) * ES;
-        if (a.y_vec16 && ch + CHUNK_ELEMS <= pl.Kg) {
-            *reinterpret_cast<v4i *>(dst) = v;
-        } else {
-            // ragged or unaligned tail: 4 bytes at a time (channel counts are multiples of 4)
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (ch + (u * 4 + 3) / ES < pl.Kg) *reinterpret_cast<int *>(dst + u * 4) = v[u];
-        }
-    }
+    TL::finish(acc, lds, a, t);
 }
 
 template <typename T, int BC, int BP, int WGC, int WGP, int NST, int WPE>
@@ -439,7 +226,7 @@ hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
 
 }  // namespace
 
-// The direct-to-LDS kernel zero-fills out-of-image taps and addresses buffers with 32-bit offsets.
+// The direct-to-LDS kernels zero-fill out-of-image taps and address buffers with 32-bit offsets.
 bool conv_mfma_dma_eligible(const ConvArgs &a) {
     if (a.x_bytes >= 0x7ffffff0ull || a.plan.wsum_off >= 0x7ffffff0ull) return false;
     if (a.R > 32 || a.s_eff > 32) return false;

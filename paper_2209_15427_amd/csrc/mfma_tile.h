@@ -1,0 +1,266 @@
+// Pieces shared by the MFMA convolution kernels that move their operands with direct-to-LDS
+// loads (conv_mfma_dma.hip, conv_patch.hip): MFMA wrappers, explicit LDS synchronisation helpers,
+// tile decoding (XCD-aware order, expert-aligned tiles of the grouped MoE launch), accumulator
+// initialisation and the fused epilogue.
+#pragma once
+
+#include <type_traits>
+
+#include "common.h"
+#include "epilogue.h"
+
+namespace mpq {
+namespace tile {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+
+#define MPQ_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+
+template <typename T> struct Mma;
+template <> struct Mma<int8_t> {
+    typedef v16i Acc;
+    static __device__ __forceinline__ Acc run(v4i a, v4i b, Acc c) {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Mma<_Float16> {
+    typedef v16f Acc;
+    static __device__ __forceinline__ Acc run(v4i a, v4i b, Acc c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c,
+                                                      0, 0, 0);
+    }
+};
+
+constexpr int kThreads = 256;
+constexpr unsigned kOob = 0x7ffffff0u;   // beyond any buffer these kernels accept (< 2 GiB)
+
+// LDS fragment read the compiler does not model as a memory access: it cannot tell the LDS stages
+// apart and would otherwise drain every outstanding direct-to-LDS load in front of each read.
+// The value arrives asynchronously: lds_wait() + lds_arrived() must come before its first use.
+template <int OFF> __device__ __forceinline__ v4i lds_read(unsigned addr) {
+    v4i r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+__device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+// ties a fragment's uses to the wait that precedes this statement
+__device__ __forceinline__ void lds_arrived(v4i &f) { asm volatile("" : "+v"(f)); }
+// workgroup barrier without the release/acquire fences of __syncthreads(): the fence would wait
+// for every outstanding direct-to-LDS load, not only for the step that is about to be read
+__device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// wait until at most N of this wavefront's vector-memory operations are outstanding
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// Which tile a workgroup owns.
+struct TileCtx {
+    int g;                 // convolution group
+    int ch0;               // first output channel of the tile, within the group
+    int m0;                // first output pixel (n, p, q order) of the tile
+    int m_begin, m_end;    // pixel range the tile may touch (the expert's samples in a grouped launch)
+    const char *wbase;     // packed weights (of the expert)
+    const char *bias;
+    Epi epi;
+};
+
+// Consecutive workgroups land on different XCDs, so each XCD is handed a contiguous range of
+// tiles (neighbouring tiles share input rows and weights in its L2).  In a grouped launch expert
+// e owns ceil(rows_e / BP) consecutive pixel tiles.  Returns false when the workgroup has no tile.
+template <int BC, int BP>
+__device__ __forceinline__ bool decode_tile(const ConvArgs &a, TileCtx &t) {
+    const Plan &pl = a.plan;
+    const int PQ = a.P * a.Q;
+    const int ctiles = (pl.Kg + BC - 1) / BC;
+    const int nblk = gridDim.x;
+    int bid = blockIdx.x;
+    {
+        const int per = nblk / 8, rem = nblk % 8, x = bid % 8, j = bid / 8;
+        bid = x * per + (x < rem ? x : rem) + j;
+    }
+    const int ct = bid % ctiles;
+    bid /= ctiles;
+    int pt = bid % a.ptiles;
+    t.g = bid / a.ptiles;
+    t.m_begin = 0;
+    t.m_end = a.N * PQ;
+    t.wbase = (const char *)a.w;
+    t.bias = (const char *)a.bias;
+    t.epi = a.epi;
+    if (a.seg.offsets) {
+        int e = 0, tile_base = 0;
+        bool found = false;
+        for (; e < a.seg.num_experts; ++e) {
+            int lo = a.seg.offsets[e], hi = a.seg.offsets[e + 1];
+            int tiles = ((hi - lo) * PQ + BP - 1) / BP;
+            if (pt < tile_base + tiles) {
+                t.m_begin = lo * PQ;
+                t.m_end = hi * PQ;
+                pt -= tile_base;
+                found = true;
+                break;
+            }
+            tile_base += tiles;
+        }
+        if (!found) return false;
+        t.wbase += (size_t)e * a.seg.w_stride;
+        if (t.bias) t.bias += (size_t)e * a.seg.bias_stride * 4;
+        t.epi = a.seg.epi[e];
+    }
+    t.m0 = t.m_begin + pt * BP;
+    t.ch0 = ct * BC;
+    return t.m0 < t.m_end;
+}
+
+// Per-wavefront view of a BC x BP tile: WGC x WGP wavefronts, each TC x TP MFMA tiles of 32 x 32.
+// Register v of lane l in a 32x32 tile holds channel 8*(v/4) + 4*(l/32) + v%4 of pixel l%32.
+template <typename T, int BC, int BP, int WGC, int WGP>
+struct Tile {
+    static constexpr int WTC = BC / WGC, WTP = BP / WGP;
+    static constexpr int TC = WTC / 32, TP = WTP / 32;
+    static constexpr int ES = (int)sizeof(T);
+    static constexpr int ROWB = BC * ES, CH16 = ROWB / 16;     // output image row in LDS
+    static constexpr int kImageBytes = BP * ROWB;
+    typedef typename Mma<T>::Acc Acc;
+    static_assert(WGC * WGP == 4, "four wavefronts per workgroup");
+    static_assert((CH16 & (CH16 - 1)) == 0, "chunks per output row must be a power of two");
+
+    // Accumulators start at the epilogue's per-channel constant: the bias, minus z_x * sum(w) for int8.
+    static __device__ __forceinline__ void init_acc(Acc (&acc)[TC][TP], const ConvArgs &a, const TileCtx &t) {
+        const Plan &pl = a.plan;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wc = wave % WGC;
+        const int *wsum = reinterpret_cast<const int *>(t.wbase + pl.wsum_off);
+#pragma unroll
+        for (int i = 0; i < TC; ++i) {
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+                const int ch = t.ch0 + wc * WTC + i * 32 + vq * 8 + (lane >> 5) * 4;
+                const int kabs = t.g * pl.Kg + (ch < pl.Kg ? ch : 0);
+                if constexpr (ES == 1) {
+                    v4i b4 = {0, 0, 0, 0};
+                    if (t.bias) b4 = *reinterpret_cast<const v4i *>(t.bias + (size_t)kabs * 4);
+                    if (t.epi.zx != 0) b4 -= *reinterpret_cast<const v4i *>(wsum + kabs) * t.epi.zx;
+#pragma unroll
+                    for (int j = 0; j < TP; ++j)
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) acc[i][j][vq * 4 + u] = b4[u];
+                } else {
+                    float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (t.bias) bb = *reinterpret_cast<const float4 *>(t.bias + (size_t)kabs * 4);
+#pragma unroll
+                    for (int j = 0; j < TP; ++j) {
+                        acc[i][j][vq * 4 + 0] = bb.x;
+                        acc[i][j][vq * 4 + 1] = bb.y;
+                        acc[i][j][vq * 4 + 2] = bb.z;
+                        acc[i][j][vq * 4 + 3] = bb.w;
+                    }
+                }
+            }
+        }
+    }
+
+    // Fused epilogue.  Storage-type outputs are requantized (int8; fast path for ReLU with a right
+    // shift: mulhi(t, mult) >> (shift - 1), see epilogue.h) or rounded to fp16, laid out in LDS as
+    // the tile's [pixel][channel] image (16-byte chunks XOR-swizzled by the pixel index), then
+    // written with 16-byte stores in which consecutive lanes cover consecutive channels of a pixel,
+    // so that every store instruction fills whole cache lines.  Raw accumulator outputs (gating
+    // logits) are stored directly.  `lds` must hold kImageBytes and be idle (barrier before).
+    static __device__ __forceinline__ void finish(Acc (&acc)[TC][TP], unsigned char *lds, const ConvArgs &a,
+                                                  const TileCtx &t) {
+        const Plan &pl = a.plan;
+        const Epi &epi = t.epi;
+        const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+        const int wc = wave % WGC, wp = wave / WGC;
+        const int frow = lane & 31, fk = lane >> 5;
+        const int g = t.g, m0 = t.m0, m_end = t.m_end, ch0 = t.ch0;
+        const bool raw = epi.kind == kEpiRawI32 || epi.kind == kEpiRawF32;
+        auto run_epilogue = [&](auto fast_tag) {
+            constexpr bool FAST = decltype(fast_tag)::value;
+            const FastRequant fr = make_fast_requant(epi);
+#pragma unroll
+            for (int i = 0; i < TC; ++i) {
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int chl = wc * WTC + i * 32 + vq * 8 + fk * 4;     // channel within the tile
+                    const int ch = ch0 + chl;
+                    const bool chv = ch < pl.Kg;
+                    const int kabs = g * pl.Kg + (chv ? ch : 0);
+                    const unsigned cb = (unsigned)(chl * ES);
+#pragma unroll
+                    for (int j = 0; j < TP; ++j) {
+                        const int row = wp * WTP + j * 32 + frow;
+                        const int m = m0 + row;
+                        const unsigned la =
+                            (unsigned)(row * ROWB) + (((cb >> 4) ^ (unsigned)(row & (CH16 - 1))) << 4) + (cb & 15u);
+                        if constexpr (ES == 1) {
+                            int q[4];
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) q[u] = acc[i][j][vq * 4 + u];
+                            if (raw) {
+                                if (chv && m < m_end)
+                                    *reinterpret_cast<v4i *>((int *)a.y + (size_t)m * a.K + kabs) = v4i{q[0], q[1], q[2], q[3]};
+                            } else {
+                                unsigned packed = 0;
+                                if constexpr (FAST) {
+                                    packed = requant4_fast(q[0], q[1], q[2], q[3], fr);
+                                } else {
+#pragma unroll
+                                    for (int u = 0; u < 4; ++u)
+                                        packed |= ((unsigned)requant32(q[u], epi) & 0xffu) << (8 * u);
+                                }
+                                *reinterpret_cast<unsigned *>(lds + la) = packed;
+                            }
+                        } else {
+                            float f[4];
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                f[u] = acc[i][j][vq * 4 + u];
+                                if (epi.relu) f[u] = f[u] > 0.f ? f[u] : 0.f;
+                            }
+                            if (raw) {
+                                if (chv && m < m_end)
+                                    *reinterpret_cast<float4 *>((float *)a.y + (size_t)m * a.K + kabs) =
+                                        make_float4(f[0], f[1], f[2], f[3]);
+                            } else {
+                                typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+                                v4h hv = {(_Float16)f[0], (_Float16)f[1], (_Float16)f[2], (_Float16)f[3]};
+                                *reinterpret_cast<v4h *>(lds + la) = hv;
+                            }
+                        }
+                    }
+                }
+            }
+        };
+        const bool fast = ES == 1 && fast_requant_ok(epi);
+        if (fast) run_epilogue(std::true_type{});
+        else run_epilogue(std::false_type{});
+        if (raw) return;
+        __syncthreads();
+        constexpr int CHUNK_ELEMS = 16 / ES;
+        char *yb = (char *)a.y;
+#pragma unroll 4
+        for (int idx = tid; idx < BP * CH16; idx += kThreads) {
+            const int row = idx / CH16, c16 = idx % CH16;
+            const int m = m0 + row;
+            const int ch = ch0 + c16 * CHUNK_ELEMS;
+            if (m >= m_end || ch >= pl.Kg) continue;
+            const v4i v = *reinterpret_cast<const v4i *>(lds + row * ROWB + ((c16 ^ (row & (CH16 - 1))) << 4));
+            char *dst = yb + ((size_t)m * a.K + (size_t)(g * pl.Kg + ch)) * ES;
+            if (a.y_vec16 && ch + CHUNK_ELEMS <= pl.Kg) {
+                *reinterpret_cast<v4i *>(dst) = v;
+            } else {
+                // ragged or unaligned tail: 4 bytes at a time (channel counts are multiples of 4)
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (ch + (u * 4 + 3) / ES < pl.Kg) *reinterpret_cast<int *>(dst + u * 4) = v[u];
+            }
+        }
+    }
+};
+
+}  // namespace tile
+}  // namespace mpq
