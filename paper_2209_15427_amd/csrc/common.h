@@ -95,12 +95,13 @@ struct ConvArgs {
     int ksteps;            // 64-byte steps along the packed reduction axis
     int tap_px;            // input pixels one tap spans (1, or the padded row length in row mode)
     int ptiles;            // pixel tiles in the grid (filled by the launcher)
+    unsigned magic_ct, magic_pt;   // magic_u32 of the channel / pixel tile counts (filled by the launcher)
     int y_vec16;           // output rows and channel-tile origins are 16-byte aligned
     int phased;            // walk the reduction axis channel block by channel block (see conv_mfma_dma.hip)
     // patch kernel (conv_patch.hip): chunks per pixel per channel block, channel blocks, steps per
     // block, and ceil(2^32 / d) for d = Wv, Hv * Wv, cbc
     int cbc, nphase, ksp;
-    unsigned magic_wv, magic_hw, magic_cbc;
+    unsigned magic_wv, magic_hw, magic_cbc, magic_s, magic_pq, magic_q;
     unsigned fill_word;    // the input zero-point replicated over 32 bits (out-of-image taps)
     unsigned long long x_bytes;   // size of the input tensor the kernel sees
     Plan plan;

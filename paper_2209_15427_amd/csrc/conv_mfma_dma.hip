@@ -209,9 +209,9 @@ hipError_t launch_one(ConvArgs a, hipStream_t st) {
     long long rows = (long long)a.N * PQ;
     int ptiles = (int)((rows + BP - 1) / BP);
     if (a.seg.offsets) ptiles += a.seg.num_experts;
-    a.ptiles = ptiles;
     long long blocks = (long long)ptiles * ctiles * a.groups;
     if (blocks <= 0) return hipSuccess;
+    if (!set_tile_counts(a, ptiles, ctiles)) return hipErrorInvalidValue;
     if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
     conv_mfma_dma_kernel<T, BC, BP, WGC, WGP, NST, WPE><<<(unsigned)blocks, kThreads, 0, st>>>(a);
     return hipGetLastError();

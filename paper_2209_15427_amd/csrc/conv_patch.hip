@@ -29,11 +29,7 @@ using namespace tile;
 
 constexpr int kMaxPatchSlots = 8;
 
-__device__ __forceinline__ unsigned udiv_magic(unsigned v, unsigned magic) {
-    return (unsigned)(((unsigned long long)v * magic) >> 32);
-}
-
-template <typename T, int BC, int BP, int WGC, int WGP, int NSTW, int NSLOT, int WPE>
+template <typename T, int BC, int BP, int WGC, int WGP, int NSTW, int NSLOT, int WPE, bool UNI>
 __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     typedef Tile<T, BC, BP, WGC, WGP> TL;
     constexpr int WTC = TL::WTC, WTP = TL::WTP, TC = TL::TC, TP = TL::TP, ES = TL::ES;
@@ -66,13 +62,13 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
 
     // ---- geometry of the virtual (zero-padded) input ------------------------------------------
     const int Hv = a.H + 2 * a.pad_h, Wv = a.W + 2 * a.pad_w, HWv = Hv * Wv;
-    const int cbc = a.cbc, CB = cbc * kChunkBytes;     // chunks / bytes per pixel per channel block
+    const int cbc = UNI ? 4 : a.cbc, CB = cbc * kChunkBytes;     // chunks / bytes per pixel per channel block
     const int CgB = pl.Cg * ES;                        // bytes per pixel per group
     const int NT = a.R * a.S;                          // taps
-    const unsigned swm = cbc == 4 ? 3u : 0u;           // 64-byte rows need the XOR swizzle
+    const unsigned swm = UNI ? 3u : 0u;                // 64-byte rows need the XOR swizzle
     auto virt = [&](int m) {                           // virtual pixel of output pixel m at tap (0, 0)
-        const int n = m / PQ, rem = m - n * PQ;
-        const int p = rem / a.Q, q = rem - p * a.Q;
+        const int n = (int)udiv_magic((unsigned)m, a.magic_pq), rem = m - n * PQ;
+        const int p = (int)udiv_magic((unsigned)rem, a.magic_q), q = rem - p * a.Q;
         return (n * Hv + p) * Wv + q;
     };
     const int v0 = virt(m0);
@@ -101,50 +97,70 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
         }
         xoff[k] = off;
     }
+    auto request_slot = [&](const int k, int buf, int cb) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, MPQ_LDS(lds + buf * PATCH_BYTES + (k * kThreads + wave * 64) * kChunkBytes),
+                                                 16, xoff[k] + (unsigned)(cb * CB), 0, 0, 0);
+    };
     auto request_patch = [&](int buf, int cb) {
-        unsigned char *dst = lds + buf * PATCH_BYTES;
 #pragma unroll
-        for (int k = 0; k < NSLOT; ++k)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, MPQ_LDS(dst + (k * kThreads + wave * 64) * kChunkBytes), 16,
-                                                     xoff[k] + (unsigned)(cb * CB), 0, 0, 0);
+        for (int k = 0; k < NSLOT; ++k) request_slot(k, buf, cb);
+    };
+    // one slot of the next phase's patch per step (the slot index must be a constant per load)
+    auto request_patch_part = [&](int k, int buf, int cb) {
+        static_assert(NSLOT <= 8, "slots are written out below");
+        switch (k) {
+        case 0: request_slot(0, buf, cb); break;
+        case 1: if constexpr (NSLOT > 1) request_slot(1, buf, cb); break;
+        case 2: if constexpr (NSLOT > 2) request_slot(2, buf, cb); break;
+        case 3: if constexpr (NSLOT > 3) request_slot(3, buf, cb); break;
+        case 4: if constexpr (NSLOT > 4) request_slot(4, buf, cb); break;
+        case 5: if constexpr (NSLOT > 5) request_slot(5, buf, cb); break;
+        case 6: if constexpr (NSLOT > 6) request_slot(6, buf, cb); break;
+        case 7: if constexpr (NSLOT > 7) request_slot(7, buf, cb); break;
+        }
     };
 
     // ---- weight stream: lane l fills slot l of a 16-row group (row l / 4, physical chunk l % 4);
-    // the chunk it fetches is kc = 4 kstep + logical chunk -> (tap, chunk within the channel block)
+    // the chunk it fetches is kc = 4 kstep + logical chunk -> (tap, chunk within the channel block).
+    // UNI (64-byte channel blocks): step = tap for every lane, all of this is scalar arithmetic.
     const int lrow = lane >> 2;
     const int lchunk = (lane & 3) ^ ((lane >> 4) & 3);
-    unsigned woff[LW];
+    // (fixed bounds on the arrays the lambdas below capture: see xoff)
+    static_assert(LW <= 2, "weight loads per thread");
+    unsigned woff[2];
 #pragma unroll
     for (int i = 0; i < LW; ++i) {
         const int ch = ch0 + (i * 4 + wave) * 16 + lrow;
-        woff[i] = ch < pl.Kg ? (unsigned)(((size_t)(g * pl.Kg + ch) * pl.Kp) * ES) : kOob;
+        woff[i] = ch < pl.Kg ? (unsigned)(((size_t)(g * pl.Kg + ch) * pl.Kp) * ES) + (UNI ? (unsigned)lchunk * kChunkBytes : 0u)
+                             : kOob;
     }
     const int KSP = a.ksp;                             // steps per phase
     int w_cb = 0, w_step = 0;                          // next weight step to request: (phase, step)
-    int w_tap = lchunk / cbc, w_cc = lchunk - w_tap * cbc;
     auto request_weights = [&](int stage) {
         // past the last phase the requests continue (uniform outstanding-load count) and read zeros
-        const bool ok = w_tap < NT && w_cb < a.nphase;
-        const unsigned kbyte = (unsigned)(w_tap * CgB + w_cb * CB + w_cc * kChunkBytes);
-#pragma unroll
-        for (int i = 0; i < LW; ++i) {
-            const unsigned vo = ok ? woff[i] + kbyte : kOob;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MPQ_LDS(wring + stage * WSTAGE + (i * 4 + wave) * 1024), 16,
-                                                     vo, 0, 0, 0);
+        unsigned kbyte;
+        if constexpr (UNI) {
+            kbyte = w_cb < a.nphase ? (unsigned)(w_step * CgB + w_cb * CB) : kOob;
+        } else {
+            const unsigned kc = (unsigned)(w_step * 4 + lchunk);
+            const unsigned tap = udiv_magic(kc, a.magic_cbc);
+            const unsigned cc = kc - tap * (unsigned)cbc;
+            kbyte = ((int)tap < NT && w_cb < a.nphase) ? tap * (unsigned)CgB + cc * kChunkBytes + (unsigned)(w_cb * CB) : kOob;
         }
+#pragma unroll
+        for (int i = 0; i < LW; ++i)       // woff < 2^31 and kOob < 2^31: the sum cannot wrap back into range
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MPQ_LDS(wring + stage * WSTAGE + (i * 4 + wave) * 1024), 16,
+                                                     woff[i] + kbyte, 0, 0, 0);
         if (++w_step == KSP) {
             w_step = 0;
             ++w_cb;
-            w_tap = lchunk / cbc;
-            w_cc = lchunk - w_tap * cbc;
-        } else {
-            w_cc += 4;
-            while (w_cc >= cbc) {
-                w_cc -= cbc;
-                ++w_tap;
-            }
         }
     };
+
+    // first requests go out before the rest of the set-up, which then overlaps their latency
+    request_patch(0, 0);
+    request_weights(0);
+    request_weights(1);
 
     Acc acc[TC][TP];
     TL::init_acc(acc, a, t);
@@ -154,100 +170,125 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     const unsigned sw = (unsigned)((frow >> 2) & 3);
     const unsigned fa0 = (unsigned)((wc * WTC + frow) * kStepBytes) + ((0u + fk) ^ sw) * kChunkBytes;
     const unsigned fa1 = (unsigned)((wc * WTC + frow) * kStepBytes) + ((2u + fk) ^ sw) * kChunkBytes;
-    // B: patch row of this lane's pixel in each 32-pixel sub-tile (tap (0,0)); pixels past the
-    // tile's end reuse the last valid one (their results are never stored)
-    int vrow[TP];
+    // B: byte address (within patch buffer 0) of this lane's pixel in each 32-pixel sub-tile at
+    // tap (0,0); pixels past the tile's end reuse the last valid one (their results are never
+    // stored).  UNI adds the lane's half of the reduction step here, the swizzle comes per step.
+    unsigned vb[4];
 #pragma unroll
     for (int j = 0; j < TP; ++j) {
         int m = m0 + wp * WTP + j * 32 + frow;
         m = m <= m_last ? m : m_last;
-        vrow[j] = virt(m) - v0;
+        vb[j] = (unsigned)(size_t)MPQ_LDS(lds) + (unsigned)((virt(m) - v0) * CB) + (UNI ? (unsigned)fk * kChunkBytes : 0u);
     }
-    // this lane's chunk for sub-step ks is kc = 4 kstep + 2 ks + fk -> (tap, cc); delta = r Wv + s
-    int b_tap[2], b_cc[2], b_s[2], b_delta[2];
-    auto reset_b = [&]() {
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const int kc = 2 * ks + fk;
-            b_tap[ks] = kc / cbc;
-            b_cc[ks] = kc - b_tap[ks] * cbc;
-            const int r = b_tap[ks] / a.S;
-            b_s[ks] = b_tap[ks] - r * a.S;
-            b_delta[ks] = r * Wv + b_s[ks];
-        }
-    };
-    auto advance_b = [&]() {
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            b_cc[ks] += 4;
-            while (b_cc[ks] >= cbc) {
-                b_cc[ks] -= cbc;
-                ++b_tap[ks];
-                ++b_delta[ks];
-                if (++b_s[ks] == a.S) {
-                    b_s[ks] = 0;
-                    b_delta[ks] += Wv - a.S;
-                }
-            }
-        }
-    };
-    reset_b();
+    const int dWv = Wv - a.S;
+    // read position: the step whose fragments are fetched next (in-phase index, patch buffer, and
+    // for UNI the patch-row offset r Wv + s of its tap)
+    int r_step = 0, r_pbuf = 0, u_s = 0, u_delta = 0;
+    unsigned ba[4];                                    // UNI: this step's first-half B addresses
 
-    auto multiply = [&](int stage, int pbuf) {
+    // Fragments are fetched half a reduction step (one 32-byte k-slice) ahead of the matrix
+    // instructions that use them: set 0 / set 1 hold the first / second half.
+    v4i af[2][TC], bf[2][TP];
+    auto fetch = [&](const int ks, int stage) {
         const unsigned wbase_l = (unsigned)(size_t)MPQ_LDS(wring + stage * WSTAGE);
-        const unsigned pbase_l = (unsigned)(size_t)MPQ_LDS(lds + pbuf * PATCH_BYTES);
-        v4i af[2][TC], bf[2][TP];
+        const unsigned fa = wbase_l + (ks == 0 ? fa0 : fa1);
+        af[ks][0] = lds_read<0>(fa);
+        if constexpr (TC > 1) af[ks][1] = lds_read<2048>(fa);
+        if constexpr (UNI) {
+            // rows are 64 bytes: chunk c of row r sits at slot c ^ ((r >> 2) & 3); the buffers are
+            // 1 KiB aligned, so bits 8..9 of the byte address are bits 2..3 of the row.  The second
+            // half's chunk is the first half's with bit 1 flipped.
+            if (ks == 0) {
+                const unsigned so = (unsigned)(u_delta * (int)kStepBytes + r_pbuf * PATCH_BYTES);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            const unsigned fa = ks == 0 ? fa0 : fa1;
-            af[ks][0] = lds_read<0>(wbase_l + fa);
-            if constexpr (TC > 1) af[ks][1] = lds_read<2048>(wbase_l + fa);
-            // a lane whose chunk lies past the last tap multiplies zero weights: keep its address valid
-            const int delta = b_tap[ks] < NT ? b_delta[ks] : 0;
+                for (int j = 0; j < TP; ++j) {
+                    const unsigned tt = vb[j] + so;
+                    ba[j] = tt ^ ((tt >> 4) & 0x30u);
+                    bf[0][j] = lds_read<0>(ba[j]);
+                }
+            } else {
 #pragma unroll
-            for (int j = 0; j < TP; ++j) {
-                const unsigned row = (unsigned)(vrow[j] + delta);
-                const unsigned addr = pbase_l + row * (unsigned)CB + (((unsigned)b_cc[ks] ^ ((row >> 2) & swm)) << 4);
-                bf[ks][j] = lds_read<0>(addr);
+                for (int j = 0; j < TP; ++j) bf[1][j] = lds_read<0>(ba[j] ^ 32u);
             }
+        } else {
+            // this lane's chunk is kc = 4 step + 2 ks + fk -> (tap, cc); tap = r S + s sits r Wv + s rows on.
+            // A lane whose chunk lies past the last tap multiplies zero weights: keep its address valid.
+            const unsigned kc = (unsigned)(r_step * 4 + 2 * ks + fk);
+            unsigned tap = udiv_magic(kc, a.magic_cbc);
+            const unsigned cc = kc - tap * (unsigned)cbc;
+            tap = (int)tap < NT ? tap : 0u;
+            const unsigned r = udiv_magic(tap, a.magic_s);
+            const unsigned delta = tap + r * (unsigned)dWv;
+            const unsigned o = delta * (unsigned)CB + cc * kChunkBytes + (unsigned)(r_pbuf * PATCH_BYTES);
+#pragma unroll
+            for (int j = 0; j < TP; ++j) bf[ks][j] = lds_read<0>(vb[j] + o);
         }
+    };
+    auto arrived = [&](const int ks) {
         lds_wait();
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int i = 0; i < TC; ++i) lds_arrived(af[ks][i]);
 #pragma unroll
-            for (int i = 0; i < TC; ++i) lds_arrived(af[ks][i]);
+        for (int j = 0; j < TP; ++j) lds_arrived(bf[ks][j]);
+    };
+    auto multiply = [&](const int ks) {
 #pragma unroll
-            for (int j = 0; j < TP; ++j) lds_arrived(bf[ks][j]);
-        }
+        for (int i = 0; i < TC; ++i)
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int i = 0; i < TC; ++i)
-#pragma unroll
-                for (int j = 0; j < TP; ++j) acc[i][j] = Mma<T>::run(af[ks][i], bf[ks][j], acc[i][j]);
-        advance_b();
+            for (int j = 0; j < TP; ++j) acc[i][j] = Mma<T>::run(af[ks][i], bf[ks][j], acc[i][j]);
     };
 
     // ---- pipeline ---------------------------------------------------------------------------------
-    request_patch(0, 0);
-#pragma unroll
-    for (int p = 0; p < NSTW - 1; ++p) request_weights(p);
-    int cur = 0, refill = NSTW - 1;
+    // Requests complete in order, so a weight load queued behind a whole patch would stall the
+    // loop until that patch is in: the next phase's patch goes out one slot per step instead.
+    // Issue order: P(0) W(0) W(1) | W(2) | then per step k: p(k) W(k + 3), where p(k) is slot
+    // ks of the next phase's patch while the in-phase step index ks < NSLOT.  Step k needs W(k + 1)
+    // before its second half; what was issued after W(k + 1) may stay outstanding: p(k - 1), if
+    // there was one, and W(k + 2).  The last slot leaves in step NSLOT - 1 <= KSP - 3, ahead of the
+    // W that the phase's last step waits for, so the patch is complete when the phase ends.
+    wait_vmcnt<LW>();
+    bare_barrier();
+    request_weights(2);
+    fetch(0, 0);
+    int cur = 0;
     for (int cb = 0; cb < a.nphase; ++cb) {
         for (int ks = 0; ks < KSP; ++ks) {
-            // the weights of this step have landed when at most the later steps' loads -- and, for
-            // the two steps after a patch request, that patch's loads -- are outstanding
-            if (ks >= 1 && ks <= NSTW - 1 && cb + 1 < a.nphase) wait_vmcnt<LW *(NSTW - 2) + NSLOT>();
-            else wait_vmcnt<LW *(NSTW - 2)>();
-            bare_barrier();              // everyone's have; everyone is done with `refill` (and, at
-                                         // a phase start, with the patch buffer of two phases ago)
-            request_weights(refill);
-            if (ks == 0 && cb + 1 < a.nphase) request_patch((cb + 1) & 1, cb + 1);
-            multiply(cur, cb & 1);
-            cur = cur + 1 == NSTW ? 0 : cur + 1;
-            refill = refill + 1 == NSTW ? 0 : refill + 1;
+            arrived(0);
+            fetch(1, cur);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(0);
+            __builtin_amdgcn_sched_barrier(0);
+            arrived(1);                  // this wave is done reading ring slot `cur`
+            const bool phase_end = ks + 1 == KSP;
+            const int nxt = cur + 1 == NSTW ? 0 : cur + 1;
+            if (!(phase_end && cb + 1 == a.nphase)) {
+                const bool more = cb + 1 < a.nphase;
+                if (more && ks >= 1 && ks <= NSLOT) wait_vmcnt<LW + 1>();
+                else wait_vmcnt<LW>();
+                bare_barrier();          // everyone has step k + 1 and is done with slot `cur` (and, at
+                                         // a phase end, with this phase's patch buffer)
+                if (more && ks < NSLOT) request_patch_part(ks, (cb + 1) & 1, cb + 1);
+                request_weights(cur);
+                if (phase_end) {
+                    r_step = 0;
+                    r_pbuf ^= 1;
+                    u_s = 0;
+                    u_delta = 0;
+                } else {
+                    ++r_step;
+                    ++u_delta;
+                    if (++u_s == a.S) {
+                        u_s = 0;
+                        u_delta += dWv;
+                    }
+                }
+                fetch(0, nxt);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            multiply(1);
+            __builtin_amdgcn_sched_barrier(0);
+            cur = nxt;
         }
-        reset_b();
     }
     wait_vmcnt<0>();
     bare_barrier();
@@ -255,26 +296,24 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     TL::finish(acc, lds, a, t);
 }
 
-template <typename T, int BC, int BP, int WGC, int WGP, int NSTW, int NSLOT, int WPE>
+template <typename T, int BC, int BP, int WGC, int WGP, int NSTW, int NSLOT, int WPE, bool UNI>
 hipError_t launch_one(ConvArgs a, hipStream_t st) {
     const int PQ = a.P * a.Q;
     const int ctiles = (a.plan.Kg + BC - 1) / BC;
     long long rows = (long long)a.N * PQ;
     int ptiles = (int)((rows + BP - 1) / BP);
     if (a.seg.offsets) ptiles += a.seg.num_experts;
-    a.ptiles = ptiles;
     long long blocks = (long long)ptiles * ctiles * a.groups;
     if (blocks <= 0) return hipSuccess;
+    if (!set_tile_counts(a, ptiles, ctiles)) return hipErrorInvalidValue;
     if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
-    conv_patch_kernel<T, BC, BP, WGC, WGP, NSTW, NSLOT, WPE><<<(unsigned)blocks, kThreads, 0, st>>>(a);
+    conv_patch_kernel<T, BC, BP, WGC, WGP, NSTW, NSLOT, WPE, UNI><<<(unsigned)blocks, kThreads, 0, st>>>(a);
     return hipGetLastError();
 }
 
 constexpr int kPatchSlots = 7;                                  // 16-byte loads per thread
 constexpr int kPatchBytes = kPatchSlots * 256 * kChunkBytes;    // 28 KiB per patch buffer
 constexpr int kBP = 256;
-
-unsigned magic_for(unsigned d) { return (unsigned)(((1ull << 32) + d - 1) / d); }
 
 }  // namespace
 
@@ -294,7 +333,7 @@ bool conv_patch_prepare(ConvArgs &a) {
     a.nphase = CgB / CB;
     const int NT = a.R * a.S;                          // taps
     a.ksp = (NT * a.cbc + 3) / 4;
-    if (a.ksp < 4) return false;                 // too few steps per phase to hide the patch load
+    if (a.ksp < kPatchSlots + 2) return false;   // one patch slot per step must finish two steps early
     const int Hv = a.H + 2 * a.pad_h, Wv = a.W + 2 * a.pad_w, PQ = a.P * a.Q;
     // largest virtual run any tile of kBP consecutive output pixels can need
     long long worst = 0;
@@ -309,21 +348,37 @@ bool conv_patch_prepare(ConvArgs &a) {
     if (worst * CB > kPatchBytes) return false;
     const unsigned long long vmax = (unsigned long long)(a.N + 1) * Hv * Wv + kPatchBytes;
     if (vmax * (unsigned long long)(Hv * Wv) >= (1ull << 32)) return false;    // exactness of the magic division
-    a.magic_wv = magic_for((unsigned)Wv);
-    a.magic_hw = magic_for((unsigned)(Hv * Wv));
-    a.magic_cbc = magic_for((unsigned)a.cbc);
+    a.magic_wv = magic_u32((unsigned)Wv);
+    a.magic_hw = magic_u32((unsigned)(Hv * Wv));
+    a.magic_cbc = magic_u32((unsigned)a.cbc);
+    a.magic_s = magic_u32((unsigned)a.S);
+    // output pixel -> (n, p, q): m < N PQ + BP, rem < PQ
+    if (a.S < 2 || a.Q < 2 || PQ < 2 || !magic_exact((unsigned long long)a.N * PQ + kBP, (unsigned)PQ)) return false;
+    a.magic_pq = magic_u32((unsigned)PQ);
+    a.magic_q = magic_u32((unsigned)a.Q);
     return true;
 }
 
-hipError_t launch_conv_patch(const ConvArgs &a, hipStream_t st) {
+namespace {
+
+template <typename T>
+hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
     const int Kg = a.plan.Kg;
     const bool wide = Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0);
-    if (a.in_dtype == MPQ_INT8) {
-        if (wide) return launch_one<int8_t, 128, kBP, 2, 2, 3, kPatchSlots, 2>(a, st);
-        return launch_one<int8_t, 64, kBP, 1, 4, 3, kPatchSlots, 2>(a, st);
+    const bool uni = a.cbc == 4;                       // 64-byte channel blocks: one tap per step
+    if (wide) {
+        if (uni) return launch_one<T, 128, kBP, 2, 2, 3, kPatchSlots, 2, true>(a, st);
+        return launch_one<T, 128, kBP, 2, 2, 3, kPatchSlots, 2, false>(a, st);
     }
-    if (wide) return launch_one<_Float16, 128, kBP, 2, 2, 3, kPatchSlots, 2>(a, st);
-    return launch_one<_Float16, 64, kBP, 1, 4, 3, kPatchSlots, 2>(a, st);
+    if (uni) return launch_one<T, 64, kBP, 1, 4, 3, kPatchSlots, 2, true>(a, st);
+    return launch_one<T, 64, kBP, 1, 4, 3, kPatchSlots, 2, false>(a, st);
+}
+
+}  // namespace
+
+hipError_t launch_conv_patch(const ConvArgs &a, hipStream_t st) {
+    if (a.in_dtype == MPQ_INT8) return launch_typed<int8_t>(a, st);
+    return launch_typed<_Float16>(a, st);
 }
 
 }  // namespace mpq

@@ -15,11 +15,18 @@ inline int grid_for(size_t work, int threads, int max_blocks = 256 * 32) {
     return (int)b;
 }
 
-// round-half-even of the fp64 quotient, + zero-point, clamped; NaN -> zero-point
-__device__ __forceinline__ int quant_one(float r, double scale, int zp, int lo, int hi) {
-    double v = (double)r;
+// round-half-even of the fp64 quotient, + zero-point, clamped; NaN -> zero-point.
+// The quotient is first approximated by a product with the reciprocal (relative error below
+// 2^-51); rounding that approximation gives the same integer as rounding the correctly rounded
+// quotient unless it lies within 2^-40 (relative) of a rounding boundary k + 1/2, and only then
+// is the division carried out.
+__device__ __forceinline__ int quant_one(float r, double scale, double inv_scale, int zp, int lo, int hi) {
+    const double v = (double)r;
     if (v != v) return zp;
-    double t = __builtin_rint(v / scale);
+    const double ta = v * inv_scale;
+    double t = __builtin_rint(ta);
+    const double d = __builtin_fabs(__builtin_fabs(ta - t) - 0.5);
+    if (d <= __builtin_fabs(ta) * 0x1p-40) t = __builtin_rint(v / scale);
     t = t > 4.0e9 ? 4.0e9 : (t < -4.0e9 ? -4.0e9 : t);
     long long o = (long long)t + (long long)zp;
     o = o < lo ? lo : (o > hi ? hi : o);
@@ -30,17 +37,16 @@ template <typename OutT>
 __global__ void __launch_bounds__(kThreads)
 quantize_kernel(const float *__restrict__ src, OutT *__restrict__ dst, size_t n, float scale,
                 int zp, int lo, int hi, int vec_ok) {
-    const double s = (double)scale;
+    const double s = (double)scale, inv = 1.0 / s;
     size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t nthreads = (size_t)gridDim.x * blockDim.x;
     size_t n4 = vec_ok ? n / 4 : 0;
-    for (size_t i = tid; i < n4; i += nthreads) {
-        float4 v = reinterpret_cast<const float4 *>(src)[i];
+    auto emit = [&](size_t i, float4 v) {
         OutT o[4];
-        o[0] = (OutT)quant_one(v.x, s, zp, lo, hi);
-        o[1] = (OutT)quant_one(v.y, s, zp, lo, hi);
-        o[2] = (OutT)quant_one(v.z, s, zp, lo, hi);
-        o[3] = (OutT)quant_one(v.w, s, zp, lo, hi);
+        o[0] = (OutT)quant_one(v.x, s, inv, zp, lo, hi);
+        o[1] = (OutT)quant_one(v.y, s, inv, zp, lo, hi);
+        o[2] = (OutT)quant_one(v.z, s, inv, zp, lo, hi);
+        o[3] = (OutT)quant_one(v.w, s, inv, zp, lo, hi);
         if constexpr (sizeof(OutT) == 1) {
             reinterpret_cast<uint32_t *>(dst)[i] = *reinterpret_cast<uint32_t *>(o);
         } else if constexpr (sizeof(OutT) == 2) {
@@ -48,8 +54,18 @@ quantize_kernel(const float *__restrict__ src, OutT *__restrict__ dst, size_t n,
         } else {
             reinterpret_cast<uint4 *>(dst)[i] = *reinterpret_cast<uint4 *>(o);
         }
+    };
+    // four independent loads in flight per thread
+    size_t i = tid;
+    for (; i + 3 * nthreads < n4; i += 4 * nthreads) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = reinterpret_cast<const float4 *>(src)[i + u * nthreads];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) emit(i + u * nthreads, v[u]);
     }
-    for (size_t i = n4 * 4 + tid; i < n; i += nthreads) dst[i] = (OutT)quant_one(src[i], s, zp, lo, hi);
+    for (; i < n4; i += nthreads) emit(i, reinterpret_cast<const float4 *>(src)[i]);
+    for (size_t j = n4 * 4 + tid; j < n; j += nthreads) dst[j] = (OutT)quant_one(src[j], s, inv, zp, lo, hi);
 }
 
 template <typename InT>
@@ -165,10 +181,14 @@ maxpool_kernel(const T *__restrict__ x, T *__restrict__ y, int N, int H, int W, 
 }
 
 // 16-byte-per-thread variant for int8 (C % 16 == 0): max over the window on 16 channels at once.
+// There is no packed 8-bit max: the even and the odd bytes of every dword are moved to the high
+// byte of a 16-bit lane (where the byte's sign is the lane's sign), the running maxima are kept in
+// that split form (packed 16-bit max), and the halves are merged once at the end.
 __global__ void __launch_bounds__(kThreads)
 maxpool_i8x16_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, int N, int H, int W, int C,
                      int P, int Q, int k, int st) {
-    typedef signed char v16c __attribute__((ext_vector_type(16)));
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    typedef short v2s __attribute__((ext_vector_type(2)));
     int cv = C / 16;
     size_t total = (size_t)N * P * Q * cv;
     size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -181,13 +201,24 @@ maxpool_i8x16_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, int N
         int p = (int)(np % P);
         int n = (int)(np / P);
         const int8_t *base = x + (((size_t)n * H + (size_t)p * st) * W + (size_t)q * st) * C + c * 16;
-        v16c m = *reinterpret_cast<const v16c *>(base);
+        v2s me[4], mo[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) me[u] = mo[u] = v2s{(short)-32768, (short)-32768};
         for (int r = 0; r < k; ++r)
             for (int s = 0; s < k; ++s) {
-                v16c v = *reinterpret_cast<const v16c *>(base + ((size_t)r * W + s) * C);
-                m = __builtin_elementwise_max(m, v);
+                const v4u v = *reinterpret_cast<const v4u *>(base + ((size_t)r * W + s) * C);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const unsigned e = (v[u] << 8) & 0xff00ff00u, o = v[u] & 0xff00ff00u;
+                    me[u] = __builtin_elementwise_max(me[u], __builtin_bit_cast(v2s, e));
+                    mo[u] = __builtin_elementwise_max(mo[u], __builtin_bit_cast(v2s, o));
+                }
             }
-        *reinterpret_cast<v16c *>(y + px * C + c * 16) = m;
+        v4u m;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            m[u] = (__builtin_bit_cast(unsigned, mo[u]) & 0xff00ff00u) | ((__builtin_bit_cast(unsigned, me[u]) >> 8) & 0x00ff00ffu);
+        *reinterpret_cast<v4u *>(y + px * C + c * 16) = m;
     }
 }
 

@@ -57,6 +57,20 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 0xf) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
+// Division by a run-time constant: with magic = ceil(2^32 / d), d >= 2, the high half of v * magic
+// is floor(v / d) for every v with v * d < 2^32 (the host checks the range it uses).
+__device__ __forceinline__ unsigned udiv_magic(unsigned v, unsigned magic) { return __umulhi(v, magic); }
+inline unsigned magic_u32(unsigned d) { return d < 2 ? 0u : (unsigned)(((1ull << 32) + d - 1) / d); }
+inline bool magic_exact(unsigned long long vmax, unsigned d) { return vmax * d < (1ull << 32); }
+// the launchers' part of ConvArgs; false when the grid is too large for the magic divisions
+inline bool set_tile_counts(ConvArgs &a, int ptiles, int ctiles) {
+    a.ptiles = ptiles;
+    a.magic_pt = magic_u32((unsigned)ptiles);
+    a.magic_ct = magic_u32((unsigned)ctiles);
+    const unsigned long long blocks = (unsigned long long)ptiles * ctiles * a.groups;
+    return magic_exact(blocks, (unsigned)ptiles) && magic_exact(blocks, (unsigned)ctiles);
+}
+
 // Which tile a workgroup owns.
 struct TileCtx {
     int g;                 // convolution group
@@ -82,10 +96,10 @@ __device__ __forceinline__ bool decode_tile(const ConvArgs &a, TileCtx &t) {
         const int per = nblk / 8, rem = nblk % 8, x = bid % 8, j = bid / 8;
         bid = x * per + (x < rem ? x : rem) + j;
     }
-    const int ct = bid % ctiles;
-    bid /= ctiles;
-    int pt = bid % a.ptiles;
-    t.g = bid / a.ptiles;
+    const int b1 = ctiles > 1 ? (int)udiv_magic((unsigned)bid, a.magic_ct) : bid;
+    const int ct = bid - b1 * ctiles;
+    t.g = a.ptiles > 1 ? (int)udiv_magic((unsigned)b1, a.magic_pt) : b1;
+    int pt = b1 - t.g * a.ptiles;
     t.m_begin = 0;
     t.m_end = a.N * PQ;
     t.wbase = (const char *)a.w;
