@@ -4,18 +4,21 @@
 // with the monotone requantization and is taken on the int8 codes).
 //
 // Why a kernel of its own: with C = 3 the reduction axis of one output pixel is R short runs of
-// S * C bytes, the layer is bound by activation traffic rather than by the matrix cores, and its
-// output (the largest tensor of the network) is immediately pooled 4:1.  So one workgroup
-//   1. keeps the whole packed weight matrix (K <= 96 rows x R * 48 bytes) in LDS,
-//   2. copies the input rows a strip of output rows needs from HBM once, as raw N,H,W,3 bytes,
-//      and expands them in LDS to 4 bytes per pixel, so that every tap run starts 16-byte aligned
-//      (the 4th byte meets a zero weight),
+// S * C bytes, the layer is bound by activation traffic and by the work around the matrix
+// instructions rather than by the matrix cores, and its output (the largest tensor of the
+// network) is immediately pooled 4:1.  One persistent workgroup per compute unit
+//   1. loads the whole packed weight matrix (K <= 96 rows x R * 48 bytes) and the per-channel
+//      accumulator start values into LDS once,
+//   2. walks strips of output rows (blockIdx.x, + gridDim.x, ...).  Per strip: the raw N,H,W,3
+//      input rows arrive by direct-to-LDS loads that were issued a strip earlier, and are
+//      expanded in LDS to 4 bytes per pixel, so that every tap run starts 16-byte aligned (the
+//      4th byte meets a zero weight),
 //   3. feeds the MFMA B operand straight from that patch -- an output pixel's run for kernel row r
 //      is 48 contiguous bytes at (stride * p + r) * pitch + stride * q * 4 -- and the A operand
 //      from the resident weights (row pitch 33 chunks: odd, hence bank-conflict free), with no
 //      barrier inside the reduction loop,
-//   4. requantizes into an LDS image of the strip's convolution output, pools it there, and
-//      writes only the pooled rows, channel-contiguous.
+//   4. requantizes into an LDS image of the strip's convolution output (it overwrites the
+//      consumed patch), pools it there, and writes only the pooled rows, channel-contiguous.
 // HBM traffic: input once (+ halo rows between strips), pooled output once.
 #include <type_traits>
 
@@ -58,11 +61,11 @@ struct FirstArgs {
     int Kp;               // packed weight row length in bytes
     int pitch;            // bytes per expanded patch row (multiple of 16, > W * 4)
     int max_in_rows;      // input rows a full strip needs
-    unsigned w_magic;     // ceil(2^32 / W)
+    unsigned q_magic, qo_magic, kd_magic, w_magic;   // ceil(2^32 / d) for d = Q, Qo, K / 4, W
     unsigned long long x_bytes;
     size_t wsum_off;
     // LDS layout (bytes)
-    int lds_w, lds_patch, lds_stage;
+    int lds_w, lds_patch, lds_extra, lds_stage;
     Epi epi;
 };
 
@@ -73,53 +76,69 @@ __device__ __forceinline__ v4i lds_read16(unsigned addr) {
 }
 __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void lds_arrived(v4i &f) { asm volatile("" : "+v"(f)); }
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() carries a fence that also waits
+// for the direct-to-LDS loads in flight, i.e. for the next strip's patch.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// byte-wise signed max of two packed int8x4 words (v_pk_max_i16 on the bytes moved to the high
-// half of each 16-bit lane, where their sign bit is the lane's sign bit)
-__device__ __forceinline__ unsigned max_i8x4(unsigned a, unsigned b) {
+// Running byte-wise signed max of packed int8x4 words.  There is no packed 8-bit max: the even and
+// the odd bytes are moved to the high byte of a 16-bit lane (where the byte's sign is the lane's
+// sign), the maxima are kept in that split form (packed 16-bit max) and merged at the end.
+struct MaxI8x4 {
     typedef short v2s __attribute__((ext_vector_type(2)));
-    const unsigned ae = (a << 8) & 0xff00ff00u, be = (b << 8) & 0xff00ff00u;   // bytes 0, 2
-    const unsigned ao = a & 0xff00ff00u, bo = b & 0xff00ff00u;                 // bytes 1, 3
-    const v2s me = __builtin_elementwise_max(__builtin_bit_cast(v2s, ae), __builtin_bit_cast(v2s, be));
-    const v2s mo = __builtin_elementwise_max(__builtin_bit_cast(v2s, ao), __builtin_bit_cast(v2s, bo));
-    return (__builtin_bit_cast(unsigned, mo) & 0xff00ff00u) | ((__builtin_bit_cast(unsigned, me) >> 8) & 0x00ff00ffu);
-}
+    v2s me = {(short)-32768, (short)-32768}, mo = {(short)-32768, (short)-32768};
+    __device__ __forceinline__ void add(unsigned v) {
+        me = __builtin_elementwise_max(me, __builtin_bit_cast(v2s, (v << 8) & 0xff00ff00u));
+        mo = __builtin_elementwise_max(mo, __builtin_bit_cast(v2s, v & 0xff00ff00u));
+    }
+    __device__ __forceinline__ unsigned get() const {
+        return (__builtin_bit_cast(unsigned, mo) & 0xff00ff00u) | ((__builtin_bit_cast(unsigned, me) >> 8) & 0x00ff00ffu);
+    }
+};
 
-__global__ void __launch_bounds__(kThreads, 2) conv_first_kernel(FirstArgs a) {
+__global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-    unsigned char *wl = lds;                       // [96][Kp] weights
-    unsigned char *patch = lds + a.lds_w;          // [in_rows][pitch] expanded input
-    unsigned char *stage = patch + a.lds_patch;    // raw input bytes, later the output image
+    unsigned char *wl = lds;                                   // [96][Kp] weights
+    int *cst = reinterpret_cast<int *>(lds + a.lds_w);         // [96] accumulator start values
+    unsigned char *patch = lds + a.lds_w + 1024;               // [in_rows][pitch] expanded input, then the
+    unsigned char *image = patch;                              // strip's output image (runs on past it)
+    unsigned char *stage = patch + a.lds_patch + a.lds_extra;  // raw input rows of the next strip
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n = blockIdx.x / a.strips, strip = blockIdx.x % a.strips;
+    const int frow = lane & 31, fk = lane >> 5;
+    const Epi epi = a.epi;
+    const int total_strips = a.N * a.strips;
 
-    // ---- strip geometry (uniform) -------------------------------------------------------------
-    const int o0 = strip * a.rows_per_strip;                                   // first final-output row
-    const int orows = min(a.rows_per_strip, a.Po - o0);
-    const int c0 = a.pool ? 2 * o0 : o0;                                       // first convolution row
-    const int crows = a.pool ? 2 * orows + 1 : orows;
-    const int npix = crows * a.Q;
-    const int h_first = c0 * a.stride;
-    const int in_rows = (crows - 1) * a.stride + a.R;
+    const __amdgpu_buffer_rsrc_t xrs =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.x, (short)0, (int)a.x_bytes, 0x00020000);
 
-    // ---- 1. weights and raw input rows -> LDS (direct-to-LDS loads, 16 bytes per lane) -----------
-    {
-        const __amdgpu_buffer_rsrc_t wrs =
-            __builtin_amdgcn_make_buffer_rsrc((void *)a.w, (short)0, a.K * a.Kp, 0x00020000);
-        const int wchunks = kMaxK * a.Kp / 16;
-        for (int c = wave * 64; c < wchunks; c += kThreads)      // rows >= K read past the buffer: zeros
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MPQ_LDS(wl + c * 16), 16, (c + lane) * 16, 0, 0, 0);
-    }
-    const long long start = ((long long)n * a.H + h_first) * a.W * a.C;        // first byte needed
-    const int sh16 = (int)(start & 15);
-    {
-        const __amdgpu_buffer_rsrc_t xrs =
-            __builtin_amdgcn_make_buffer_rsrc((void *)a.x, (short)0, (int)a.x_bytes, 0x00020000);
-        const unsigned base = (unsigned)(start - sh16);
-        const int rchunks = (sh16 + in_rows * a.W * a.C + 15) / 16;
-        unsigned tail_off = 0;      // a 16-byte chunk that straddles the end of the tensor is dropped
-        int tail_lds = -1;          // whole by the range check: its valid bytes are copied by hand
+    // Strip geometry (uniform).
+    struct Strip {
+        int n, o0, orows, crows, npix, in_rows;
+        unsigned start;       // first input byte
+    };
+    auto strip_of = [&](int sidx) {
+        Strip s;
+        s.n = sidx / a.strips;
+        const int strip = sidx - s.n * a.strips;
+        s.o0 = strip * a.rows_per_strip;                                     // first final-output row
+        s.orows = min(a.rows_per_strip, a.Po - s.o0);
+        const int c0 = a.pool ? 2 * s.o0 : s.o0;                             // first convolution row
+        s.crows = a.pool ? 2 * s.orows + 1 : s.orows;
+        s.npix = s.crows * a.Q;
+        s.in_rows = (s.crows - 1) * a.stride + a.R;
+        s.start = (unsigned)((((long long)s.n * a.H + (long long)c0 * a.stride) * a.W) * a.C);
+        return s;
+    };
+
+    // Raw input rows of a strip -> `stage` (16 bytes per lane, from the 16-byte boundary below the
+    // first byte).  A 16-byte chunk that straddles the end of the tensor is dropped whole by the
+    // range check: the lane that issued it copies the valid bytes by hand once the loads have landed.
+    unsigned tail_off = 0;
+    int tail_lds = -1;
+    auto request_strip = [&](const Strip &s) {
+        tail_lds = -1;
+        const unsigned sh16 = s.start & 15u, base = s.start - sh16;
+        const int rchunks = (int)((sh16 + (unsigned)(s.in_rows * a.W * a.C) + 15u) / 16u);
         for (int c = wave * 64; c < rchunks; c += kThreads) {
             const unsigned o = base + (unsigned)(c + lane) * 16;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, MPQ_LDS(stage + c * 16), 16, o, 0, 0, 0);
@@ -128,174 +147,217 @@ __global__ void __launch_bounds__(kThreads, 2) conv_first_kernel(FirstArgs a) {
                 tail_lds = (c + lane) * 16;
             }
         }
-        __builtin_amdgcn_s_waitcnt(0);
-        if (tail_lds >= 0) {
-            const unsigned char *src = (const unsigned char *)a.x;
-            for (unsigned b = 0; tail_off + b < a.x_bytes; ++b) stage[tail_lds + b] = src[tail_off + b];
-        }
-    }
-    __syncthreads();
-
-    // ---- 2. expand C bytes per pixel to 4 (rows are contiguous in memory: pixel i of the strip's
-    // input sits at raw byte sh16 + i * C) ------------------------------------------------------
-    {
-        const int total = in_rows * a.W;
+    };
+    // `stage` -> patch: C bytes per pixel become 4 (rows are contiguous in memory: pixel i of the
+    // strip's input sits at raw byte sh16 + i * C); the tail of every patch row is zeroed.
+    auto expand_strip = [&](const Strip &s) {
+        const unsigned sh16 = s.start & 15u;
+        const int total = s.in_rows * a.W;
         const unsigned mask = a.C >= 4 ? 0xffffffffu : ((1u << (8 * a.C)) - 1u);
         for (int i = tid; i < total; i += kThreads) {
             const int row = (int)(((unsigned long long)(unsigned)i * a.w_magic) >> 32);
             const int col = i - row * a.W;
-            const unsigned off = (unsigned)(sh16 + i * a.C);
+            const unsigned off = sh16 + (unsigned)(i * a.C);
             const unsigned lo = *reinterpret_cast<const unsigned *>(stage + (off & ~3u));
             const unsigned hi = *reinterpret_cast<const unsigned *>(stage + (off & ~3u) + 4);
             const unsigned v = __builtin_amdgcn_alignbyte(hi, lo, off & 3u) & mask;
             *reinterpret_cast<unsigned *>(patch + row * a.pitch + col * 4) = v;
         }
-        const int padw = a.pitch / 4 - a.W;        // zero the tail of every patch row
-        for (int i = tid; i < in_rows * padw; i += kThreads)
+        const int padw = a.pitch / 4 - a.W;
+        for (int i = tid; i < s.in_rows * padw; i += kThreads)
             *reinterpret_cast<unsigned *>(patch + (i / padw) * a.pitch + (a.W + i % padw) * 4) = 0u;
-    }
-    __syncthreads();
+    };
 
-    // ---- 3. reduction: A from the resident weights, B from the patch ------------------------------
-    const int frow = lane & 31, fk = lane >> 5;
-    // accumulators start at the epilogue's per-channel constant: bias - z_x * sum(w)
-    // (register v of lane l in a 32x32 tile: channel 8*(v/4) + 4*(l/32) + v%4, pixel l%32)
-    const Epi epi = a.epi;
-    const int *wsum = reinterpret_cast<const int *>((const char *)a.w + a.wsum_off);
-    v16i acc[kRowTiles][kColTiles];
-#pragma unroll
-    for (int i = 0; i < kRowTiles; ++i) {
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-            const int ch = i * 32 + vq * 8 + fk * 4;
-            v4i b4 = {0, 0, 0, 0};
-            if (ch < a.K) {
-                if (a.bias) b4 = *reinterpret_cast<const v4i *>((const int *)a.bias + ch);
-                if (epi.zx != 0) b4 -= *reinterpret_cast<const v4i *>(wsum + ch) * epi.zx;
+    // ---- once per workgroup: weights and accumulator start values ----------------------------------
+    {
+        const __amdgpu_buffer_rsrc_t wrs =
+            __builtin_amdgcn_make_buffer_rsrc((void *)a.w, (short)0, a.K * a.Kp, 0x00020000);
+        const int wchunks = kMaxK * a.Kp / 16;
+        for (int c = wave * 64; c < wchunks; c += kThreads)      // rows >= K read past the buffer: zeros
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MPQ_LDS(wl + c * 16), 16, (c + lane) * 16, 0, 0, 0);
+        // bias - z_x * sum(w): the epilogue's per-channel constant of the expanded form
+        if (tid < kMaxK) {
+            int v = 0;
+            if (tid < a.K) {
+                if (a.bias) v = reinterpret_cast<const int *>(a.bias)[tid];
+                if (epi.zx != 0) v -= reinterpret_cast<const int *>((const char *)a.w + a.wsum_off)[tid] * epi.zx;
             }
-#pragma unroll
-            for (int j = 0; j < kColTiles; ++j)
-#pragma unroll
-                for (int u = 0; u < 4; ++u) acc[i][j][vq * 4 + u] = b4[u];
+            cst[tid] = v;
         }
     }
+    int sidx = blockIdx.x;
+    if (sidx >= total_strips) {
+        __builtin_amdgcn_s_waitcnt(0);
+        return;
+    }
+    Strip cur = strip_of(sidx);
+    request_strip(cur);
 
     const unsigned wl_addr = (unsigned)(size_t)MPQ_LDS(wl) + (unsigned)(frow * a.Kp);
-    const unsigned patch_addr = (unsigned)(size_t)MPQ_LDS(patch);
-    unsigned bbase[kColTiles];
-    bool tile_live[kColTiles];
-#pragma unroll
-    for (int j = 0; j < kColTiles; ++j) {
-        const int tile = wave * kColTiles + j;
-        tile_live[j] = tile * 32 < npix;
-        int pix = tile * 32 + frow;
-        pix = pix < npix ? pix : 0;
-        const int py = pix / a.Q, px = pix - py * a.Q;
-        bbase[j] = patch_addr + (unsigned)(py * a.stride * a.pitch + px * a.stride * 4);
-    }
-    if (tile_live[0]) {      // uniform per wavefront: tiles are assigned in order
-        // this lane's chunk index advances by 2 per step: (kr, kj) = (kc / cpt, kc % cpt); the
-        // fragments of step ks + 1 are requested before step ks is multiplied
-        int kc = fk, kr = kc / a.cpt, kj = kc % a.cpt;
-        const int ksteps = (a.nchunks + 1) / 2;
-        v4i af[2][kRowTiles], bf[2][kColTiles];
-        auto fetch = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles]) {
-            const bool kval = kc < a.nchunks;       // odd chunk count: the last half step reads chunk 0
-            const unsigned aoff = kval ? (unsigned)(kc * 16) : 0u;
-            const unsigned boff = kval ? (unsigned)(kr * a.pitch + kj * 16) : 0u;
-#pragma unroll
-            for (int i = 0; i < kRowTiles; ++i) fa[i] = lds_read16(wl_addr + (unsigned)(i * 32 * a.Kp) + aoff);
-#pragma unroll
-            for (int j = 0; j < kColTiles; ++j) fb[j] = lds_read16(bbase[j] + boff);
-            kc += 2;
-            kj += 2;
-            if (kj >= a.cpt) {
-                kj -= a.cpt;
-                ++kr;
-            }
-        };
-        auto multiply = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles], bool kval) {
-#pragma unroll
-            for (int i = 0; i < kRowTiles; ++i) lds_arrived(fa[i]);
-#pragma unroll
-            for (int j = 0; j < kColTiles; ++j) {
-                lds_arrived(fb[j]);
-                if (!kval) fb[j] = v4i{0, 0, 0, 0};      // ... and contributes nothing
-            }
+    const FastRequant fr = make_fast_requant(epi);
+    const bool fast = fast_requant_ok(epi);
+    const int kd = a.K / 4;                           // dwords per output pixel
+    int8_t *y = (int8_t *)a.y;
+
+    for (;;) {
+        __builtin_amdgcn_s_waitcnt(0);                // this strip's raw rows (and the weights) have landed
+        if (tail_lds >= 0) {
+            const unsigned char *src = (const unsigned char *)a.x;
+            for (unsigned b = 0; tail_off + b < a.x_bytes; ++b) stage[tail_lds + b] = src[tail_off + b];
+        }
+        __syncthreads();                              // ... for everyone; the previous image is consumed
+        expand_strip(cur);
+        lds_barrier();                                // patch complete, `stage` free
+        const int next = sidx + gridDim.x;
+        Strip nxt = cur;
+        if (next < total_strips) {                    // the next strip's rows arrive behind the arithmetic
+            nxt = strip_of(next);
+            request_strip(nxt);
+        } else {
+            tail_lds = -1;
+        }
+
+        // ---- reduction: A from the resident weights, B from the patch ---------------------------
+        // (register v of lane l in a 32x32 tile: channel 8*(v/4) + 4*(l/32) + v%4, pixel l%32)
+        const int npix = cur.npix;
+        v16i acc[kRowTiles][kColTiles];
+        {
+            // (asm reads: a compiler-visible LDS load would first wait for the loads in flight)
+            v4i b4[kRowTiles][4];
 #pragma unroll
             for (int i = 0; i < kRowTiles; ++i)
 #pragma unroll
-                for (int j = 0; j < kColTiles; ++j)
-                    if (j == 0 || tile_live[j])
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        };
-        fetch(af[0], bf[0]);
-        for (int ks = 0; ks < ksteps; ks += 2) {
+                for (int vq = 0; vq < 4; ++vq)
+                    b4[i][vq] = lds_read16((unsigned)(size_t)MPQ_LDS(cst + i * 32 + vq * 8 + fk * 4));
             lds_wait();
-            if (ks + 1 < ksteps) fetch(af[1], bf[1]);
-            multiply(af[0], bf[0], 2 * ks + fk < a.nchunks);
-            if (ks + 1 < ksteps) {
-                lds_wait();
-                if (ks + 2 < ksteps) fetch(af[0], bf[0]);
-                multiply(af[1], bf[1], 2 * (ks + 1) + fk < a.nchunks);
-            }
+#pragma unroll
+            for (int i = 0; i < kRowTiles; ++i)
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    lds_arrived(b4[i][vq]);
+#pragma unroll
+                    for (int j = 0; j < kColTiles; ++j)
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) acc[i][j][vq * 4 + u] = b4[i][vq][u];
+                }
         }
-    }
-
-    // ---- 4. requantize into the LDS output image [pixel][kOutPitch] ------------------------------
-    auto requantize = [&](auto fast_tag) {
-        constexpr bool FAST = decltype(fast_tag)::value;
-        const FastRequant fr = make_fast_requant(epi);
+        const unsigned patch_addr = (unsigned)(size_t)MPQ_LDS(patch);
+        unsigned bbase[kColTiles];
+        bool tile_live[kColTiles];
 #pragma unroll
-        for (int i = 0; i < kRowTiles; ++i) {
+        for (int j = 0; j < kColTiles; ++j) {
+            const int tile = wave * kColTiles + j;
+            tile_live[j] = tile * 32 < npix;
+            int pix = tile * 32 + frow;
+            pix = pix < npix ? pix : 0;
+            const int py = (int)(((unsigned long long)(unsigned)pix * a.q_magic) >> 32), px = pix - py * a.Q;
+            bbase[j] = patch_addr + (unsigned)(py * a.stride * a.pitch + px * a.stride * 4);
+        }
+        if (tile_live[0]) {      // uniform per wavefront: tiles are assigned in order
+            // this lane's chunk index advances by 2 per step: (kr, kj) = (kc / cpt, kc % cpt); the
+            // fragments of step ks + 1 are requested before step ks is multiplied
+            int kc = fk, kr = kc / a.cpt, kj = kc % a.cpt;
+            const int ksteps = (a.nchunks + 1) / 2;
+            v4i af[2][kRowTiles], bf[2][kColTiles];
+            auto fetch = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles]) {
+                const bool kval = kc < a.nchunks;       // odd chunk count: the last half step reads chunk 0
+                const unsigned aoff = kval ? (unsigned)(kc * 16) : 0u;
+                const unsigned boff = kval ? (unsigned)(kr * a.pitch + kj * 16) : 0u;
 #pragma unroll
-            for (int vq = 0; vq < 4; ++vq) {
-                const int ch = i * 32 + vq * 8 + fk * 4;
-                if (ch >= a.K) continue;
+                for (int i = 0; i < kRowTiles; ++i) fa[i] = lds_read16(wl_addr + (unsigned)(i * 32 * a.Kp) + aoff);
+#pragma unroll
+                for (int j = 0; j < kColTiles; ++j) fb[j] = lds_read16(bbase[j] + boff);
+                kc += 2;
+                kj += 2;
+                if (kj >= a.cpt) {
+                    kj -= a.cpt;
+                    ++kr;
+                }
+            };
+            auto multiply = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles], bool kval) {
+#pragma unroll
+                for (int i = 0; i < kRowTiles; ++i) lds_arrived(fa[i]);
 #pragma unroll
                 for (int j = 0; j < kColTiles; ++j) {
-                    const int pix = (wave * kColTiles + j) * 32 + frow;
-                    if (pix >= npix) continue;
-                    int t[4];
+                    lds_arrived(fb[j]);
+                    if (!kval) fb[j] = v4i{0, 0, 0, 0};      // ... and contributes nothing
+                }
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u];
-                    unsigned packed = 0;
-                    if constexpr (FAST) {
-                        packed = requant4_fast(t[0], t[1], t[2], t[3], fr);
-                    } else {
+                for (int i = 0; i < kRowTiles; ++i)
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) packed |= ((unsigned)requant32(t[u], epi) & 0xffu) << (8 * u);
-                    }
-                    *reinterpret_cast<unsigned *>(stage + pix * kOutPitch + ch) = packed;
+                    for (int j = 0; j < kColTiles; ++j)       // (a dead second tile recomputes pixel 0)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            };
+            fetch(af[0], bf[0]);
+            for (int ks = 0; ks < ksteps; ks += 2) {
+                lds_wait();
+                if (ks + 1 < ksteps) fetch(af[1], bf[1]);
+                multiply(af[0], bf[0], 2 * ks + fk < a.nchunks);
+                if (ks + 1 < ksteps) {
+                    lds_wait();
+                    if (ks + 2 < ksteps) fetch(af[0], bf[0]);
+                    multiply(af[1], bf[1], 2 * (ks + 1) + fk < a.nchunks);
                 }
             }
         }
-    };
-    if (fast_requant_ok(epi)) requantize(std::true_type{});
-    else requantize(std::false_type{});
-    __syncthreads();
+        lds_barrier();                                // everyone is done reading the patch
 
-    // ---- 5. (pool and) store, channel-contiguous -----------------------------------------------
-    const int kd = a.K / 4;                           // dwords per pixel
-    const int total = orows * a.Qo * kd;
-    int8_t *y = (int8_t *)a.y;
-    for (int idx = tid; idx < total; idx += kThreads) {
-        const int cd = idx % kd;
-        const int op = idx / kd;
-        const int oq = op % a.Qo, orow = op / a.Qo;
-        unsigned v;
-        if (a.pool) {
-            const unsigned char *src = stage + ((2 * orow) * a.Q + 2 * oq) * kOutPitch + cd * 4;
-            v = *reinterpret_cast<const unsigned *>(src);
+        // ---- requantize into the LDS output image [pixel][kOutPitch] --------------------------
+        // (channels K..95 of a pixel hold zero-weight results and land in the image's row padding)
+        auto requantize = [&](auto fast_tag) {
+            constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
-            for (int r = 0; r < 3; ++r)
+            for (int j = 0; j < kColTiles; ++j) {
+                const int pix = (wave * kColTiles + j) * 32 + frow;
+                if (pix >= npix) continue;
+                unsigned char *dst = image + pix * kOutPitch + fk * 4;
 #pragma unroll
-                for (int s = 0; s < 3; ++s)
-                    if (r + s > 0) v = max_i8x4(v, *reinterpret_cast<const unsigned *>(src + (r * a.Q + s) * kOutPitch));
-        } else {
-            v = *reinterpret_cast<const unsigned *>(stage + (orow * a.Q + oq) * kOutPitch + cd * 4);
+                for (int i = 0; i < kRowTiles; ++i) {
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        int t[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u];
+                        unsigned packed = 0;
+                        if constexpr (FAST) {
+                            packed = requant4_fast(t[0], t[1], t[2], t[3], fr);
+                        } else {
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) packed |= ((unsigned)requant32(t[u], epi) & 0xffu) << (8 * u);
+                        }
+                        *reinterpret_cast<unsigned *>(dst + i * 32 + vq * 8) = packed;
+                    }
+                }
+            }
+        };
+        if (fast) requantize(std::true_type{});
+        else requantize(std::false_type{});
+        lds_barrier();
+
+        // ---- (pool and) store, channel-contiguous ---------------------------------------------
+        const int total = cur.orows * a.Qo * kd;
+        for (int idx = tid; idx < total; idx += kThreads) {
+            const int op = (int)(((unsigned long long)(unsigned)idx * a.kd_magic) >> 32);
+            const int cd = idx - op * kd;
+            const int orow = (int)(((unsigned long long)(unsigned)op * a.qo_magic) >> 32), oq = op - orow * a.Qo;
+            unsigned v;
+            if (a.pool) {
+                const unsigned char *src = image + ((2 * orow) * a.Q + 2 * oq) * kOutPitch + cd * 4;
+                MaxI8x4 m;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int s = 0; s < 3; ++s) m.add(*reinterpret_cast<const unsigned *>(src + (r * a.Q + s) * kOutPitch));
+                v = m.get();
+            } else {
+                v = *reinterpret_cast<const unsigned *>(image + (orow * a.Q + oq) * kOutPitch + cd * 4);
+            }
+            *reinterpret_cast<unsigned *>(y + (((size_t)cur.n * a.Po + cur.o0 + orow) * a.Qo + oq) * a.K + cd * 4) = v;
         }
-        *reinterpret_cast<unsigned *>(y + (((size_t)n * a.Po + o0 + orow) * a.Qo + oq) * a.K + cd * 4) = v;
+
+        if (next >= total_strips) break;
+        sidx = next;
+        cur = nxt;
     }
 }
 
@@ -326,6 +388,10 @@ hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_
     if (a.x_bytes >= 0x7ffffff0ull || c.W > 4096) return hipErrorNotSupported;
     a.wsum_off = pl.wsum_off;
     a.epi = c.epi;
+    if (c.Q < 2 || Qo < 2 || c.K < 8) return hipErrorNotSupported;
+    a.q_magic = (unsigned)(((1ull << 32) + c.Q - 1) / c.Q);
+    a.qo_magic = (unsigned)(((1ull << 32) + Qo - 1) / Qo);
+    a.kd_magic = (unsigned)(((1ull << 32) + c.K / 4 - 1) / (c.K / 4));
     a.w_magic = (unsigned)(((1ull << 32) + c.W - 1) / c.W);
     // the patch row must hold the last output pixel's run: (Q - 1) * stride + tap pixels
     int need_px = (c.Q - 1) * a.stride + pl.tap_elems / 4;
@@ -342,15 +408,16 @@ hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_
         a.max_in_rows = (crows - 1) * a.stride + c.R;
         a.lds_w = (int)round_up((size_t)kMaxK * a.Kp + 16, 1024);
         a.lds_patch = (int)round_up((size_t)a.max_in_rows * a.pitch + 64, 1024);
-        const size_t raw = (size_t)a.max_in_rows * c.W * c.C + 64;
+        // the output image of a strip overwrites the strip's consumed patch and may run on past it
         const size_t img = (size_t)crows * c.Q * kOutPitch + 16;
+        a.lds_extra = img > (size_t)a.lds_patch ? (int)round_up(img - a.lds_patch, 1024) : 0;
         // + 1 KiB: the last wavefront-wide raw copy may run up to 63 chunks past the data
-        a.lds_stage = (int)round_up((raw > img ? raw : img) + 1024, 1024);
-        if (a.lds_w + a.lds_patch + a.lds_stage <= 160 * 1024) break;
+        a.lds_stage = (int)round_up((size_t)a.max_in_rows * c.W * c.C + 64 + 1024, 1024);
+        if (a.lds_w + 1024 + a.lds_patch + a.lds_extra + a.lds_stage <= 160 * 1024) break;
     }
     a.rows_per_strip = rps;
     a.strips = (Po + rps - 1) / rps;
-    const size_t lds_bytes = (size_t)a.lds_w + a.lds_patch + a.lds_stage;
+    const size_t lds_bytes = (size_t)a.lds_w + 1024 + (size_t)a.lds_patch + a.lds_extra + a.lds_stage;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)conv_first_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -358,9 +425,20 @@ hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const long long blocks = (long long)c.N * a.strips;
-    if (blocks <= 0) return hipSuccess;
-    conv_first_kernel<<<(unsigned)blocks, kThreads, lds_bytes, st>>>(a);
+    const long long total = (long long)c.N * a.strips;
+    if (total <= 0) return hipSuccess;
+    if (total > 0x7fffffffll) return hipErrorNotSupported;
+    // one persistent workgroup per compute unit, each walking strips blockIdx.x, + gridDim.x, ...
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        if (cus < 1) cus = 1;
+    }
+    const unsigned blocks = (unsigned)(total < cus ? total : cus);
+    conv_first_kernel<<<blocks, kThreads, lds_bytes, st>>>(a);
     return hipGetLastError();
 }
 
