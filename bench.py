@@ -31,11 +31,19 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the FC / MoE side measurements")
     ap.add_argument("--cpu-images", type=int, default=256, help="images the oracle is timed on")
+    ap.add_argument("--profile-layer", default=None,
+                    help="for counter collection: run only this layer's kernel (conv1..conv5; conv2 and conv5 "
+                         "without their pool), or 'copy' (a 256 MiB device copy), --steps times, print nothing else")
     return ap.parse_args()
 
 
 PEAK = {"int8": 5000.0, "fp16": 2500.0, "int16": 1250.0}   # dense MFMA, TOP/s (int16: int8 peak / 4)
 HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch (fetch + write) of the convolution kernels, from rocprofv3 --pmc runs of
+# `bench.py --profile-layer NAME` (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter
+# reads for `--profile-layer copy`); the summaries are under profiles/.  None: not measured.
+MEASURED_TRAFFIC = {}
 
 
 def main():
@@ -73,6 +81,23 @@ def main():
         else:
             mb.mpq_quantize(x_dev, x_store, n_in, dt, chain.s_in, 0)
         return chain.forward(x_store)
+
+    if args.profile_layer:
+        step()
+        torch.cuda.synchronize()
+        if args.profile_layer == "copy":
+            src = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+            dst = torch.empty_like(src)
+            call = lambda: dst.copy_(src)
+        else:
+            i = [L.name for L in cf.ALEXNET_CONVS].index(args.profile_layer)
+            ins = [x_store] + chain.acts[:-1]
+            call = (lambda: chain.run_layer(0, ins[0])) if i == 0 else conv_only_call(mb, chain, ins, i, dt)
+        for _ in range(args.steps):
+            call()
+        torch.cuda.synchronize()
+        print(json.dumps({"profile_layer": args.profile_layer, "launches": args.steps}))
+        return
 
     H, W = cf.ALEXNET_INPUT[1:]
     macs_layer, hw = [], (H, W)
@@ -131,29 +156,28 @@ def main():
         layer_us[L.name] = time_call(lambda i=i: chain.run_layer(i, ins[i]))
 
     # ---- dominant kernel: the convolution kernel of the slowest layer, timed alone -----------
-    # (same kernel, same launch shape; a layer with a fused pool is re-issued without its pool so
-    # that the events bracket exactly one kernel)
+    # (same kernel, same launch shape.  conv1's kernel has its 3x3/2 pool fused and is timed as it
+    # runs in the step; the other pooled layers are re-issued without their pool so that the
+    # events bracket exactly one kernel per launch)
     conv_only_us = {}
+    names = [L.name for L in cf.ALEXNET_CONVS]
     for i, L in enumerate(cf.ALEXNET_CONVS):
-        if L.name == "conv1":
-            continue      # conv1's call also runs the channel-padding copy; it is never dominant
-        lay = chain.layers[i]
-        n, h, w_, c = ins[i].shape
-        d = mb.conv_desc(L.C, L.K, L.R, L.S, L.stride, L.pad, L.groups, L.relu, 0, 0)
-        P, Q = L.out_hw(h, w_)
-        tmp = torch.empty((n, P, Q, L.K), dtype=mb.TORCH_DTYPE[dt], device="cuda")
-        s_x = chain.s_in if i == 0 else chain.layers[i - 1].y_scale
-        xv = mb.tensor(ins[i], dt, n, h, w_, c, s_x)
-        yv = mb.tensor(tmp, dt, n, P, Q, L.K, lay.y_scale)
-        conv_only_us[L.name] = time_call(lambda: mb.mpq_conv2d(xv, lay.packed, lay.w_scale, 0, lay.bias, yv, d, None, 0))
+        if i == 0:
+            conv_only_us[L.name] = layer_us[L.name]
+            continue
+        conv_only_us[L.name] = time_call(conv_only_call(mb, chain, ins, i, dt))
+    ops_of = {n: 2.0 * macs_layer[names.index(n)] * B for n in names}
+    kernels = {n: {"us": round(conv_only_us[n], 2), "achieved": round(ops_of[n] / (conv_only_us[n] * 1e-6) / 1e12, 1),
+                   "frac": round(ops_of[n] / (conv_only_us[n] * 1e-6) / 1e12 / PEAK[args.dtype], 4),
+                   "hbm_bytes_measured": MEASURED_TRAFFIC.get((n, args.dtype, B))} for n in names}
     dom = max(conv_only_us, key=conv_only_us.get)
-    dom_i = [L.name for L in cf.ALEXNET_CONVS].index(dom)
-    dom_ops = 2.0 * macs_layer[dom_i] * B
-    dom_achieved = dom_ops / (conv_only_us[dom] * 1e-6) / 1e12
-    roofline = {"bound": "mfma", "kernel": f"conv_mfma_kernel ({dom}, batch {B}, {args.dtype})",
+    dom_achieved = ops_of[dom] / (conv_only_us[dom] * 1e-6) / 1e12
+    roofline = {"bound": "mfma",
+                "kernel": f"{'conv_first_kernel (3x3/2 pool fused)' if dom == 'conv1' else 'conv_patch_kernel'} "
+                          f"({dom}, batch {B}, {args.dtype})",
                 "achieved": round(dom_achieved, 2), "peak": PEAK[args.dtype], "unit": "TFLOP/s" if dt == mb.FP16 else "TOP/s",
-                "frac": round(dom_achieved / PEAK[args.dtype], 4), "traffic": None,
-                "kernel_us": round(conv_only_us[dom], 2)}
+                "frac": round(dom_achieved / PEAK[args.dtype], 4), "traffic": MEASURED_TRAFFIC.get((dom, args.dtype, B)),
+                "kernel_us": round(conv_only_us[dom], 2), "algorithmic_ops": ops_of[dom]}
 
     out = {
         "metric": f"{args.dtype} conv TOPS + images/s (AlexNet-shape conv stack, batch {B})",
@@ -167,19 +191,35 @@ def main():
                    "batch": B, "input": "3x227x227 N(0,1), seeded", "gop_per_image": round(2 * macs_img / 1e9, 4)},
         "frac_of_mfma_peak": round(tops / PEAK[args.dtype], 4),
         "layer_us": {k: round(v, 1) for k, v in layer_us.items()},
-        "conv_kernel_us": {k: round(v, 1) for k, v in conv_only_us.items()},
-        "conv_kernel_tops": {k: round(2.0 * macs_layer[[L.name for L in cf.ALEXNET_CONVS].index(k)] * B / (v * 1e-6) / 1e12, 1)
-                             for k, v in conv_only_us.items()},
+        "conv_kernels": kernels,
         "roofline": roofline,
     }
 
     if not args.no_extras:
         out["fc_batch1"] = bench_fc(torch, mb, pl, cf, calib, args.dtype)
+        if B == 256:
+            out["moe_config5"] = bench_moe(torch, mb, pl, cf, calib, args.dtype, chain.acts[1], B)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cf, calib, args.dtype, args.cpu_images, macs_img)
 
     print(json.dumps(out))
+
+
+def conv_only_call(mb, chain, ins, i, dt):
+    """The convolution of layer i of the chain as one mpq_conv2d call without its max-pool."""
+    import torch
+    from workloads import configs as cf
+    L = cf.ALEXNET_CONVS[i]
+    lay = chain.layers[i]
+    n, h, w_, c = ins[i].shape
+    d = mb.conv_desc(L.C, L.K, L.R, L.S, L.stride, L.pad, L.groups, L.relu, 0, 0)
+    P, Q = L.out_hw(h, w_)
+    tmp = torch.empty((n, P, Q, L.K), dtype=mb.TORCH_DTYPE[dt], device="cuda")
+    s_x = chain.s_in if i == 0 else chain.layers[i - 1].y_scale
+    xv = mb.tensor(ins[i], dt, n, h, w_, c, s_x)
+    yv = mb.tensor(tmp, dt, n, P, Q, L.K, lay.y_scale)
+    return lambda: mb.mpq_conv2d(xv, lay.packed, lay.w_scale, 0, lay.bias, yv, d, None, 0)
 
 
 def graph_time(torch, fn, iters=10, reps=10):
@@ -200,6 +240,47 @@ def graph_time(torch, fn, iters=10, reps=10):
     b.record()
     torch.cuda.synchronize()
     return a.elapsed_time(b) * 1e3 / (iters * reps)
+
+
+def bench_moe(torch, mb, pl, cf, calib, dtype_name, trunk_out, batch):
+    """Config 5 expert stage at the given batch with the prescribed 102/77/51/26 routing: gating FC
+    (raw logits) and mpq_moe_forward (route + gather + grouped experts + scatter), timed per call.
+    `trunk_out` is the device activation after conv2 + pool of the main chain."""
+    import numpy as np
+    if dtype_name == "int16":
+        return None
+    dt = mb.DTYPE_ID[dtype_name]
+    _, gate_w, experts_p = cf.moe_params()
+    cal = calib.load()
+    if dtype_name == "fp16":
+        gate = pl.Chain([cf.MOE_GATE], [(gate_w, None)], dt, batch, (256, 13, 13), raw_last=True)
+        moe = pl.MoE(cf.MOE_EXPERT_LAYERS, experts_p, dt, batch, (13, 13, 256))
+    else:
+        sa, sm = cal["alexnet"][dtype_name], cal["moe"][dtype_name]
+        s_trunk = sa["layers"][1]["y"]
+        gsc = [{"w": sm["gate_w"], "b": 1.0, "y": 1.0}]
+        gate = pl.Chain([cf.MOE_GATE], [(gate_w, None)], dt, batch, (256, 13, 13), s_trunk, gsc, raw_last=True)
+        moe = pl.MoE(cf.MOE_EXPERT_LAYERS, experts_p, dt, batch, (13, 13, 256), s_trunk, sm["experts"])
+    lg = torch.from_numpy(cf.moe_benchmark_logits(batch).astype(np.float32)).to("cuda")
+    gate_us = graph_time(torch, lambda: gate.forward(trunk_out), 5, 5)
+    moe_us = graph_time(torch, lambda: moe.forward(trunk_out, lg, mb.FP32), 5, 5)
+    counts = [int(v) for v in moe.expert_counts.cpu().numpy()]
+    # expert MACs per sample: the expert layers on a 13x13x256 input
+    hw, macs = (13, 13), 0
+    for L in cf.MOE_EXPERT_LAYERS:
+        if L.kind == "fc":
+            macs += L.N * L.K
+        else:
+            macs += L.macs(*hw)
+            P, Q = L.out_hw(*hw)
+            if L.pool_k:
+                P, Q = (P - L.pool_k) // L.pool_s + 1, (Q - L.pool_k) // L.pool_s + 1
+            hw = (P, Q)
+    return {"workload": f"config 5 expert stage, batch {batch}, top-1, counts {counts}",
+            "gate_us": round(gate_us, 1), "moe_forward_us": round(moe_us, 1),
+            "samples_per_s": round(batch / (moe_us * 1e-6), 1),
+            "expert_gmac_per_sample": round(macs / 1e9, 4),
+            "expert_tops": round(2.0 * macs * batch / (moe_us * 1e-6) / 1e12, 1)}
 
 
 def bench_fc(torch, mb, pl, cf, calib, dtype_name):
