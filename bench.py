@@ -43,7 +43,11 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (fetch + write) of the convolution kernels, from rocprofv3 --pmc runs of
 # `bench.py --profile-layer NAME` (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter
 # reads for `--profile-layer copy`); the summaries are under profiles/.  None: not measured.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    ("conv1", "int8", 256): (2 * 25745.0 + 17496.0) * 1024, ("conv2", "int8", 256): (2 * 18356.2 + 46656.0) * 1024,
+    ("conv3", "int8", 256): (2 * 9086.4 + 16224.0) * 1024, ("conv4", "int8", 256): (2 * 12417.9 + 16257.7) * 1024,
+    ("conv5", "int8", 256): (2 * 11945.6 + 10816.0) * 1024,
+}
 
 
 def main():

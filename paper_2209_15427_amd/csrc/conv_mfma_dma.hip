@@ -220,7 +220,14 @@ hipError_t launch_one(ConvArgs a, hipStream_t st) {
 template <typename T>
 hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
     const int Kg = a.plan.Kg;
-    if (Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0)) return launch_one<T, 128, 256, 2, 2, 3, 2>(a, st);
+    bool wide = Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0);
+    if (wide) {
+        // few pixel tiles (a fully-connected layer, an expert's share of the batch): the narrow
+        // tile doubles the number of workgroups that stream the weights
+        long long ptiles = ((long long)a.N * a.P * a.Q + 255) / 256 + (a.seg.offsets ? a.seg.num_experts : 0);
+        if (ptiles * ((Kg + 127) / 128) * a.groups < 192) wide = false;
+    }
+    if (wide) return launch_one<T, 128, 256, 2, 2, 3, 2>(a, st);
     return launch_one<T, 64, 256, 1, 4, 3, 2>(a, st);
 }
 
