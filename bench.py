@@ -223,7 +223,8 @@ def conv_only_call(mb, chain, ins, i, dt):
     s_x = chain.s_in if i == 0 else chain.layers[i - 1].y_scale
     xv = mb.tensor(ins[i], dt, n, h, w_, c, s_x)
     yv = mb.tensor(tmp, dt, n, P, Q, L.K, lay.y_scale)
-    return lambda: mb.mpq_conv2d(xv, lay.packed, lay.w_scale, 0, lay.bias, yv, d, None, 0)
+    # the views hold raw pointers: the closure keeps the output buffer (and the input) alive
+    return lambda _keep=(tmp, ins[i]): mb.mpq_conv2d(xv, lay.packed, lay.w_scale, 0, lay.bias, yv, d, None, 0)
 
 
 def graph_time(torch, fn, iters=10, reps=10):
