@@ -253,8 +253,15 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
             a.tap_px = 1;
         }
         a.x_bytes = (unsigned long long)a.N * a.H * a.W * a.C * pl.esize;
-        if (conv_patch_prepare(a)) err = launch_conv_patch(a, st);
-        else err = conv_mfma_dma_eligible(a) ? launch_conv_mfma_dma(a, st) : launch_conv_mfma(a, st);
+        bool pool_fused = false;
+        if (conv_patch_prepare(a, d.pool_k == 3 && d.pool_s == 2, g.Po, g.Qo, y_data, &pool_fused)) {
+            err = launch_conv_patch(a, st);
+            if (err == hipSuccess && pool_fused) return MPQ_OK;
+        } else {
+            a.tile_px = 0;
+            a.pool = 0;
+            err = conv_mfma_dma_eligible(a) ? launch_conv_mfma_dma(a, st) : launch_conv_mfma(a, st);
+        }
     } else {
         err = launch_conv_generic(a, st);
     }

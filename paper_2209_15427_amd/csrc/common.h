@@ -95,6 +95,9 @@ struct ConvArgs {
     int ksteps;            // 64-byte steps along the packed reduction axis
     int tap_px;            // input pixels one tap spans (1, or the padded row length in row mode)
     int ptiles;            // pixel tiles in the grid (filled by the launcher)
+    int tile_px;           // 0: a pixel tile is BP consecutive output pixels; else image-aligned tiles of P Q pixels
+    int pool;              // image-aligned tiles only: store the 3x3 / stride-2 max-pool of the output (Po x Qo)
+    int Po, Qo;
     unsigned magic_ct, magic_pt;   // magic_u32 of the channel / pixel tile counts (filled by the launcher)
     int y_vec16;           // output rows and channel-tile origins are 16-byte aligned
     int phased;            // walk the reduction axis channel block by channel block (see conv_mfma_dma.hip)
@@ -128,7 +131,7 @@ hipError_t launch_conv_generic(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
 bool conv_mfma_dma_eligible(const ConvArgs &a);
 hipError_t launch_conv_mfma_dma(const ConvArgs &a, hipStream_t st);
-bool conv_patch_prepare(ConvArgs &a);
+bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, bool *fused);
 hipError_t launch_conv_patch(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_first(const ConvArgs &a, int pool_k, int pool_s, void *y_final, int Po, int Qo,
                              hipStream_t st);

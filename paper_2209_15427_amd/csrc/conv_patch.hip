@@ -28,6 +28,7 @@ namespace {
 using namespace tile;
 
 constexpr int kMaxPatchSlots = 8;
+constexpr int kImageBP = 192;      // pixel-tile size of the image-aligned variant (one image of <= 192 output pixels per tile)
 
 template <typename T, int BC, int BP, int WGC, int WGP, int NSTW, int NSLOT, int WPE, bool UNI>
 __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
@@ -293,7 +294,13 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     wait_vmcnt<0>();
     bare_barrier();
 
-    TL::finish(acc, lds, a, t);
+    if constexpr (BP == kImageBP) {
+        if (a.pool) {
+            TL::template finish<true>(acc, lds, a, t);
+            return;
+        }
+    }
+    TL::template finish<false>(acc, lds, a, t);
 }
 
 template <typename T, int BC, int BP, int WGC, int WGP, int NSTW, int NSLOT, int WPE, bool UNI>
@@ -303,6 +310,7 @@ hipError_t launch_one(ConvArgs a, hipStream_t st) {
     long long rows = (long long)a.N * PQ;
     int ptiles = (int)((rows + BP - 1) / BP);
     if (a.seg.offsets) ptiles += a.seg.num_experts;
+    if (a.tile_px) ptiles = a.N;                       // image-aligned: one pixel tile per image
     long long blocks = (long long)ptiles * ctiles * a.groups;
     if (blocks <= 0) return hipSuccess;
     if (!set_tile_counts(a, ptiles, ctiles)) return hipErrorInvalidValue;
@@ -319,7 +327,14 @@ constexpr int kBP = 256;
 
 // Fills the patch-kernel fields of `a` and says whether the layer fits: stride 1, tap-mode plan,
 // zero padding value (see the header), every tile's virtual run within one patch buffer.
-bool conv_patch_prepare(ConvArgs &a) {
+// A layer whose image has 129..192 output pixels gets image-aligned tiles (one image per pixel
+// tile: 256 images x 2 groups of conv5 are exactly one wave of 512 workgroups); with those, a
+// 3x3 / stride-2 max-pool (`pool`, output Po x Qo at `y_pool`) is taken in the epilogue: *fused
+// says so, and a.y then is the pooled tensor.
+bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, bool *fused) {
+    *fused = false;
+    a.tile_px = 0;
+    a.pool = 0;
     const Plan &pl = a.plan;
     if (pl.mode != kModeTap || a.stride_h != 1 || a.stride_w != 1) return false;
     if (!conv_mfma_dma_eligible(a)) return false;
@@ -335,14 +350,24 @@ bool conv_patch_prepare(ConvArgs &a) {
     a.ksp = (NT * a.cbc + 3) / 4;
     if (a.ksp < kPatchSlots + 2) return false;   // one patch slot per step must finish two steps early
     const int Hv = a.H + 2 * a.pad_h, Wv = a.W + 2 * a.pad_w, PQ = a.P * a.Q;
-    // largest virtual run any tile of kBP consecutive output pixels can need
+    const int Kg = pl.Kg;
+    const bool wide = Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0);
+    const bool raw_out = a.epi.kind == kEpiRawI32 || a.epi.kind == kEpiRawF32;
+    if (wide && a.cbc == 4 && PQ > 128 && PQ <= kImageBP && !raw_out && !a.seg.offsets) {
+        // worth it when the pool can be fused, or when the images make one wave of workgroups
+        // (2 per CU on 256 CUs) where consecutive 256-pixel tiles would leave slots idle
+        const long long blocks_img = (long long)a.N * ((Kg + 127) / 128) * a.groups;
+        const bool pool_ok = pool && (reinterpret_cast<uintptr_t>(y_pool) % 16) == 0;
+        if (pool_ok || blocks_img <= 512) a.tile_px = PQ;
+    }
+    // largest virtual run any tile (kBP consecutive output pixels, or one image) can need
     long long worst = 0;
     auto virt = [&](long long m) {
         const long long n = m / PQ, rem = m % PQ;
         return (n * Hv + rem / a.Q) * Wv + rem % a.Q;
     };
-    for (int s0 = 0; s0 < PQ; ++s0) {
-        const long long span = virt((long long)s0 + kBP - 1) + (long long)(a.R - 1) * Wv + (a.S - 1) - virt(s0) + 1;
+    for (int s0 = 0; s0 < (a.tile_px ? 1 : PQ); ++s0) {
+        const long long span = virt((long long)s0 + (a.tile_px ? PQ : kBP) - 1) + (long long)(a.R - 1) * Wv + (a.S - 1) - virt(s0) + 1;
         if (span > worst) worst = span;
     }
     if (worst * CB > kPatchBytes) return false;
@@ -356,6 +381,14 @@ bool conv_patch_prepare(ConvArgs &a) {
     if (a.S < 2 || a.Q < 2 || PQ < 2 || !magic_exact((unsigned long long)a.N * PQ + kBP, (unsigned)PQ)) return false;
     a.magic_pq = magic_u32((unsigned)PQ);
     a.magic_q = magic_u32((unsigned)a.Q);
+    if (a.tile_px && pool && (reinterpret_cast<uintptr_t>(y_pool) % 16) == 0 && Po >= 1 && Qo >= 1 &&
+        2 * (Po - 1) + 3 <= a.P && 2 * (Qo - 1) + 3 <= a.Q) {
+        a.pool = 1;
+        a.Po = Po;
+        a.Qo = Qo;
+        a.y = y_pool;
+        *fused = true;
+    }
     return true;
 }
 
@@ -366,6 +399,7 @@ hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
     const int Kg = a.plan.Kg;
     const bool wide = Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0);
     const bool uni = a.cbc == 4;                       // 64-byte channel blocks: one tap per step
+    if (a.tile_px) return launch_one<T, 128, kImageBP, 2, 2, 3, kPatchSlots, 2, true>(a, st);
     if (wide) {
         if (uni) return launch_one<T, 128, kBP, 2, 2, 3, kPatchSlots, 2, true>(a, st);
         return launch_one<T, 128, kBP, 2, 2, 3, kPatchSlots, 2, false>(a, st);

@@ -71,6 +71,45 @@ inline bool set_tile_counts(ConvArgs &a, int ptiles, int ctiles) {
     return magic_exact(blocks, (unsigned)ptiles) && magic_exact(blocks, (unsigned)ctiles);
 }
 
+// Running element-wise max over 16-byte chunks of storage codes.  int8 has no packed max: the even
+// and the odd bytes of every dword are moved to the high byte of a 16-bit lane (where the byte's
+// sign is the lane's sign), the maxima are kept in that split form and merged at the end.
+template <typename T> struct MaxAcc;
+template <> struct MaxAcc<int8_t> {
+    typedef short v2s __attribute__((ext_vector_type(2)));
+    v2s me[4], mo[4];
+    __device__ __forceinline__ MaxAcc() {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) me[u] = mo[u] = v2s{(short)-32768, (short)-32768};
+    }
+    __device__ __forceinline__ void add(v4i v) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const unsigned w = (unsigned)v[u];
+            me[u] = __builtin_elementwise_max(me[u], __builtin_bit_cast(v2s, (w << 8) & 0xff00ff00u));
+            mo[u] = __builtin_elementwise_max(mo[u], __builtin_bit_cast(v2s, w & 0xff00ff00u));
+        }
+    }
+    __device__ __forceinline__ v4i get() const {
+        v4i r;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            r[u] = (int)((__builtin_bit_cast(unsigned, mo[u]) & 0xff00ff00u) | ((__builtin_bit_cast(unsigned, me[u]) >> 8) & 0x00ff00ffu));
+        return r;
+    }
+};
+template <> struct MaxAcc<_Float16> {
+    typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+    v8h m;
+    bool first = true;
+    __device__ __forceinline__ void add(v4i v) {
+        const v8h h = __builtin_bit_cast(v8h, v);
+        m = first ? h : __builtin_elementwise_max(m, h);
+        first = false;
+    }
+    __device__ __forceinline__ v4i get() const { return __builtin_bit_cast(v4i, m); }
+};
+
 // Which tile a workgroup owns.
 struct TileCtx {
     int g;                 // convolution group
@@ -105,6 +144,14 @@ __device__ __forceinline__ bool decode_tile(const ConvArgs &a, TileCtx &t) {
     t.wbase = (const char *)a.w;
     t.bias = (const char *)a.bias;
     t.epi = a.epi;
+    if (a.tile_px) {
+        // image-aligned tiles: pixel tile pt is image pt (tile_px = P Q <= BP pixels; not used with
+        // expert-grouped launches)
+        t.m0 = t.m_begin = pt * a.tile_px;
+        t.m_end = t.m0 + a.tile_px;
+        t.ch0 = ct * BC;
+        return pt < a.N;
+    }
     if (a.seg.offsets) {
         int e = 0, tile_base = 0;
         bool found = false;
@@ -183,6 +230,9 @@ struct Tile {
     // written with 16-byte stores in which consecutive lanes cover consecutive channels of a pixel,
     // so that every store instruction fills whole cache lines.  Raw accumulator outputs (gating
     // logits) are stored directly.  `lds` must hold kImageBytes and be idle (barrier before).
+    // POOL (image-aligned tiles only): instead of the image, its 3x3 / stride-2 max-pool is stored
+    // (the max commutes with the monotone requantization and is taken on the stored codes).
+    template <bool POOL = false>
     static __device__ __forceinline__ void finish(Acc (&acc)[TC][TP], unsigned char *lds, const ConvArgs &a,
                                                   const TileCtx &t) {
         const Plan &pl = a.plan;
@@ -256,6 +306,33 @@ struct Tile {
         __syncthreads();
         constexpr int CHUNK_ELEMS = 16 / ES;
         char *yb = (char *)a.y;
+        if constexpr (POOL) {
+            const int PoQo = a.Po * a.Qo, n = m0 / a.tile_px;
+            for (int idx = tid; idx < PoQo * CH16; idx += kThreads) {
+                const int op = idx / CH16, c16 = idx % CH16;
+                const int ch = ch0 + c16 * CHUNK_ELEMS;
+                if (ch >= pl.Kg) continue;
+                const int orow = op / a.Qo, oq = op - orow * a.Qo;
+                MaxAcc<T> mx;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int sx = 0; sx < 3; ++sx) {
+                        const int row = (2 * orow + r) * a.Q + 2 * oq + sx;
+                        mx.add(*reinterpret_cast<const v4i *>(lds + row * ROWB + ((c16 ^ (row & (CH16 - 1))) << 4)));
+                    }
+                const v4i v = mx.get();
+                char *dst = yb + (((size_t)n * PoQo + op) * a.K + (size_t)(g * pl.Kg + ch)) * ES;
+                if (a.y_vec16 && ch + CHUNK_ELEMS <= pl.Kg) {
+                    *reinterpret_cast<v4i *>(dst) = v;
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (ch + (u * 4 + 3) / ES < pl.Kg) *reinterpret_cast<int *>(dst + u * 4) = v[u];
+                }
+            }
+            return;
+        }
 #pragma unroll 4
         for (int idx = tid; idx < BP * CH16; idx += kThreads) {
             const int row = idx / CH16, c16 = idx % CH16;
