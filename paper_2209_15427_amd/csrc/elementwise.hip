@@ -189,18 +189,15 @@ maxpool_i8x16_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, int N
                      int P, int Q, int k, int st) {
     typedef unsigned v4u __attribute__((ext_vector_type(4)));
     typedef short v2s __attribute__((ext_vector_type(2)));
-    int cv = C / 16;
-    size_t total = (size_t)N * P * Q * cv;
-    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    size_t nthreads = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = tid; i < total; i += nthreads) {
-        int c = (int)(i % cv);
-        size_t px = i / cv;
-        int q = (int)(px % Q);
-        size_t np = px / Q;
-        int p = (int)(np % P);
-        int n = (int)(np / P);
-        const int8_t *base = x + (((size_t)n * H + (size_t)p * st) * W + (size_t)q * st) * C + c * 16;
+    // one workgroup per output row (n, p); threadIdx.x = 16-channel group, threadIdx.y strides q:
+    // no per-thread division, and a row's loads are contiguous runs of C bytes
+    const int np = blockIdx.x;
+    const int n = np / P, p = np - n * P;
+    const int c = threadIdx.x;
+    const int8_t *row0 = x + (((size_t)n * H + (size_t)p * st) * W) * C + c * 16;
+    int8_t *out = y + ((size_t)np * Q) * C + c * 16;
+    for (int q = threadIdx.y; q < Q; q += blockDim.y) {
+        const int8_t *base = row0 + (size_t)q * st * C;
         v2s me[4], mo[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) me[u] = mo[u] = v2s{(short)-32768, (short)-32768};
@@ -218,7 +215,7 @@ maxpool_i8x16_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, int N
 #pragma unroll
         for (int u = 0; u < 4; ++u)
             m[u] = (__builtin_bit_cast(unsigned, mo[u]) & 0xff00ff00u) | ((__builtin_bit_cast(unsigned, me[u]) >> 8) & 0x00ff00ffu);
-        *reinterpret_cast<v4u *>(y + px * C + c * 16) = m;
+        *reinterpret_cast<v4u *>(out + (size_t)q * C) = m;
     }
 }
 
@@ -308,9 +305,11 @@ hipError_t launch_maxpool(const void *x, void *y, int N, int H, int W, int C, in
     size_t total = (size_t)N * P * Q * C;
     if (total == 0) return hipSuccess;
     bool aligned = (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (reinterpret_cast<uintptr_t>(y) % 16 == 0);
-    if (dtype == MPQ_INT8 && C % 16 == 0 && aligned) {
-        maxpool_i8x16_kernel<<<grid_for(total / 16, kThreads), kThreads, 0, st>>>(
-            (const int8_t *)x, (int8_t *)y, N, H, W, C, P, Q, k, s);
+    if (dtype == MPQ_INT8 && C % 16 == 0 && C / 16 <= kThreads && aligned && (long long)N * P <= 0x7fffffffll) {
+        const int cv = C / 16;
+        int ty = kThreads / cv;
+        if (ty > Q) ty = Q;
+        maxpool_i8x16_kernel<<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const int8_t *)x, (int8_t *)y, N, H, W, C, P, Q, k, s);
     } else if (dtype == MPQ_INT8) {
         maxpool_kernel<int8_t><<<grid_for(total, kThreads), kThreads, 0, st>>>((const int8_t *)x, (int8_t *)y,
                                                                              N, H, W, C, P, Q, k, s);

@@ -137,6 +137,9 @@ CONV_CASES = [
     (2, 20, 12, 12, 50, 5, 5, 1, 0, 1, False, (2, 2), 0, 0, 0),        # generic path (LeNet conv2)
     (2, 32, 9, 9, 64, 3, 3, 1, 1, 2, True, (0, 0), 3, -4, 2),          # z_w != 0 -> generic path
     (5, 256, 13, 13, 192, 3, 3, 1, 1, 1, True, (0, 0), 0, 0, 0),       # MoE expert conv3'
+    (3, 128, 13, 13, 400, 3, 3, 1, 1, 2, True, (3, 2), 0, 0, 0),       # image-aligned tiles, pool in the epilogue, ragged channels (200 per group)
+    (2, 64, 12, 14, 128, 3, 3, 1, 1, 1, True, (3, 2), 0, 0, -7),       # image-aligned, non-square image, z_y != 0
+    (2, 64, 12, 14, 128, 3, 3, 1, 1, 1, False, (3, 2), 0, 0, 0),       # image-aligned + pool without ReLU (general requantize)
 ]
 
 
@@ -173,8 +176,8 @@ def test_conv_is_deterministic():
 # ---------------------------------------------------------------------------------------------
 # fp16 convolution
 # ---------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("case", [CONV_CASES[i] for i in (0, 1, 2, 3, 5, 7, 8)],
-                         ids=["c0", "c1", "c2", "c3", "c5", "c7", "c8"])
+@pytest.mark.parametrize("case", [CONV_CASES[i] for i in (0, 1, 2, 3, 5, 7, 8, 11, 12)],
+                         ids=["c0", "c1", "c2", "c3", "c5", "c7", "c8", "c11", "c12"])
 def test_fp16_conv(case):
     _say("fp16 conv", case)
     N, C, H, W, K, R, S, stride, pad, groups, relu, pool = case[:12]
