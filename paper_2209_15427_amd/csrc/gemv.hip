@@ -130,10 +130,9 @@ __global__ void __launch_bounds__(kThreads) gemv_kernel(GemvArgs g) {
 
 template <typename T, int NR>
 hipError_t launch_rows(const GemvArgs &g, hipStream_t st) {
-    // rows per workgroup: enough workgroups to cover the chip several times over
-    if (g.ns >= 4096) {
-        gemv_kernel<T, NR, 4><<<(g.ns + 3) / 4, kThreads, 0, st>>>(g);
-    } else if (g.ns >= 2048) {
+    // rows per workgroup: two where there are rows enough; more rows per workgroup (fewer, longer
+    // workgroups) measured slower on the 4096-row layers, as did plain instead of non-temporal loads
+    if (g.ns >= 2048) {
         gemv_kernel<T, NR, 2><<<(g.ns + 1) / 2, kThreads, 0, st>>>(g);
     } else {
         gemv_kernel<T, NR, 1><<<g.ns, kThreads, 0, st>>>(g);
