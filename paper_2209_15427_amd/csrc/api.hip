@@ -53,6 +53,26 @@ Plan make_plan(const mpq_conv_desc &d, int dtype, int in_w) {
     p.Kp = (int)(round_up((size_t)packed_len * p.esize, kStepBytes) / p.esize);
     p.wsum_off = round_up((size_t)d.k * p.Kp * p.esize, 256);
     p.total = p.wsum_off + round_up((size_t)d.k * 4, 256);
+    // fragment-ordered copy for the stride-1 patch kernel (see Plan): channel blocks of the whole
+    // group (<= 96 bytes per pixel) or of 64 bytes, at least kPatchMinSteps steps per phase
+    if (p.mode == kModeTap && d.stride_h == 1 && d.stride_w == 1 && dtype != MPQ_INT16) {
+        const int CgB = p.Cg * p.esize;
+        int CB = 0;
+        if (CgB <= 96) CB = CgB;
+        else if (CgB % 64 == 0) CB = 64;
+        if (CB >= 32 && CB % kChunkBytes == 0) {
+            const int cbc = CB / kChunkBytes, ksp = (d.r * d.s * cbc + 3) / 4;
+            if (ksp >= kPatchMinSteps) {
+                p.f_cbc = cbc;
+                p.f_nphase = CgB / CB;
+                p.f_ksp = ksp;
+                p.f_rt = (p.Kg + 31) / 32;
+                p.frag_off = p.total;
+                p.frag_bytes = (size_t)d.groups * p.f_rt * p.f_nphase * p.f_ksp * 2048;
+                p.total += round_up(p.frag_bytes, 256);
+            }
+        }
+    }
     return p;
 }
 

@@ -33,6 +33,8 @@ enum PlanMode {
                         // channel-padded copy of the input                       (first layer, C <= 4)
 };
 
+constexpr int kPatchMinSteps = 9;    // patch kernel: one patch slot per step must finish two steps early
+
 struct Plan {
     int mode;
     int esize;        // bytes per element of x / w
@@ -47,6 +49,13 @@ struct Plan {
     int Wp;           // row mode: width of the padded input copy
     size_t wsum_off;  // byte offset of int32 wsum[K] in the packed blob
     size_t total;     // packed blob size in bytes (multiple of 256)
+    // Second copy of the weights in MFMA A-fragment order for the stride-1 patch kernel
+    // (frag_bytes = 0: none).  The reduction axis of a group is cut into f_nphase channel blocks
+    // of f_cbc 16-byte chunks; a phase walks (tap, chunk) in f_ksp steps of 64 bytes.  Per group,
+    // 32-row tile, phase, step and half-step: 1 KiB = 64 lanes x 16 bytes, lane l holding row
+    // l % 32 of the tile, chunk 2 * half + l / 32 of the step (zeros past the last tap / row).
+    int f_cbc, f_nphase, f_ksp, f_rt;   // f_rt: 32-row tiles per group
+    size_t frag_off, frag_bytes;
 };
 
 // Epilogue selector + constants (per tensor; per expert in the MoE launches).

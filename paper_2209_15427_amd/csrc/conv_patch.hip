@@ -30,38 +30,32 @@ using namespace tile;
 constexpr int kMaxPatchSlots = 8;
 constexpr int kImageBP = 192;      // pixel-tile size of the image-aligned variant (one image of <= 192 output pixels per tile)
 
-template <typename T, int BC, int BP, int WGC, int WGP, int NSTW, int NSLOT, int WPE, bool UNI>
+template <typename T, int BC, int BP, int WGC, int WGP, int NSLOT, int WPE, bool UNI>
 __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     typedef Tile<T, BC, BP, WGC, WGP> TL;
     constexpr int WTC = TL::WTC, WTP = TL::WTP, TC = TL::TC, TP = TL::TP, ES = TL::ES;
-    constexpr int LW = BC / 64;                       // weight loads per thread and step
     // NSLOT: patch loads per thread and phase
     constexpr int PATCH_BYTES = NSLOT * kThreads * kChunkBytes;
-    constexpr int WSTAGE = BC * kStepBytes;
-    constexpr int LDS_BYTES = 2 * PATCH_BYTES + NSTW * WSTAGE;
-    static_assert(TL::kImageBytes <= LDS_BYTES, "output tile must fit the LDS");
+    constexpr int LDS_BYTES = 2 * PATCH_BYTES > TL::kImageBytes ? 2 * PATCH_BYTES : TL::kImageBytes;   // <= 80 KiB
+    static_assert(LDS_BYTES <= 80 * 1024, "two workgroups per CU");
     static_assert(TC <= 2 && TP <= 4, "fragment reads are written out for up to 2 x 4 sub-tiles");
-    static_assert(NSTW == 3, "the outstanding-load counts below are derived for three weight stages");
     typedef typename TL::Acc Acc;
 
     __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
-    unsigned char *wring = lds + 2 * PATCH_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wc = wave % WGC, wp = wave / WGC;
     const Plan &pl = a.plan;
-    const int PQ = a.P * a.Q;
 
     TileCtx t;
     if (!decode_tile<BC, BP>(a, t)) return;
     const int g = t.g, m0 = t.m0, m_end = t.m_end, ch0 = t.ch0;
 
-    const __amdgpu_buffer_rsrc_t wrs =
-        __builtin_amdgcn_make_buffer_rsrc((void *)t.wbase, (short)0, (int)pl.wsum_off, 0x00020000);
     const __amdgpu_buffer_rsrc_t xrs =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.x, (short)0, (int)a.x_bytes, 0x00020000);
 
     // ---- geometry of the virtual (zero-padded) input ------------------------------------------
+    const int PQ = a.P * a.Q;
     const int Hv = a.H + 2 * a.pad_h, Wv = a.W + 2 * a.pad_w, HWv = Hv * Wv;
     const int cbc = UNI ? 4 : a.cbc, CB = cbc * kChunkBytes;     // chunks / bytes per pixel per channel block
     const int CgB = pl.Cg * ES;                        // bytes per pixel per group
@@ -77,7 +71,7 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     const int PV = virt(m_last) + (a.R - 1) * Wv + (a.S - 1) - v0 + 1;    // rows of the patch in use
 
     // ---- patch fill: this thread's slots (16-byte chunk slots tid, tid + 256, ...) ---------------
-    // (array bound not dependent on a template parameter: with `xoff[NSLOT]` hipcc's host pass
+    // (array bounds not dependent on a template parameter: with `xoff[NSLOT]` hipcc's host pass
     // silently emitted no launch stub for this kernel)
     unsigned xoff[kMaxPatchSlots];
     static_assert(NSLOT <= kMaxPatchSlots, "more patch loads per thread than slots");
@@ -106,72 +100,42 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
 #pragma unroll
         for (int k = 0; k < NSLOT; ++k) request_slot(k, buf, cb);
     };
-    // one slot of the next phase's patch per step (the slot index must be a constant per load)
-    auto request_patch_part = [&](int k, int buf, int cb) {
-        static_assert(NSLOT <= 8, "slots are written out below");
-        switch (k) {
-        case 0: request_slot(0, buf, cb); break;
-        case 1: if constexpr (NSLOT > 1) request_slot(1, buf, cb); break;
-        case 2: if constexpr (NSLOT > 2) request_slot(2, buf, cb); break;
-        case 3: if constexpr (NSLOT > 3) request_slot(3, buf, cb); break;
-        case 4: if constexpr (NSLOT > 4) request_slot(4, buf, cb); break;
-        case 5: if constexpr (NSLOT > 5) request_slot(5, buf, cb); break;
-        case 6: if constexpr (NSLOT > 6) request_slot(6, buf, cb); break;
-        case 7: if constexpr (NSLOT > 7) request_slot(7, buf, cb); break;
-        }
-    };
-
-    // ---- weight stream: lane l fills slot l of a 16-row group (row l / 4, physical chunk l % 4);
-    // the chunk it fetches is kc = 4 kstep + logical chunk -> (tap, chunk within the channel block).
-    // UNI (64-byte channel blocks): step = tap for every lane, all of this is scalar arithmetic.
-    const int lrow = lane >> 2;
-    const int lchunk = (lane & 3) ^ ((lane >> 4) & 3);
-    // (fixed bounds on the arrays the lambdas below capture: see xoff)
-    static_assert(LW <= 2, "weight loads per thread");
-    unsigned woff[2];
-#pragma unroll
-    for (int i = 0; i < LW; ++i) {
-        const int ch = ch0 + (i * 4 + wave) * 16 + lrow;
-        woff[i] = ch < pl.Kg ? (unsigned)(((size_t)(g * pl.Kg + ch) * pl.Kp) * ES) + (UNI ? (unsigned)lchunk * kChunkBytes : 0u)
-                             : kOob;
-    }
+    // ---- A operand: the fragment-ordered copy of the weights, straight from global memory (L2) ---
+    // Per 32-row tile the steps of all phases are consecutive 2 KiB blocks: first half-step at
+    // + 0, second at + 1024, lane l at + 16 l.  A wavefront reads its own fragments, so the
+    // weights need neither LDS nor a barrier.  Row tiles past the group's last (ragged channel
+    // tile) re-read the last one; their results are never stored.
+    const unsigned char *fbase = (const unsigned char *)t.wbase + pl.frag_off;
     const int KSP = a.ksp;                             // steps per phase
-    int w_cb = 0, w_step = 0;                          // next weight step to request: (phase, step)
-    auto request_weights = [&](int stage) {
-        // past the last phase the requests continue (uniform outstanding-load count) and read zeros
-        unsigned kbyte;
-        if constexpr (UNI) {
-            kbyte = w_cb < a.nphase ? (unsigned)(w_step * CgB + w_cb * CB) : kOob;
-        } else {
-            const unsigned kc = (unsigned)(w_step * 4 + lchunk);
-            const unsigned tap = udiv_magic(kc, a.magic_cbc);
-            const unsigned cc = kc - tap * (unsigned)cbc;
-            kbyte = ((int)tap < NT && w_cb < a.nphase) ? tap * (unsigned)CgB + cc * kChunkBytes + (unsigned)(w_cb * CB) : kOob;
-        }
+    // (fixed bounds on the arrays the lambdas below capture: see xoff)
+    unsigned aoff[2];
 #pragma unroll
-        for (int i = 0; i < LW; ++i)       // woff < 2^31 and kOob < 2^31: the sum cannot wrap back into range
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MPQ_LDS(wring + stage * WSTAGE + (i * 4 + wave) * 1024), 16,
-                                                     woff[i] + kbyte, 0, 0, 0);
-        if (++w_step == KSP) {
-            w_step = 0;
-            ++w_cb;
+    for (int i = 0; i < TC; ++i) {
+        int rt = (ch0 + wc * WTC) / 32 + i;
+        rt = rt < pl.f_rt ? rt : pl.f_rt - 1;
+        aoff[i] = (unsigned)(((g * pl.f_rt + rt) * a.nphase * KSP) * 2048 + lane * kChunkBytes);
+    }
+    v4i af[2][TC], bf[2][TP];
+    // half-step ks of the step whose block starts STEP * 2048 bytes after `base`
+    auto load_a = [&](const int ks, const int next, unsigned base) {
+#pragma unroll
+        for (int i = 0; i < TC; ++i) {
+            if (next) af[ks][i] = ks ? global_read<3072>(fbase, aoff[i] + base) : global_read<2048>(fbase, aoff[i] + base);
+            else af[ks][i] = ks ? global_read<1024>(fbase, aoff[i] + base) : global_read<0>(fbase, aoff[i] + base);
         }
     };
 
     // first requests go out before the rest of the set-up, which then overlaps their latency
     request_patch(0, 0);
-    request_weights(0);
-    request_weights(1);
+    load_a(0, 0, 0u);
+    load_a(1, 0, 0u);
 
     Acc acc[TC][TP];
     TL::init_acc(acc, a, t);
 
-    // ---- fragment addressing -------------------------------------------------------------------
+    // ---- B fragment addressing ------------------------------------------------------------------
     const int frow = lane & 31, fk = lane >> 5;
-    const unsigned sw = (unsigned)((frow >> 2) & 3);
-    const unsigned fa0 = (unsigned)((wc * WTC + frow) * kStepBytes) + ((0u + fk) ^ sw) * kChunkBytes;
-    const unsigned fa1 = (unsigned)((wc * WTC + frow) * kStepBytes) + ((2u + fk) ^ sw) * kChunkBytes;
-    // B: byte address (within patch buffer 0) of this lane's pixel in each 32-pixel sub-tile at
+    // byte address (within patch buffer 0) of this lane's pixel in each 32-pixel sub-tile at
     // tap (0,0); pixels past the tile's end reuse the last valid one (their results are never
     // stored).  UNI adds the lane's half of the reduction step here, the swizzle comes per step.
     unsigned vb[4];
@@ -187,14 +151,9 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     int r_step = 0, r_pbuf = 0, u_s = 0, u_delta = 0;
     unsigned ba[4];                                    // UNI: this step's first-half B addresses
 
-    // Fragments are fetched half a reduction step (one 32-byte k-slice) ahead of the matrix
+    // B fragments are fetched half a reduction step (one 32-byte k-slice) ahead of the matrix
     // instructions that use them: set 0 / set 1 hold the first / second half.
-    v4i af[2][TC], bf[2][TP];
-    auto fetch = [&](const int ks, int stage) {
-        const unsigned wbase_l = (unsigned)(size_t)MPQ_LDS(wring + stage * WSTAGE);
-        const unsigned fa = wbase_l + (ks == 0 ? fa0 : fa1);
-        af[ks][0] = lds_read<0>(fa);
-        if constexpr (TC > 1) af[ks][1] = lds_read<2048>(fa);
+    auto fetch = [&](const int ks) {
         if constexpr (UNI) {
             // rows are 64 bytes: chunk c of row r sits at slot c ^ ((r >> 2) & 3); the buffers are
             // 1 KiB aligned, so bits 8..9 of the byte address are bits 2..3 of the row.  The second
@@ -225,7 +184,7 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
             for (int j = 0; j < TP; ++j) bf[ks][j] = lds_read<0>(vb[j] + o);
         }
     };
-    auto arrived = [&](const int ks) {
+    auto arrived = [&](const int ks) {     // (after the vector-memory wait of the A fragments)
         lds_wait();
 #pragma unroll
         for (int i = 0; i < TC; ++i) lds_arrived(af[ks][i]);
@@ -240,59 +199,79 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     };
 
     // ---- pipeline ---------------------------------------------------------------------------------
-    // Requests complete in order, so a weight load queued behind a whole patch would stall the
-    // loop until that patch is in: the next phase's patch goes out one slot per step instead.
-    // Issue order: P(0) W(0) W(1) | W(2) | then per step k: p(k) W(k + 3), where p(k) is slot
-    // ks of the next phase's patch while the in-phase step index ks < NSLOT.  Step k needs W(k + 1)
-    // before its second half; what was issued after W(k + 1) may stay outstanding: p(k - 1), if
-    // there was one, and W(k + 2).  The last slot leaves in step NSLOT - 1 <= KSP - 3, ahead of the
-    // W that the phase's last step waits for, so the patch is complete when the phase ends.
-    wait_vmcnt<LW>();
+    // Per step k, in program order: use A0(k), B0(k); issue A0(k + 1); use A1(k), B1(k); issue one
+    // slot of the next phase's patch (while the in-phase step index < NSLOT); issue A1(k + 1).
+    // Loads complete in order, so A0(k) has landed when at most [slot of step k - 1] + A1(k), and
+    // A1(k) when at most A0(k + 1), are outstanding.  A slot issued in step j is followed by two
+    // A requests before the second wait of step j + 1, which therefore covers it: every slot of
+    // this wavefront has landed well before the phase's last step (NSLOT <= KSP - 2).  The only
+    // barrier is at a phase end: everyone is done reading this phase's patch buffer (the slots of
+    // the phase after next go there) and everyone's slots of the next patch are in.
+    // The steps of a phase are written out by kind (which slot goes out, whether one went out in
+    // the step before, phase end, last step of all), so that a step's body has no branches: the
+    // branchy single-loop form spent a third of a step in scalar control flow.
+    constexpr int LA = TC;                 // A loads per half-step
+    __builtin_amdgcn_s_waitcnt(0);
     bare_barrier();
-    request_weights(2);
-    fetch(0, 0);
-    int cur = 0;
-    for (int cb = 0; cb < a.nphase; ++cb) {
-        for (int ks = 0; ks < KSP; ++ks) {
-            arrived(0);
-            fetch(1, cur);
-            __builtin_amdgcn_sched_barrier(0);
-            multiply(0);
-            __builtin_amdgcn_sched_barrier(0);
-            arrived(1);                  // this wave is done reading ring slot `cur`
-            const bool phase_end = ks + 1 == KSP;
-            const int nxt = cur + 1 == NSTW ? 0 : cur + 1;
-            if (!(phase_end && cb + 1 == a.nphase)) {
-                const bool more = cb + 1 < a.nphase;
-                if (more && ks >= 1 && ks <= NSLOT) wait_vmcnt<LW + 1>();
-                else wait_vmcnt<LW>();
-                bare_barrier();          // everyone has step k + 1 and is done with slot `cur` (and, at
-                                         // a phase end, with this phase's patch buffer)
-                if (more && ks < NSLOT) request_patch_part(ks, (cb + 1) & 1, cb + 1);
-                request_weights(cur);
-                if (phase_end) {
-                    r_step = 0;
-                    r_pbuf ^= 1;
-                    u_s = 0;
-                    u_delta = 0;
-                } else {
-                    ++r_step;
-                    ++u_delta;
-                    if (++u_s == a.S) {
-                        u_s = 0;
-                        u_delta += dWv;
-                    }
-                }
-                fetch(0, nxt);
-                __builtin_amdgcn_sched_barrier(0);
+    fetch(0);
+    unsigned a_base = 0;                   // byte offset of the current step's block in a row tile's stream
+    constexpr int kEndNone = 0, kEndPhase = 1, kEndAll = 2;
+    // SLOT: patch slot to request in this step (-1: none); PREV: a slot went out in the step before
+    auto step = [&](auto slot_tag, auto prev_tag, auto end_tag, int cb) {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        constexpr bool PREV = decltype(prev_tag)::value;
+        constexpr int END = decltype(end_tag)::value;
+        wait_vmcnt<PREV ? LA + 1 : LA>();
+        arrived(0);
+        fetch(1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(0);
+        if constexpr (END != kEndAll) load_a(0, 1, a_base);
+        wait_vmcnt<END == kEndAll ? 0 : LA>();
+        arrived(1);                  // this wave is done reading the current patch rows
+        if constexpr (END != kEndAll) {
+            if constexpr (END == kEndPhase) bare_barrier();
+            if constexpr (SLOT >= 0) request_slot(SLOT, (cb + 1) & 1, cb + 1);
+            if constexpr (END == kEndPhase) {
+                r_step = 0;
+                r_pbuf ^= 1;
+                u_s = 0;
+                u_delta = 0;
+            } else {
+                ++r_step;
+                const bool wrap = u_s + 1 == a.S;
+                u_delta += wrap ? dWv + 1 : 1;
+                u_s = wrap ? 0 : u_s + 1;
             }
-            multiply(1);
+            fetch(0);
             __builtin_amdgcn_sched_barrier(0);
-            cur = nxt;
         }
+        multiply(1);
+        if constexpr (END != kEndAll) load_a(1, 1, a_base);
+        a_base += 2048u;
+    };
+    using std::integral_constant;
+    typedef integral_constant<int, -1> NoSlot;
+    typedef integral_constant<bool, false> NoPrev;
+    typedef integral_constant<bool, true> Prev;
+    typedef integral_constant<int, kEndNone> Mid;
+    static_assert(NSLOT == 7, "the slot steps are written out below");
+    for (int cb = 0; cb + 1 < a.nphase; ++cb) {
+        // a phase that prefetches the next patch: steps 0 .. NSLOT - 1 carry one slot each
+        step(integral_constant<int, 0>{}, NoPrev{}, Mid{}, cb);
+        step(integral_constant<int, 1>{}, Prev{}, Mid{}, cb);
+        step(integral_constant<int, 2>{}, Prev{}, Mid{}, cb);
+        step(integral_constant<int, 3>{}, Prev{}, Mid{}, cb);
+        step(integral_constant<int, 4>{}, Prev{}, Mid{}, cb);
+        step(integral_constant<int, 5>{}, Prev{}, Mid{}, cb);
+        step(integral_constant<int, 6>{}, Prev{}, Mid{}, cb);
+        step(NoSlot{}, Prev{}, Mid{}, cb);                                   // step NSLOT (< KSP - 1)
+        for (int ks = NSLOT + 1; ks < KSP - 1; ++ks) step(NoSlot{}, NoPrev{}, Mid{}, cb);
+        step(NoSlot{}, NoPrev{}, integral_constant<int, kEndPhase>{}, cb);
     }
-    wait_vmcnt<0>();
-    bare_barrier();
+    for (int ks = 0; ks < KSP - 1; ++ks) step(NoSlot{}, NoPrev{}, Mid{}, 0);
+    step(NoSlot{}, NoPrev{}, integral_constant<int, kEndAll>{}, 0);
+    bare_barrier();                        // everyone is done with the patch buffers
 
     if constexpr (BP == kImageBP) {
         if (a.pool) {
@@ -303,7 +282,7 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     TL::template finish<false>(acc, lds, a, t);
 }
 
-template <typename T, int BC, int BP, int WGC, int WGP, int NSTW, int NSLOT, int WPE, bool UNI>
+template <typename T, int BC, int BP, int WGC, int WGP, int NSLOT, int WPE, bool UNI>
 hipError_t launch_one(ConvArgs a, hipStream_t st) {
     const int PQ = a.P * a.Q;
     const int ctiles = (a.plan.Kg + BC - 1) / BC;
@@ -315,7 +294,7 @@ hipError_t launch_one(ConvArgs a, hipStream_t st) {
     if (blocks <= 0) return hipSuccess;
     if (!set_tile_counts(a, ptiles, ctiles)) return hipErrorInvalidValue;
     if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
-    conv_patch_kernel<T, BC, BP, WGC, WGP, NSTW, NSLOT, WPE, UNI><<<(unsigned)blocks, kThreads, 0, st>>>(a);
+    conv_patch_kernel<T, BC, BP, WGC, WGP, NSLOT, WPE, UNI><<<(unsigned)blocks, kThreads, 0, st>>>(a);
     return hipGetLastError();
 }
 
@@ -338,16 +317,12 @@ bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, bo
     const Plan &pl = a.plan;
     if (pl.mode != kModeTap || a.stride_h != 1 || a.stride_w != 1) return false;
     if (!conv_mfma_dma_eligible(a)) return false;
-    const int CgB = pl.Cg * pl.esize;
-    int CB;
-    if (CgB <= 96) CB = CgB;
-    else if (CgB % 64 == 0) CB = 64;
-    else return false;
-    if (CB % kChunkBytes != 0 || CB < 32) return false;
-    a.cbc = CB / kChunkBytes;
-    a.nphase = CgB / CB;
-    const int NT = a.R * a.S;                          // taps
-    a.ksp = (NT * a.cbc + 3) / 4;
+    // the fragment-ordered weight copy fixes the channel blocking (make_plan)
+    if (pl.frag_bytes == 0 || pl.frag_off + pl.frag_bytes >= 0x7ffffff0ull) return false;
+    a.cbc = pl.f_cbc;
+    a.nphase = pl.f_nphase;
+    a.ksp = pl.f_ksp;
+    const int CB = a.cbc * kChunkBytes;
     if (a.ksp < kPatchSlots + 2) return false;   // one patch slot per step must finish two steps early
     const int Hv = a.H + 2 * a.pad_h, Wv = a.W + 2 * a.pad_w, PQ = a.P * a.Q;
     const int Kg = pl.Kg;
@@ -399,13 +374,13 @@ hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
     const int Kg = a.plan.Kg;
     const bool wide = Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0);
     const bool uni = a.cbc == 4;                       // 64-byte channel blocks: one tap per step
-    if (a.tile_px) return launch_one<T, 128, kImageBP, 2, 2, 3, kPatchSlots, 2, true>(a, st);
+    if (a.tile_px) return launch_one<T, 128, kImageBP, 2, 2, kPatchSlots, 2, true>(a, st);
     if (wide) {
-        if (uni) return launch_one<T, 128, kBP, 2, 2, 3, kPatchSlots, 2, true>(a, st);
-        return launch_one<T, 128, kBP, 2, 2, 3, kPatchSlots, 2, false>(a, st);
+        if (uni) return launch_one<T, 128, kBP, 2, 2, kPatchSlots, 2, true>(a, st);
+        return launch_one<T, 128, kBP, 2, 2, kPatchSlots, 2, false>(a, st);
     }
-    if (uni) return launch_one<T, 64, kBP, 1, 4, 3, kPatchSlots, 2, true>(a, st);
-    return launch_one<T, 64, kBP, 1, 4, 3, kPatchSlots, 2, false>(a, st);
+    if (uni) return launch_one<T, 64, kBP, 1, 4, kPatchSlots, 2, true>(a, st);
+    return launch_one<T, 64, kBP, 1, 4, kPatchSlots, 2, false>(a, st);
 }
 
 }  // namespace

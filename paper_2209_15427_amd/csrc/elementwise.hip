@@ -219,6 +219,35 @@ maxpool_i8x16_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, int N
     }
 }
 
+// Fragment-ordered copy of tap-mode packed weights (layout: see Plan): one thread per 16-byte chunk.
+__global__ void __launch_bounds__(kThreads)
+frag_pack_kernel(const unsigned char *__restrict__ packed, unsigned char *__restrict__ frag, int Kg, size_t row_bytes,
+                 int CgB, int taps, int cbc, int nphase, int ksp, int rt_per_group, size_t nchunks) {
+    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t idx = tid; idx < nchunks; idx += nthreads) {
+        const int l = (int)(idx % 64);
+        size_t t = idx / 64;
+        const int half = (int)(t % 2);
+        t /= 2;
+        const int s = (int)(t % ksp);
+        t /= ksp;
+        const int cb = (int)(t % nphase);
+        t /= nphase;
+        const int rt = (int)(t % rt_per_group);
+        const int g = (int)(t / rt_per_group);
+        const int row = rt * 32 + l % 32;
+        const int kc = 4 * s + 2 * half + l / 32;
+        const int tap = kc / cbc, cc = kc % cbc;
+        v4u v = {0u, 0u, 0u, 0u};
+        if (row < Kg && tap < taps)
+            v = *reinterpret_cast<const v4u *>(packed + (size_t)(g * Kg + row) * row_bytes + (size_t)tap * CgB +
+                                               (size_t)(cb * cbc + cc) * kChunkBytes);
+        reinterpret_cast<v4u *>(frag)[idx] = v;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_quantize(const float *src, void *dst, size_t n, int dtype, float scale, int zp,
@@ -283,6 +312,12 @@ hipError_t launch_pack(const void *w_kcrs, void *packed, const mpq_conv_desc &d,
         wsum_kernel<int16_t><<<g2, kThreads, 0, st>>>((const int16_t *)w_kcrs, wsum, d.k, per_k);
     else
         fill_i32_kernel<<<g2, kThreads, 0, st>>>(wsum, d.k, 0);
+    e = hipGetLastError();
+    if (e != hipSuccess || p.frag_bytes == 0) return e;
+    const size_t nchunks = p.frag_bytes / kChunkBytes;
+    frag_pack_kernel<<<grid_for(nchunks, kThreads), kThreads, 0, st>>>(
+        (const unsigned char *)packed, (unsigned char *)packed + p.frag_off, p.Kg, (size_t)p.Kp * p.esize, p.Cg * p.esize,
+        d.r * d.s, p.f_cbc, p.f_nphase, p.f_ksp, p.f_rt, nchunks);
     return hipGetLastError();
 }
 

@@ -52,6 +52,15 @@ __device__ __forceinline__ void lds_arrived(v4i &f) { asm volatile("" : "+v"(f))
 // for every outstanding direct-to-LDS load, not only for the step that is about to be read
 __device__ __forceinline__ void bare_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
+// 16-byte global load the compiler does not model (the kernels count their own outstanding loads):
+// base is uniform, voff per lane; the value arrives asynchronously, wait_vmcnt<N>() +
+// lds_arrived() must come before its first use.
+template <int OFF> __device__ __forceinline__ v4i global_read(const void *base, unsigned voff) {
+    v4i r;
+    asm volatile("global_load_dwordx4 %0, %1, %2 offset:%3" : "=v"(r) : "v"(voff), "s"(base), "n"(OFF));
+    return r;
+}
+
 // wait until at most N of this wavefront's vector-memory operations are outstanding
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 0xf) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
@@ -195,30 +204,38 @@ struct Tile {
         const Plan &pl = a.plan;
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wc = wave % WGC;
         const int *wsum = reinterpret_cast<const int *>(t.wbase + pl.wsum_off);
+        // all loads first, unconditionally (a missing bias reads the always-present sums and is
+        // masked afterwards): with the loads under branches each one was waited for in turn
+        const bool has_bias = t.bias != nullptr;
+        const char *bsrc = has_bias ? t.bias : reinterpret_cast<const char *>(wsum);
+        v4i braw[TC][4], wraw[TC][4];
 #pragma unroll
-        for (int i = 0; i < TC; ++i) {
+        for (int i = 0; i < TC; ++i)
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
                 const int ch = t.ch0 + wc * WTC + i * 32 + vq * 8 + (lane >> 5) * 4;
                 const int kabs = t.g * pl.Kg + (ch < pl.Kg ? ch : 0);
+                braw[i][vq] = *reinterpret_cast<const v4i *>(bsrc + (size_t)kabs * 4);
+                if constexpr (ES == 1) wraw[i][vq] = *reinterpret_cast<const v4i *>(wsum + kabs);
+            }
+#pragma unroll
+        for (int i = 0; i < TC; ++i) {
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
                 if constexpr (ES == 1) {
-                    v4i b4 = {0, 0, 0, 0};
-                    if (t.bias) b4 = *reinterpret_cast<const v4i *>(t.bias + (size_t)kabs * 4);
-                    if (t.epi.zx != 0) b4 -= *reinterpret_cast<const v4i *>(wsum + kabs) * t.epi.zx;
+                    v4i b4 = has_bias ? braw[i][vq] : v4i{0, 0, 0, 0};
+                    b4 -= wraw[i][vq] * t.epi.zx;
 #pragma unroll
                     for (int j = 0; j < TP; ++j)
 #pragma unroll
                         for (int u = 0; u < 4; ++u) acc[i][j][vq * 4 + u] = b4[u];
                 } else {
-                    float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (t.bias) bb = *reinterpret_cast<const float4 *>(t.bias + (size_t)kabs * 4);
+                    typedef float v4f __attribute__((ext_vector_type(4)));
+                    const v4f bb = has_bias ? __builtin_bit_cast(v4f, braw[i][vq]) : v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int j = 0; j < TP; ++j) {
-                        acc[i][j][vq * 4 + 0] = bb.x;
-                        acc[i][j][vq * 4 + 1] = bb.y;
-                        acc[i][j][vq * 4 + 2] = bb.z;
-                        acc[i][j][vq * 4 + 3] = bb.w;
-                    }
+                    for (int j = 0; j < TP; ++j)
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) acc[i][j][vq * 4 + u] = bb[u];
                 }
             }
         }
