@@ -28,6 +28,7 @@ namespace {
 using namespace tile;
 
 constexpr int kMaxPatchSlots = 8;
+constexpr int kPatchMaxSteps = 40;  // steps per phase the offset table of the non-64-byte variant holds
 constexpr int kImageBP = 192;      // pixel-tile size of the image-aligned variant (one image of <= 192 output pixels per tile)
 
 template <typename T, int BC, int BP, int WGC, int WGP, int NSLOT, int WPE, bool UNI>
@@ -36,7 +37,10 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     constexpr int WTC = TL::WTC, WTP = TL::WTP, TC = TL::TC, TP = TL::TP, ES = TL::ES;
     // NSLOT: patch loads per thread and phase
     constexpr int PATCH_BYTES = NSLOT * kThreads * kChunkBytes;
-    constexpr int LDS_BYTES = 2 * PATCH_BYTES > TL::kImageBytes ? 2 * PATCH_BYTES : TL::kImageBytes;   // <= 80 KiB
+    constexpr int PAIR_BYTES = 2 * PATCH_BYTES > TL::kImageBytes ? 2 * PATCH_BYTES : TL::kImageBytes;
+    // channel blocks that are not 64 bytes: table of per-step patch offsets behind the buffers
+    constexpr int TAB_BYTES = UNI ? 0 : kPatchMaxSteps * 16;
+    constexpr int LDS_BYTES = PAIR_BYTES + TAB_BYTES;
     static_assert(LDS_BYTES <= 80 * 1024, "two workgroups per CU");
     static_assert(TC <= 2 && TP <= 4, "fragment reads are written out for up to 2 x 4 sub-tiles");
     typedef typename TL::Acc Acc;
@@ -151,6 +155,12 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     int r_step = 0, r_pbuf = 0, u_s = 0, u_delta = 0;
     unsigned ba[4];                                    // UNI: this step's first-half B addresses
 
+    // not UNI: the patch offsets of this lane half for the step being fetched (asm read: see lds_read)
+    typedef unsigned v2u __attribute__((ext_vector_type(2)));
+    v2u opair = {0u, 0u};
+    auto load_offsets = [&](int stp) {
+        asm volatile("ds_read_b64 %0, %1" : "=v"(opair) : "v"((unsigned)(size_t)MPQ_LDS(lds + PAIR_BYTES) + (unsigned)((stp * 2 + fk) * 8)));
+    };
     // B fragments are fetched half a reduction step (one 32-byte k-slice) ahead of the matrix
     // instructions that use them: set 0 / set 1 hold the first / second half.
     auto fetch = [&](const int ks) {
@@ -171,15 +181,8 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
                 for (int j = 0; j < TP; ++j) bf[1][j] = lds_read<0>(ba[j] ^ 32u);
             }
         } else {
-            // this lane's chunk is kc = 4 step + 2 ks + fk -> (tap, cc); tap = r S + s sits r Wv + s rows on.
-            // A lane whose chunk lies past the last tap multiplies zero weights: keep its address valid.
-            const unsigned kc = (unsigned)(r_step * 4 + 2 * ks + fk);
-            unsigned tap = udiv_magic(kc, a.magic_cbc);
-            const unsigned cc = kc - tap * (unsigned)cbc;
-            tap = (int)tap < NT ? tap : 0u;
-            const unsigned r = udiv_magic(tap, a.magic_s);
-            const unsigned delta = tap + r * (unsigned)dWv;
-            const unsigned o = delta * (unsigned)CB + cc * kChunkBytes + (unsigned)(r_pbuf * PATCH_BYTES);
+            // (tap, chunk) offsets of this lane half for the step: `opair`, read from the table a step ahead
+            const unsigned o = (ks ? opair[1] : opair[0]) + (unsigned)(r_pbuf * PATCH_BYTES);
 #pragma unroll
             for (int j = 0; j < TP; ++j) bf[ks][j] = lds_read<0>(vb[j] + o);
         }
@@ -210,9 +213,31 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     // The steps of a phase are written out by kind (which slot goes out, whether one went out in
     // the step before, phase end, last step of all), so that a step's body has no branches: the
     // branchy single-loop form spent a third of a step in scalar control flow.
+    // Not UNI: chunk position c = 2 ks + fk of step s is chunk kc = 4 s + c of the phase -> (tap, cc);
+    // tap = r S + q sits r Wv + q patch rows on.  Entry [s][fk] holds the two patch byte offsets
+    // (ks = 0, 1) of that lane half; a position past the last tap multiplies zero weights and reads
+    // tap 0.  Filled here once, read one step ahead in the loop.
+    unsigned *otab = reinterpret_cast<unsigned *>(lds + PAIR_BYTES);
+    if constexpr (!UNI) {
+        if (tid < 4 * KSP) {
+            const int st = tid >> 2, f = (tid >> 1) & 1, ks = tid & 1;
+            const unsigned kc = (unsigned)(st * 4 + 2 * ks + f);
+            unsigned tap = udiv_magic(kc, a.magic_cbc);
+            const unsigned cc = kc - tap * (unsigned)cbc;
+            tap = (int)tap < NT ? tap : 0u;
+            const unsigned r = udiv_magic(tap, a.magic_s);
+            otab[(st * 2 + f) * 2 + ks] = (tap + r * (unsigned)dWv) * (unsigned)CB + cc * kChunkBytes;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
     constexpr int LA = TC;                 // A loads per half-step
     __builtin_amdgcn_s_waitcnt(0);
     bare_barrier();
+    if constexpr (!UNI) {
+        load_offsets(0);
+        lds_wait();
+        asm volatile("" : "+v"(opair));
+    }
     fetch(0);
     unsigned a_base = 0;                   // byte offset of the current step's block in a row tile's stream
     constexpr int kEndNone = 0, kEndPhase = 1, kEndAll = 2;
@@ -224,11 +249,14 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
         wait_vmcnt<PREV ? LA + 1 : LA>();
         arrived(0);
         fetch(1);
+        // (the next step's offsets replace this step's, which fetch(1) has just consumed)
+        if constexpr (!UNI && END != kEndAll) load_offsets(END == kEndPhase ? 0 : r_step + 1);
         __builtin_amdgcn_sched_barrier(0);
         multiply(0);
         if constexpr (END != kEndAll) load_a(0, 1, a_base);
         wait_vmcnt<END == kEndAll ? 0 : LA>();
         arrived(1);                  // this wave is done reading the current patch rows
+        if constexpr (!UNI) asm volatile("" : "+v"(opair));
         if constexpr (END != kEndAll) {
             if constexpr (END == kEndPhase) bare_barrier();
             if constexpr (SLOT >= 0) request_slot(SLOT, (cb + 1) & 1, cb + 1);
@@ -324,6 +352,7 @@ bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, bo
     a.ksp = pl.f_ksp;
     const int CB = a.cbc * kChunkBytes;
     if (a.ksp < kPatchSlots + 2) return false;   // one patch slot per step must finish two steps early
+    if (a.cbc != 4 && a.ksp > kPatchMaxSteps) return false;
     const int Hv = a.H + 2 * a.pad_h, Wv = a.W + 2 * a.pad_w, PQ = a.P * a.Q;
     const int Kg = pl.Kg;
     const bool wide = Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0);
