@@ -254,33 +254,38 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             bbase[j] = patch_addr + (unsigned)(py * a.stride * a.pitch + px * a.stride * 4);
         }
         if (tile_live[0]) {      // uniform per wavefront: tiles are assigned in order
-            // this lane's chunk index advances by 2 per step: (kr, kj) = (kc / cpt, kc % cpt); the
-            // fragments of step ks + 1 are requested before step ks is multiplied
-            int kc = fk, kr = kc / a.cpt, kj = kc % a.cpt;
-            const int ksteps = (a.nchunks + 1) / 2;
+            // A step multiplies chunks 2 ks and 2 ks + 1 (lane halves fk = 0, 1) of the R * cpt chunks
+            // of a weight row; this lane's chunk kc = 2 ks + fk is chunk kj of kernel row kr.  The
+            // offsets advance without branches, the steps come in pairs (fragment sets 0 and 1, the
+            // next step's fragments requested before this step is multiplied), and an odd chunk
+            // count leaves a last half step in which the fk = 1 lanes contribute nothing.
+            const int full = a.nchunks >> 1, tail = a.nchunks & 1;
+            const unsigned wrap_add = (unsigned)(a.pitch - a.cpt * 16 + 32);
+            int kj = fk;                               // fk < cpt
+            unsigned aoff = (unsigned)(fk * 16), boff = (unsigned)(fk * 16);
             v4i af[2][kRowTiles], bf[2][kColTiles];
             auto fetch = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles]) {
-                const bool kval = kc < a.nchunks;       // odd chunk count: the last half step reads chunk 0
-                const unsigned aoff = kval ? (unsigned)(kc * 16) : 0u;
-                const unsigned boff = kval ? (unsigned)(kr * a.pitch + kj * 16) : 0u;
 #pragma unroll
                 for (int i = 0; i < kRowTiles; ++i) fa[i] = lds_read16(wl_addr + (unsigned)(i * 32 * a.Kp) + aoff);
 #pragma unroll
                 for (int j = 0; j < kColTiles; ++j) fb[j] = lds_read16(bbase[j] + boff);
-                kc += 2;
+                aoff += 32u;
                 kj += 2;
-                if (kj >= a.cpt) {
-                    kj -= a.cpt;
-                    ++kr;
-                }
+                const bool wrap = kj >= a.cpt;
+                kj -= wrap ? a.cpt : 0;
+                boff += wrap ? wrap_add : 32u;
             };
-            auto multiply = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles], bool kval) {
+            // YOUNGER: a fetch issued after this set's is still in flight (LDS reads return in order)
+            auto multiply = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles], auto tail_tag, auto younger_tag) {
+                if constexpr (decltype(younger_tag)::value) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(kRowTiles + kColTiles));
+                else asm volatile("s_waitcnt lgkmcnt(0)");
 #pragma unroll
                 for (int i = 0; i < kRowTiles; ++i) lds_arrived(fa[i]);
 #pragma unroll
                 for (int j = 0; j < kColTiles; ++j) {
                     lds_arrived(fb[j]);
-                    if (!kval) fb[j] = v4i{0, 0, 0, 0};      // ... and contributes nothing
+                    if constexpr (decltype(tail_tag)::value)
+                        if (fk) fb[j] = v4i{0, 0, 0, 0};
                 }
 #pragma unroll
                 for (int i = 0; i < kRowTiles; ++i)
@@ -288,16 +293,22 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
                     for (int j = 0; j < kColTiles; ++j)       // (a dead second tile recomputes pixel 0)
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
             };
+            // (a fetch past the last chunk reads valid LDS addresses and is never multiplied)
             fetch(af[0], bf[0]);
-            for (int ks = 0; ks < ksteps; ks += 2) {
-                lds_wait();
-                if (ks + 1 < ksteps) fetch(af[1], bf[1]);
-                multiply(af[0], bf[0], 2 * ks + fk < a.nchunks);
-                if (ks + 1 < ksteps) {
-                    lds_wait();
-                    if (ks + 2 < ksteps) fetch(af[0], bf[0]);
-                    multiply(af[1], bf[1], 2 * (ks + 1) + fk < a.nchunks);
-                }
+            for (int p = 0; p < (full >> 1); ++p) {
+                fetch(af[1], bf[1]);
+                multiply(af[0], bf[0], std::false_type{}, std::true_type{});
+                fetch(af[0], bf[0]);
+                multiply(af[1], bf[1], std::false_type{}, std::true_type{});
+            }
+            if (full & 1) {
+                fetch(af[1], bf[1]);
+                multiply(af[0], bf[0], std::false_type{}, std::true_type{});
+                if (tail) multiply(af[1], bf[1], std::true_type{}, std::false_type{});
+                else lds_wait();
+            } else {
+                if (tail) multiply(af[0], bf[0], std::true_type{}, std::false_type{});
+                else lds_wait();
             }
         }
         lds_barrier();                                // everyone is done reading the patch
