@@ -9,7 +9,8 @@
 // network) is immediately pooled 4:1.  One persistent workgroup per compute unit
 //   1. loads the whole packed weight matrix (K <= 96 rows x R * 48 bytes) and the per-channel
 //      accumulator start values into LDS once,
-//   2. walks strips of output rows (blockIdx.x, + gridDim.x, ...).  Per strip: the raw N,H,W,3
+//   2. walks a contiguous range of output-row strips (consecutive strips of an image share input
+//      rows and output cache lines: they stay on one CU).  Per strip: the raw N,H,W,3
 //      input rows arrive by direct-to-LDS loads that were issued a strip earlier, and are
 //      expanded in LDS to 4 bytes per pixel, so that every tap run starts 16-byte aligned (the
 //      4th byte meets a zero weight),
@@ -185,8 +186,11 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             cst[tid] = v;
         }
     }
-    int sidx = blockIdx.x;
-    if (sidx >= total_strips) {
+    // this workgroup's strips: a contiguous range
+    const int per = (total_strips + (int)gridDim.x - 1) / (int)gridDim.x;
+    int sidx = blockIdx.x * per;
+    const int s_end = min(sidx + per, total_strips);
+    if (sidx >= s_end) {
         __builtin_amdgcn_s_waitcnt(0);
         return;
     }
@@ -208,9 +212,9 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
         __syncthreads();                              // ... for everyone; the previous image is consumed
         expand_strip(cur);
         lds_barrier();                                // patch complete, `stage` free
-        const int next = sidx + gridDim.x;
+        const int next = sidx + 1;
         Strip nxt = cur;
-        if (next < total_strips) {                    // the next strip's rows arrive behind the arithmetic
+        if (next < s_end) {                           // the next strip's rows arrive behind the arithmetic
             nxt = strip_of(next);
             request_strip(nxt);
         } else {
@@ -366,7 +370,7 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             *reinterpret_cast<unsigned *>(y + (((size_t)cur.n * a.Po + cur.o0 + orow) * a.Qo + oq) * a.K + cd * 4) = v;
         }
 
-        if (next >= total_strips) break;
+        if (next >= s_end) break;
         sidx = next;
         cur = nxt;
     }
@@ -439,7 +443,7 @@ hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_
     const long long total = (long long)c.N * a.strips;
     if (total <= 0) return hipSuccess;
     if (total > 0x7fffffffll) return hipErrorNotSupported;
-    // one persistent workgroup per compute unit, each walking strips blockIdx.x, + gridDim.x, ...
+    // one persistent workgroup per compute unit, each walking a contiguous range of strips
     static int cus = 0;
     if (cus == 0) {
         int dev = 0;
