@@ -201,6 +201,7 @@ def main():
 
     if not args.no_extras:
         out["fc_batch1"] = bench_fc(torch, mb, pl, cf, calib, args.dtype)
+        out["fc_batches"] = bench_fc_batches(torch, mb, pl, cf, calib, args.dtype)
         if B == 256:
             out["moe_config5"] = bench_moe(torch, mb, pl, cf, calib, args.dtype, chain.acts[1], B)
 
@@ -333,6 +334,29 @@ def bench_fc(torch, mb, pl, cf, calib, dtype_name):
                        "cold_frac_hbm": round(wbytes / cold_us / 1e3 / HBM_PEAK_GBS, 4),
                        "warm_us": round(warm_us, 2), "warm_GBs": round(wbytes / warm_us / 1e3, 1)}
         del big
+    return res
+
+
+def bench_fc_batches(torch, mb, pl, cf, calib, dtype_name, batches=(16, 256)):
+    """Config 4 at the larger batches (weights warm in the cache): per layer time, rate and the
+    weight bytes per second it implies."""
+    dt = mb.DTYPE_ID[dtype_name]
+    res = {}
+    for B in batches:
+        row = {}
+        for li, L in enumerate(cf.ALEXNET_FCS):
+            _, x, w, b = cf.fc_case(li, B)
+            if dtype_name == "fp16":
+                chain = pl.Chain([L], [(w, b)], dt, B, (L.K, 1, 1))
+            else:
+                sc = calib.load()["fc"][L.name][dtype_name]
+                chain = pl.Chain([L], [(w, b)], dt, B, (L.K, 1, 1), sc["x"], sc["layers"])
+            xs = chain.input_storage(x)
+            us = graph_time(torch, lambda: chain.run_layer(0, xs), 5, 10)
+            es = 1 if dtype_name == "int8" else 2
+            row[L.name] = {"us": round(us, 1), "tops": round(2.0 * B * L.N * L.K / us / 1e6, 1),
+                           "weight_GBs": round(L.N * L.K * es / us / 1e3, 1)}
+        res[f"batch{B}"] = row
     return res
 
 
