@@ -40,13 +40,16 @@ def parse():
 PEAK = {"int8": 5000.0, "fp16": 2500.0, "int16": 1250.0}   # dense MFMA, TOP/s (int16: int8 peak / 4)
 HBM_PEAK_GBS = 8000.0
 
+# Layers whose max-pool runs inside the convolution kernel (one kernel per layer call).
+FUSED_POOL = ("conv1", "conv5")
+
 # HBM bytes per launch (fetch + write) of the convolution kernels, from rocprofv3 --pmc runs of
 # `bench.py --profile-layer NAME` (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter
 # reads for `--profile-layer copy`); the summaries are under profiles/.  None: not measured.
 MEASURED_TRAFFIC = {
-    ("conv1", "int8", 256): (2 * 25745.0 + 17496.0) * 1024, ("conv2", "int8", 256): (2 * 18356.2 + 46656.0) * 1024,
-    ("conv3", "int8", 256): (2 * 9086.4 + 16224.0) * 1024, ("conv4", "int8", 256): (2 * 12417.9 + 16257.7) * 1024,
-    ("conv5", "int8", 256): (2 * 11945.6 + 10816.0) * 1024,
+    ("conv1", "int8", 256): (2 * 20513.6 + 25178.1) * 1024, ("conv2", "int8", 256): (2 * 18333.1 + 46656.0) * 1024,
+    ("conv3", "int8", 256): (2 * 9104.4 + 16224.0) * 1024, ("conv4", "int8", 256): (2 * 12482.9 + 16264.1) * 1024,
+    ("conv5", "int8", 256): (2 * 11824.0 + 2304.0) * 1024,
 }
 
 
@@ -96,7 +99,7 @@ def main():
         else:
             i = [L.name for L in cf.ALEXNET_CONVS].index(args.profile_layer)
             ins = [x_store] + chain.acts[:-1]
-            call = (lambda: chain.run_layer(0, ins[0])) if i == 0 else conv_only_call(mb, chain, ins, i, dt)
+            call = (lambda: chain.run_layer(i, ins[i])) if cf.ALEXNET_CONVS[i].name in FUSED_POOL else conv_only_call(mb, chain, ins, i, dt)
         for _ in range(args.steps):
             call()
         torch.cuda.synchronize()
@@ -160,13 +163,13 @@ def main():
         layer_us[L.name] = time_call(lambda i=i: chain.run_layer(i, ins[i]))
 
     # ---- dominant kernel: the convolution kernel of the slowest layer, timed alone -----------
-    # (same kernel, same launch shape.  conv1's kernel has its 3x3/2 pool fused and is timed as it
-    # runs in the step; the other pooled layers are re-issued without their pool so that the
-    # events bracket exactly one kernel per launch)
+    # (same kernel, same launch shape.  conv1 and conv5 take their 3x3/2 pool inside the kernel and
+    # are timed as they run in the step; conv2 is re-issued without its pool so that the events
+    # bracket exactly one kernel per launch)
     conv_only_us = {}
     names = [L.name for L in cf.ALEXNET_CONVS]
     for i, L in enumerate(cf.ALEXNET_CONVS):
-        if i == 0:
+        if L.name in FUSED_POOL:
             conv_only_us[L.name] = layer_us[L.name]
             continue
         conv_only_us[L.name] = time_call(conv_only_call(mb, chain, ins, i, dt))
