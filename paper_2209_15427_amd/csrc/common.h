@@ -104,6 +104,7 @@ struct ConvArgs {
     int ksteps;            // 64-byte steps along the packed reduction axis
     int tap_px;            // input pixels one tap spans (1, or the padded row length in row mode)
     int ptiles;            // pixel tiles in the grid (filled by the launcher)
+    int big_patch;         // patch kernel: the single-phase variant with one large patch buffer
     int tile_px;           // 0: a pixel tile is BP consecutive output pixels; else image-aligned tiles of P Q pixels
     int pool;              // image-aligned tiles only: store the 3x3 / stride-2 max-pool of the output (Po x Qo)
     int Po, Qo;

@@ -27,7 +27,7 @@ namespace {
 
 using namespace tile;
 
-constexpr int kMaxPatchSlots = 8;
+constexpr int kMaxPatchSlots = 12;
 constexpr int kPatchMaxSteps = 40;  // steps per phase the offset table of the non-64-byte variant holds
 constexpr int kImageBP = 192;      // pixel-tile size of the image-aligned variant (one image of <= 192 output pixels per tile)
 
@@ -35,9 +35,12 @@ template <typename T, int BC, int BP, int WGC, int WGP, int NSLOT, int WPE, bool
 __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     typedef Tile<T, BC, BP, WGC, WGP> TL;
     constexpr int WTC = TL::WTC, WTP = TL::WTP, TC = TL::TC, TP = TL::TP, ES = TL::ES;
-    // NSLOT: patch loads per thread and phase
+    // NSLOT: patch loads per thread and phase.  More than 7: the single-phase variant (the whole
+    // group's channels in one block), which needs no second buffer and can afford a larger patch.
+    constexpr bool ONE = NSLOT > 7;
     constexpr int PATCH_BYTES = NSLOT * kThreads * kChunkBytes;
-    constexpr int PAIR_BYTES = 2 * PATCH_BYTES > TL::kImageBytes ? 2 * PATCH_BYTES : TL::kImageBytes;
+    constexpr int BUF_BYTES = (ONE ? 1 : 2) * PATCH_BYTES;
+    constexpr int PAIR_BYTES = BUF_BYTES > TL::kImageBytes ? BUF_BYTES : TL::kImageBytes;
     // channel blocks that are not 64 bytes: table of per-step patch offsets behind the buffers
     constexpr int TAB_BYTES = UNI ? 0 : kPatchMaxSteps * 16;
     constexpr int LDS_BYTES = PAIR_BYTES + TAB_BYTES;
@@ -283,7 +286,8 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     typedef integral_constant<bool, false> NoPrev;
     typedef integral_constant<bool, true> Prev;
     typedef integral_constant<int, kEndNone> Mid;
-    static_assert(NSLOT == 7, "the slot steps are written out below");
+    static_assert(NSLOT == 7 || ONE, "the slot steps are written out below");
+    if constexpr (!ONE)
     for (int cb = 0; cb + 1 < a.nphase; ++cb) {
         // a phase that prefetches the next patch: steps 0 .. NSLOT - 1 carry one slot each
         step(integral_constant<int, 0>{}, NoPrev{}, Mid{}, cb);
@@ -328,6 +332,8 @@ hipError_t launch_one(ConvArgs a, hipStream_t st) {
 
 constexpr int kPatchSlots = 7;                                  // 16-byte loads per thread
 constexpr int kPatchBytes = kPatchSlots * 256 * kChunkBytes;    // 28 KiB per patch buffer
+constexpr int kBigSlots = 11;                                   // single-phase layers: one buffer of 44 KiB
+constexpr int kBigBytes = kBigSlots * 256 * kChunkBytes;
 constexpr int kBP = 256;
 
 }  // namespace
@@ -374,8 +380,13 @@ bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, bo
         const long long span = virt((long long)s0 + (a.tile_px ? PQ : kBP) - 1) + (long long)(a.R - 1) * Wv + (a.S - 1) - virt(s0) + 1;
         if (span > worst) worst = span;
     }
-    if (worst * CB > kPatchBytes) return false;
-    const unsigned long long vmax = (unsigned long long)(a.N + 1) * Hv * Wv + kPatchBytes;
+    a.big_patch = 0;
+    if (worst * CB > kPatchBytes) {
+        // a single-phase layer whose channel block is not 64 bytes may use the one large buffer
+        if (a.nphase != 1 || a.cbc == 4 || a.tile_px || worst * CB > kBigBytes) return false;
+        a.big_patch = 1;
+    }
+    const unsigned long long vmax = (unsigned long long)(a.N + 1) * Hv * Wv + kBigBytes;
     if (vmax * (unsigned long long)(Hv * Wv) >= (1ull << 32)) return false;    // exactness of the magic division
     a.magic_wv = magic_u32((unsigned)Wv);
     a.magic_hw = magic_u32((unsigned)(Hv * Wv));
@@ -406,9 +417,11 @@ hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
     if (a.tile_px) return launch_one<T, 128, kImageBP, 2, 2, kPatchSlots, 2, true>(a, st);
     if (wide) {
         if (uni) return launch_one<T, 128, kBP, 2, 2, kPatchSlots, 2, true>(a, st);
+        if (a.big_patch) return launch_one<T, 128, kBP, 2, 2, kBigSlots, 2, false>(a, st);
         return launch_one<T, 128, kBP, 2, 2, kPatchSlots, 2, false>(a, st);
     }
     if (uni) return launch_one<T, 64, kBP, 1, 4, kPatchSlots, 2, true>(a, st);
+    if (a.big_patch) return launch_one<T, 64, kBP, 1, 4, kBigSlots, 2, false>(a, st);
     return launch_one<T, 64, kBP, 1, 4, kPatchSlots, 2, false>(a, st);
 }
 
