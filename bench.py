@@ -41,7 +41,8 @@ PEAK = {"int8": 5000.0, "fp16": 2500.0, "int16": 1250.0}   # dense MFMA, TOP/s (
 HBM_PEAK_GBS = 8000.0
 
 # Layers whose max-pool runs inside the convolution kernel (one kernel per layer call).
-FUSED_POOL = ("conv1", "conv5")
+FUSED_POOL = ()
+FUSED_POOL_BY_DTYPE = {"int8": ("conv1", "conv5"), "fp16": ("conv5",), "int16": ()}
 
 # HBM bytes per launch (fetch + write) of the convolution kernels, from rocprofv3 --pmc runs of
 # `bench.py --profile-layer NAME` (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter
@@ -66,6 +67,8 @@ def main():
     from workloads import calib, configs as cf
 
     mb.lib()    # fails loudly if the HIP library is missing
+    global FUSED_POOL
+    FUSED_POOL = FUSED_POOL_BY_DTYPE[args.dtype]
     torch.cuda.set_device(0)
     dt = mb.DTYPE_ID[args.dtype]
     B = args.batch

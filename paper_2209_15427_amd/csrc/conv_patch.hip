@@ -27,7 +27,7 @@ namespace {
 
 using namespace tile;
 
-constexpr int kMaxPatchSlots = 12;
+constexpr int kMaxPatchSlots = 14;
 constexpr int kPatchMaxSteps = 40;  // steps per phase the offset table of the non-64-byte variant holds
 constexpr int kImageBP = 192;      // pixel-tile size of the image-aligned variant (one image of <= 192 output pixels per tile)
 
@@ -332,7 +332,7 @@ hipError_t launch_one(ConvArgs a, hipStream_t st) {
 
 constexpr int kPatchSlots = 7;                                  // 16-byte loads per thread
 constexpr int kPatchBytes = kPatchSlots * 256 * kChunkBytes;    // 28 KiB per patch buffer
-constexpr int kBigSlots = 11;                                   // single-phase layers: one buffer of 44 KiB
+constexpr int kBigSlots = 13;                                   // single-phase layers: one buffer of 52 KiB
 constexpr int kBigBytes = kBigSlots * 256 * kChunkBytes;
 constexpr int kBP = 256;
 
