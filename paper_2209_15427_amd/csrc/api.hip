@@ -240,8 +240,14 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     if (seg && seg->w_stride % 256 != 0) use_mfma = false;
 
     hipError_t err = hipSuccess;
-    if (!seg && gemv_eligible(a)) {
-        // batch <= 16 (or <= 16 outputs): memory-bound, one pass over the larger matrix
+    if (!seg && gemv_eligible(a) && (a.N < 4 || a.K <= 16)) {
+        // batch < 4 (or <= 16 outputs): memory-bound, one pass over the larger matrix on the dot units
+        err = launch_gemv(a, st);
+    } else if (fc_stream_eligible(a)) {
+        // a matrix product on up to a few hundred rows (or an expert's rows): weights streamed once
+        // per 128 rows through the matrix cores
+        err = launch_fc_stream(a, st);
+    } else if (!seg && gemv_eligible(a)) {
         err = launch_gemv(a, st);
     } else if (use_mfma) {
         a.ksteps = (int)((size_t)pl.Kp * pl.esize / kStepBytes);

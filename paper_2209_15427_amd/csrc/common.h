@@ -147,6 +147,8 @@ hipError_t launch_conv_first(const ConvArgs &a, int pool_k, int pool_s, void *y_
                              hipStream_t st);
 bool gemv_eligible(const ConvArgs &a);
 hipError_t launch_gemv(const ConvArgs &a, hipStream_t st);
+bool fc_stream_eligible(const ConvArgs &a);
+hipError_t launch_fc_stream(const ConvArgs &a, hipStream_t st);
 
 // MoE helpers
 hipError_t launch_route(const void *logits, int logits_dtype, int B, int E, int *expert, int *counts,

@@ -1,0 +1,232 @@
+// Fully-connected layer on a few hundred rows at most (batch 4..512, or an expert's share of the
+// batch): the weights are the large operand and are streamed from HBM once per group of 128 rows.
+//
+// acc[m, n] = sum_k x[m, k] w[n, k] on the raw codes (expanded zero-point form, section
+// "Quantized Operations"), then the same fused epilogue as the other kernels.
+//
+// A workgroup owns 32 output features x up to 128 rows.  Weights are the MFMA A operand (a lane
+// holds 4 consecutive features of one row of the batch, as in the convolution kernels), the rows
+// of x the B operand; both come straight from global memory in 16-byte loads -- the activations
+// of a row group are a few hundred KiB and stay in L2, no LDS staging.  The four wavefronts split
+// the reduction axis in interleaved 128-byte steps (whole cache lines of every weight row) and
+// add their partial tiles through LDS before the epilogue.  In the expert-grouped launch a row
+// group never crosses an expert boundary and takes that expert's weights, bias and epilogue
+// constants.
+//
+// The implicit-GEMM convolution kernel on the same shapes has one 256-row pixel tile per 64
+// features: 64..160 workgroups, each walking the whole reduction axis with a barrier per step.
+#include "mfma_tile.h"
+
+namespace mpq {
+
+namespace {
+
+using namespace tile;
+
+constexpr int kFeat = 32;              // output features per workgroup
+constexpr int kStep = 128;             // reduction bytes per wavefront step
+
+// NRT: 32-row tiles the instance can hold (rows per group = 32 NRT); U: reduction steps whose loads
+// are in flight together (HBM latency is covered by bytes in flight: 64 U bytes of weights per lane)
+template <typename T, int NRT, int U>
+__global__ void __launch_bounds__(kThreads, 2) fc_stream_kernel(ConvArgs a, int ctiles) {
+    constexpr int ES = (int)sizeof(T);
+    typedef typename Mma<T>::Acc Acc;
+    constexpr int kRowsPerGroup = 32 * NRT;
+    __shared__ int red[4 * NRT * 16 * 64];             // [wave][row tile][register][lane], 16 NRT KiB
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int frow = lane & 31, fk = lane >> 5;
+    const Plan &pl = a.plan;
+
+    const int ct = blockIdx.x % ctiles;
+    int rg = blockIdx.x / ctiles;
+    int m_begin, m_end = a.N;
+    const char *wbase = (const char *)a.w;
+    const char *bias = (const char *)a.bias;
+    Epi epi = a.epi;
+    if (a.seg.offsets) {
+        // expert e owns ceil(rows_e / 128) consecutive row groups
+        int e = 0, base = 0;
+        bool found = false;
+        for (; e < a.seg.num_experts; ++e) {
+            const int lo = a.seg.offsets[e], hi = a.seg.offsets[e + 1];
+            const int groups = (hi - lo + kRowsPerGroup - 1) / kRowsPerGroup;
+            if (rg < base + groups) {
+                m_begin = lo + (rg - base) * kRowsPerGroup;
+                m_end = hi;
+                found = true;
+                break;
+            }
+            base += groups;
+        }
+        if (!found) return;
+        wbase += (size_t)e * a.seg.w_stride;
+        if (bias) bias += (size_t)e * a.seg.bias_stride * 4;
+        epi = a.seg.epi[e];
+    } else {
+        m_begin = rg * kRowsPerGroup;
+        if (m_begin >= a.N) return;
+    }
+    const int rows = min(kRowsPerGroup, m_end - m_begin);
+    const int nrt = (rows + 31) >> 5;                  // live 32-row tiles
+    const int n0 = ct * kFeat;
+
+    // this lane's rows: weight row n0 + frow (past the last feature: the last one, discarded later)
+    // and row frow of each 32-row tile of x (past the group's end: the last row, discarded later)
+    const int Kb = a.C * ES;                           // reduction bytes per row
+    const size_t w_pitch = (size_t)pl.Kp * ES, x_pitch = (size_t)a.C * ES;
+    const char *wrow = wbase + (size_t)min(n0 + frow, a.K - 1) * w_pitch + fk * 16;
+    const char *xrow[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) xrow[rt] = (const char *)a.x + (size_t)min(m_begin + rt * 32 + frow, m_end - 1) * x_pitch + fk * 16;
+
+    Acc acc[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[rt][v] = 0;
+
+    const v4i zero = {0, 0, 0, 0};
+    for (int k0 = wave * kStep; k0 < Kb; k0 += U * 4 * kStep) {
+        v4i af[U][4], bf[U][NRT][4];
+#pragma unroll
+        for (int s = 0; s < U; ++s)
+#pragma unroll
+            for (int sub = 0; sub < 4; ++sub) {
+                const int off = k0 + s * 4 * kStep + sub * 32;
+                const bool live = off + fk * 16 + 16 <= Kb;    // (the axis is a multiple of 16 bytes)
+                af[s][sub] = live ? __builtin_nontemporal_load(reinterpret_cast<const v4i *>(wrow + off)) : zero;
+#pragma unroll
+                for (int rt = 0; rt < NRT; ++rt)
+                    bf[s][rt][sub] = (live && rt < nrt) ? *reinterpret_cast<const v4i *>(xrow[rt] + off) : zero;
+            }
+#pragma unroll
+        for (int s = 0; s < U; ++s)
+#pragma unroll
+            for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+                for (int rt = 0; rt < NRT; ++rt)
+                    if (rt < nrt) acc[rt] = Mma<T>::run(af[s][sub], bf[s][rt][sub], acc[rt]);
+    }
+
+    // partial tiles -> LDS (as raw 32-bit words), summed by the epilogue threads
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+        if (rt < nrt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                // (element first, conversion second: hipcc turned a bit_cast of acc[rt][v] into element 0
+                // for every v)
+                if constexpr (ES == 1) {
+                    const int e = acc[rt][v];
+                    red[((wave * NRT + rt) * 16 + v) * 64 + lane] = e;
+                } else {
+                    const float e = acc[rt][v];
+                    red[((wave * NRT + rt) * 16 + v) * 64 + lane] = __float_as_int(e);
+                }
+            }
+    __syncthreads();
+
+    // Register v of lane l of a tile: feature 8*(v/4) + 4*(l/32) + v%4, row l%32.  One item = 4
+    // consecutive features (quad q) of one row m.
+    const int *wsum = reinterpret_cast<const int *>(wbase + pl.wsum_off);
+    const bool raw = epi.kind == kEpiRawI32 || epi.kind == kEpiRawF32;
+    for (int it = tid; it < rows * 8; it += kThreads) {
+        const int m = it >> 3, q = it & 7;
+        const int n = n0 + 4 * q;
+        if (n >= a.K) continue;
+        const int rt = m >> 5, l = (q & 1) * 32 + (m & 31), vbase = 4 * (q >> 1);
+        const size_t o = (size_t)(m_begin + m) * a.K + n;
+        if constexpr (ES == 1) {
+            int t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                int sacc = 0;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) sacc += red[((w * NRT + rt) * 16 + vbase + u) * 64 + l];
+                if (bias) sacc += reinterpret_cast<const int *>(bias)[n + u];
+                if (epi.zx != 0) sacc -= epi.zx * wsum[n + u];
+                t[u] = sacc;
+            }
+            if (raw) {
+                *reinterpret_cast<v4i *>((int *)a.y + o) = v4i{t[0], t[1], t[2], t[3]};
+            } else {
+                unsigned packed = 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) packed |= ((unsigned)requant32(t[u], epi) & 0xffu) << (8 * u);
+                *reinterpret_cast<unsigned *>((int8_t *)a.y + o) = packed;
+            }
+        } else {
+            float f[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float sacc = 0.f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) sacc += __int_as_float(red[((w * NRT + rt) * 16 + vbase + u) * 64 + l]);
+                if (bias) sacc += reinterpret_cast<const float *>(bias)[n + u];
+                if (epi.relu) sacc = sacc > 0.f ? sacc : 0.f;
+                f[u] = sacc;
+            }
+            if (raw) {
+                *reinterpret_cast<float4 *>((float *)a.y + o) = make_float4(f[0], f[1], f[2], f[3]);
+            } else {
+                typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+                *reinterpret_cast<v4h *>((_Float16 *)a.y + o) = v4h{(_Float16)f[0], (_Float16)f[1], (_Float16)f[2], (_Float16)f[3]};
+            }
+        }
+    }
+}
+
+}  // namespace
+
+// 1x1 "convolution" on a 1x1 image (a matrix product), dense, row-major packed weights, 16-byte
+// aligned rows; int8 needs z_w = 0 (every expert's, in a grouped launch).
+bool fc_stream_eligible(const ConvArgs &a) {
+    if (a.R != 1 || a.S != 1 || a.H != 1 || a.W != 1 || a.groups != 1) return false;
+    if (a.in_dtype != MPQ_INT8 && a.in_dtype != MPQ_FP16) return false;
+    if (a.plan.mode != kModeTap) return false;
+    const int es = a.plan.esize;
+    if (((size_t)a.C * es) % kChunkBytes != 0 || a.K % 4 != 0) return false;
+    if ((reinterpret_cast<uintptr_t>(a.x) % 16) || (reinterpret_cast<uintptr_t>(a.w) % 16) ||
+        (reinterpret_cast<uintptr_t>(a.y) % 16) || (a.bias && reinterpret_cast<uintptr_t>(a.bias) % 16))
+        return false;
+    if (a.in_dtype == MPQ_INT8) {
+        if (a.epi.zw != 0) return false;
+        if (a.seg.offsets)
+            for (int e = 0; e < a.seg.num_experts; ++e)
+                if (a.seg.epi[e].zw != 0) return false;
+    }
+    if (a.seg.offsets) return a.seg.w_stride % 16 == 0;
+    return a.N >= 4 && a.N <= 512;
+}
+
+namespace {
+
+template <typename T, int NRT, int U>
+hipError_t launch_inst(const ConvArgs &a, hipStream_t st) {
+    const int ctiles = (a.K + kFeat - 1) / kFeat;
+    long long rgs = ((long long)a.N + 32 * NRT - 1) / (32 * NRT);
+    if (a.seg.offsets) rgs += a.seg.num_experts;       // upper bound with expert-aligned row groups
+    const long long blocks = rgs * ctiles;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
+    fc_stream_kernel<T, NRT, U><<<(unsigned)blocks, kThreads, 0, st>>>(a, ctiles);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
+    if (!a.seg.offsets && a.N <= 32) return launch_inst<T, 1, 4>(a, st);
+    if (!a.seg.offsets && a.N <= 64) return launch_inst<T, 2, 2>(a, st);
+    return launch_inst<T, 4, 2>(a, st);
+}
+
+}  // namespace
+
+hipError_t launch_fc_stream(const ConvArgs &a, hipStream_t st) {
+    if (a.in_dtype == MPQ_INT8) return launch_typed<int8_t>(a, st);
+    return launch_typed<_Float16>(a, st);
+}
+
+}  // namespace mpq
