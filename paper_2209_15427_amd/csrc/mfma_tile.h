@@ -350,6 +350,19 @@ struct Tile {
             }
             return;
         }
+        if (a.y_vec16 && m0 + BP <= m_end && ch0 + BC <= pl.Kg) {
+            // a full tile with 16-byte stores: no per-chunk checks (tid = row-in-pass * CH16 + chunk)
+            constexpr int RPP = kThreads / CH16;               // rows per pass
+            const int c16 = tid % CH16, r0 = tid / CH16;
+            char *dst = yb + ((size_t)(m0 + r0) * a.K + (size_t)(g * pl.Kg + ch0 + c16 * CHUNK_ELEMS)) * ES;
+            const size_t dstep = (size_t)RPP * a.K * ES;
+#pragma unroll 8
+            for (int row = r0; row < BP; row += RPP) {
+                *reinterpret_cast<v4i *>(dst) = *reinterpret_cast<const v4i *>(lds + row * ROWB + ((c16 ^ (row & (CH16 - 1))) << 4));
+                dst += dstep;
+            }
+            return;
+        }
 #pragma unroll 4
         for (int idx = tid; idx < BP * CH16; idx += kThreads) {
             const int row = idx / CH16, c16 = idx % CH16;
