@@ -213,6 +213,7 @@ FC_CASES = [  # M, K, N, relu, zx
     (1, 4096, 1000, False, 0), (1, 1024, 4100, True, 0), (5, 800, 500, True, 4), (16, 2048, 2050, True, 0),
     (256, 512, 384, True, 0), (100, 800, 500, True, -6), (64, 500, 10, False, 0), (256, 2304, 4, False, 0),
     (3, 100, 7, False, 2),
+    (130, 1040, 96, True, 3), (40, 256, 36, False, 0), (512, 128, 64, True, 0),     # streamed-weight MFMA kernel: ragged rows / features / axis
 ]
 
 
