@@ -11,9 +11,10 @@
 //      accumulator start values into LDS once,
 //   2. walks a contiguous range of output-row strips (consecutive strips of an image share input
 //      rows and output cache lines: they stay on one CU).  Per strip: the raw N,H,W,3
-//      input rows arrive by direct-to-LDS loads that were issued a strip earlier, and are
-//      expanded in LDS to 4 bytes per pixel, so that every tap run starts 16-byte aligned (the
-//      4th byte meets a zero weight),
+//      input rows arrive by direct-to-LDS loads that were issued behind the previous strip's
+//      reduction (they land while it is requantized and pooled), and are expanded in LDS to
+//      4 bytes per pixel, so that every tap run starts 16-byte aligned (the 4th byte meets a
+//      zero weight),
 //   3. feeds the MFMA B operand straight from that patch -- an output pixel's run for kernel row r
 //      is 48 contiguous bytes at (stride * p + r) * pitch + stride * q * 4 -- and the A operand
 //      from the resident weights (row pitch 33 chunks: odd, hence bank-conflict free), with no
@@ -62,7 +63,7 @@ struct FirstArgs {
     int Kp;               // packed weight row length in bytes
     int pitch;            // bytes per expanded patch row (multiple of 16, > W * 4)
     int max_in_rows;      // input rows a full strip needs
-    unsigned q_magic, qo_magic, kd_magic, w_magic;   // ceil(2^32 / d) for d = Q, Qo, K / 4, W
+    unsigned q_magic, qo_magic, kd_magic, w_magic, g_magic;   // ceil(2^32 / d) for d = Q, Qo, K / 4, W, pitch / 16
     unsigned long long x_bytes;
     size_t wsum_off;
     // LDS layout (bytes)
@@ -77,6 +78,13 @@ __device__ __forceinline__ v4i lds_read16(unsigned addr) {
 }
 __device__ __forceinline__ void lds_wait() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void lds_arrived(v4i &f) { asm volatile("" : "+v"(f)); }
+// A copy of a thread index that the compiler cannot trace back: index arithmetic derived from it stays
+// inside the phase that uses it instead of being hoisted out of the strip loop, where the hoisted
+// values filled the register file and spilled (a spill reload's wait also covers the loads in flight).
+__device__ __forceinline__ int opaque(int v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() carries a fence that also waits
 // for the direct-to-LDS loads in flight, i.e. for the next strip's patch.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
@@ -105,7 +113,6 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
     unsigned char *stage = patch + a.lds_patch + a.lds_extra;  // raw input rows of the next strip
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int frow = lane & 31, fk = lane >> 5;
     const Epi epi = a.epi;
     const int total_strips = a.N * a.strips;
 
@@ -151,8 +158,49 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
     };
     // `stage` -> patch: C bytes per pixel become 4 (rows are contiguous in memory: pixel i of the
     // strip's input sits at raw byte sh16 + i * C); the tail of every patch row is zeroed.
-    auto expand_strip = [&](const Strip &s) {
+    auto expand_strip = [&](const Strip &s, const int tid) {
         const unsigned sh16 = s.start & 15u;
+        if (a.C == 3) {
+            // One item = 4 pixels = 12 raw bytes -> one 16-byte store; the items of a row cover the whole
+            // pitch, pixels past the row's end become zeros.  All of a thread's reads are issued before
+            // its first store (the compiler cannot tell that `stage` and the patch are disjoint).
+            constexpr int EU = 5;
+            const int gpr = a.pitch >> 4;
+            const int total = s.in_rows * gpr;
+            const unsigned lim = sh16 + (unsigned)(s.in_rows * a.W * 3);
+            for (int base = 0; base < total; base += EU * kThreads) {
+                unsigned d[EU][4], sh[EU];
+                int dst[EU], col[EU];
+#pragma unroll
+                for (int k = 0; k < EU; ++k) {
+                    const int it = min(base + k * kThreads + tid, total - 1);     // (a repeat rewrites the same bytes)
+                    const int row = (int)(((unsigned long long)(unsigned)it * a.g_magic) >> 32);
+                    const int g = it - row * gpr;
+                    const unsigned off = min(sh16 + (unsigned)((row * a.W + 4 * g) * 3), lim);
+                    const unsigned *src = reinterpret_cast<const unsigned *>(stage + (off & ~3u));
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) d[k][u] = src[u];
+                    sh[k] = off & 3u;
+                    col[k] = 4 * g;
+                    dst[k] = row * a.pitch + g * 16;
+                }
+#pragma unroll
+                for (int k = 0; k < EU; ++k) {
+                    const unsigned n0 = __builtin_amdgcn_alignbyte(d[k][1], d[k][0], sh[k]);
+                    const unsigned n1 = __builtin_amdgcn_alignbyte(d[k][2], d[k][1], sh[k]);
+                    const unsigned n2 = __builtin_amdgcn_alignbyte(d[k][3], d[k][2], sh[k]);
+                    v4i px;
+                    px[0] = (int)(n0 & 0xffffffu);
+                    px[1] = (int)(__builtin_amdgcn_alignbyte(n1, n0, 3u) & 0xffffffu);
+                    px[2] = (int)(__builtin_amdgcn_alignbyte(n2, n1, 2u) & 0xffffffu);
+                    px[3] = (int)(n2 >> 8);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) px[u] = col[k] + u < a.W ? px[u] : 0;
+                    *reinterpret_cast<v4i *>(patch + dst[k]) = px;
+                }
+            }
+            return;
+        }
         const int total = s.in_rows * a.W;
         const unsigned mask = a.C >= 4 ? 0xffffffffu : ((1u << (8 * a.C)) - 1u);
         for (int i = tid; i < total; i += kThreads) {
@@ -197,7 +245,6 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
     Strip cur = strip_of(sidx);
     request_strip(cur);
 
-    const unsigned wl_addr = (unsigned)(size_t)MPQ_LDS(wl) + (unsigned)(frow * a.Kp);
     const FastRequant fr = make_fast_requant(epi);
     const bool fast = fast_requant_ok(epi);
     const int kd = a.K / 4;                           // dwords per output pixel
@@ -210,20 +257,14 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             for (unsigned b = 0; tail_off + b < a.x_bytes; ++b) stage[tail_lds + b] = src[tail_off + b];
         }
         __syncthreads();                              // ... for everyone; the previous image is consumed
-        expand_strip(cur);
+        expand_strip(cur, opaque(tid));
         lds_barrier();                                // patch complete, `stage` free
-        const int next = sidx + 1;
-        Strip nxt = cur;
-        if (next < s_end) {                           // the next strip's rows arrive behind the arithmetic
-            nxt = strip_of(next);
-            request_strip(nxt);
-        } else {
-            tail_lds = -1;
-        }
 
         // ---- reduction: A from the resident weights, B from the patch ---------------------------
         // (register v of lane l in a 32x32 tile: channel 8*(v/4) + 4*(l/32) + v%4, pixel l%32)
         const int npix = cur.npix;
+        const int ml = opaque(lane), frow = ml & 31, fk = ml >> 5;
+        const unsigned wl_addr = (unsigned)(size_t)MPQ_LDS(wl) + (unsigned)(frow * a.Kp);
         v16i acc[kRowTiles][kColTiles];
         {
             // (asm reads: a compiler-visible LDS load would first wait for the loads in flight)
@@ -316,11 +357,20 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             }
         }
         lds_barrier();                                // everyone is done reading the patch
+        const int next = sidx + 1;
+        Strip nxt = cur;
+        if (next < s_end) {                           // the next strip's rows arrive behind the epilogue
+            nxt = strip_of(next);
+            request_strip(nxt);
+        } else {
+            tail_lds = -1;
+        }
 
         // ---- requantize into the LDS output image [pixel][kOutPitch] --------------------------
         // (channels K..95 of a pixel hold zero-weight results and land in the image's row padding)
         auto requantize = [&](auto fast_tag) {
             constexpr bool FAST = decltype(fast_tag)::value;
+            const int ol = opaque(lane), frow = ol & 31, fk = ol >> 5;
 #pragma unroll
             for (int j = 0; j < kColTiles; ++j) {
                 const int pix = (wave * kColTiles + j) * 32 + frow;
@@ -350,24 +400,42 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
         lds_barrier();
 
         // ---- (pool and) store, channel-contiguous ---------------------------------------------
+        // (a thread's LDS reads for PU items are issued together; items past the end repeat the last one)
         const int total = cur.orows * a.Qo * kd;
-        for (int idx = tid; idx < total; idx += kThreads) {
-            const int op = (int)(((unsigned long long)(unsigned)idx * a.kd_magic) >> 32);
-            const int cd = idx - op * kd;
-            const int orow = (int)(((unsigned long long)(unsigned)op * a.qo_magic) >> 32), oq = op - orow * a.Qo;
-            unsigned v;
-            if (a.pool) {
-                const unsigned char *src = image + ((2 * orow) * a.Q + 2 * oq) * kOutPitch + cd * 4;
-                MaxI8x4 m;
+        int8_t *ystrip = y + ((size_t)cur.n * a.Po + cur.o0) * a.Qo * a.K;        // the strip's rows are contiguous
+        constexpr int PU = 3;
+        const int ptid = opaque(tid);
+        for (int base = 0; base < total; base += PU * kThreads) {
+            unsigned v[PU][9];
 #pragma unroll
-                for (int r = 0; r < 3; ++r)
+            for (int k = 0; k < PU; ++k) {
+                const int idx = min(base + k * kThreads + ptid, total - 1);
+                const int op = (int)(((unsigned long long)(unsigned)idx * a.kd_magic) >> 32);
+                const int cd = idx - op * kd;
+                const int orow = (int)(((unsigned long long)(unsigned)op * a.qo_magic) >> 32), oq = op - orow * a.Qo;
+                if (a.pool) {
+                    const unsigned char *src = image + ((2 * orow) * a.Q + 2 * oq) * kOutPitch + cd * 4;
 #pragma unroll
-                    for (int s = 0; s < 3; ++s) m.add(*reinterpret_cast<const unsigned *>(src + (r * a.Q + s) * kOutPitch));
-                v = m.get();
-            } else {
-                v = *reinterpret_cast<const unsigned *>(image + (orow * a.Q + oq) * kOutPitch + cd * 4);
+                    for (int r = 0; r < 3; ++r)
+#pragma unroll
+                        for (int s = 0; s < 3; ++s)
+                            v[k][r * 3 + s] = *reinterpret_cast<const unsigned *>(src + (r * a.Q + s) * kOutPitch);
+                } else {
+                    v[k][0] = *reinterpret_cast<const unsigned *>(image + (orow * a.Q + oq) * kOutPitch + cd * 4);
+                }
             }
-            *reinterpret_cast<unsigned *>(y + (((size_t)cur.n * a.Po + cur.o0 + orow) * a.Qo + oq) * a.K + cd * 4) = v;
+#pragma unroll
+            for (int k = 0; k < PU; ++k) {
+                const int idx = base + k * kThreads + ptid;
+                unsigned o = v[k][0];
+                if (a.pool) {
+                    MaxI8x4 m;
+#pragma unroll
+                    for (int i = 0; i < 9; ++i) m.add(v[k][i]);
+                    o = m.get();
+                }
+                if (idx < total) *reinterpret_cast<unsigned *>(ystrip + (size_t)idx * 4) = o;
+            }
         }
 
         if (next >= s_end) break;
@@ -413,6 +481,7 @@ hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_
     if (need_px < c.W + 1) need_px = c.W + 1;
     a.pitch = (int)round_up((size_t)need_px * 4, 16);
     if ((a.pitch / 16) % 2 == 0) a.pitch += 16;          // odd number of 16-byte chunks per row
+    a.g_magic = (unsigned)(((1ull << 32) + a.pitch / 16 - 1) / (a.pitch / 16));
     // rows per strip: as many final rows as keep the strip within 512 convolution outputs
     int rps = a.pool ? (kMaxPixels / c.Q - 1) / 2 : kMaxPixels / c.Q;
     if (rps < 1) return hipErrorNotSupported;
