@@ -10,17 +10,18 @@
 //   1. loads the whole packed weight matrix (K <= 96 rows x R * 48 bytes) and the per-channel
 //      accumulator start values into LDS once,
 //   2. walks a contiguous range of output-row strips (consecutive strips of an image share input
-//      rows and output cache lines: they stay on one CU).  Per strip: the raw N,H,W,3
-//      input rows arrive by direct-to-LDS loads that were issued behind the previous strip's
-//      reduction (they land while it is requantized and pooled), and are expanded in LDS to
-//      4 bytes per pixel, so that every tap run starts 16-byte aligned (the 4th byte meets a
-//      zero weight),
+//      rows and output cache lines: they stay on one CU).  Per strip: the raw N,H,W,3 input rows
+//      were loaded into registers a strip earlier (16 bytes = 4 pixels per load) and are expanded
+//      into an LDS patch with 4 bytes per pixel, so that every tap run starts 16-byte aligned
+//      (the 4th byte meets a zero weight),
 //   3. feeds the MFMA B operand straight from that patch -- an output pixel's run for kernel row r
 //      is 48 contiguous bytes at (stride * p + r) * pitch + stride * q * 4 -- and the A operand
 //      from the resident weights (row pitch 33 chunks: odd, hence bank-conflict free), with no
 //      barrier inside the reduction loop,
-//   4. requantizes into an LDS image of the strip's convolution output (it overwrites the
-//      consumed patch), pools it there, and writes only the pooled rows, channel-contiguous.
+//   4. requantizes into an LDS image of the strip's convolution output; that image is pooled and
+//      written out, channel-contiguous, between the reduction steps of the NEXT strip: the
+//      vector work of one wavefront runs while the other wavefront of its SIMD keeps the matrix
+//      pipe busy.  Two barriers per strip.
 // HBM traffic: input once (+ halo rows between strips), pooled output once.
 #include <type_traits>
 
@@ -45,6 +46,7 @@ constexpr int kRowTiles = kMaxK / 32;
 constexpr int kColTiles = 2;           // 32-pixel tiles per wavefront
 constexpr int kMaxPixels = kWaves * kColTiles * 32;   // 512 convolution outputs per strip
 constexpr int kOutPitch = 100;         // bytes per pixel in the LDS output image (25 dwords: odd)
+constexpr int kRawItems = 5;           // 16-byte raw input loads a thread holds in registers per strip
 
 struct FirstArgs {
     const void *x;        // N,H,W,C int8
@@ -67,7 +69,7 @@ struct FirstArgs {
     unsigned long long x_bytes;
     size_t wsum_off;
     // LDS layout (bytes)
-    int lds_w, lds_patch, lds_extra, lds_stage;
+    int lds_w, lds_patch, lds_image;
     Epi epi;
 };
 
@@ -108,9 +110,8 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     unsigned char *wl = lds;                                   // [96][Kp] weights
     int *cst = reinterpret_cast<int *>(lds + a.lds_w);         // [96] accumulator start values
-    unsigned char *patch = lds + a.lds_w + 1024;               // [in_rows][pitch] expanded input, then the
-    unsigned char *image = patch;                              // strip's output image (runs on past it)
-    unsigned char *stage = patch + a.lds_patch + a.lds_extra;  // raw input rows of the next strip
+    unsigned char *patch = lds + a.lds_w + 1024;               // [in_rows][pitch] expanded input of this strip
+    unsigned char *image = patch + a.lds_patch;                // [pixels][kOutPitch] output image of the last strip
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const Epi epi = a.epi;
@@ -138,84 +139,113 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
         return s;
     };
 
-    // Raw input rows of a strip -> `stage` (16 bytes per lane, from the 16-byte boundary below the
-    // first byte).  A 16-byte chunk that straddles the end of the tensor is dropped whole by the
-    // range check: the lane that issued it copies the valid bytes by hand once the loads have landed.
-    unsigned tail_off = 0;
-    int tail_lds = -1;
-    auto request_strip = [&](const Strip &s) {
-        tail_lds = -1;
-        const unsigned sh16 = s.start & 15u, base = s.start - sh16;
-        const int rchunks = (int)((sh16 + (unsigned)(s.in_rows * a.W * a.C) + 15u) / 16u);
-        for (int c = wave * 64; c < rchunks; c += kThreads) {
-            const unsigned o = base + (unsigned)(c + lane) * 16;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrs, MPQ_LDS(stage + c * 16), 16, o, 0, 0, 0);
-            if (o < a.x_bytes && o + 16 > a.x_bytes) {
-                tail_off = o;
-                tail_lds = (c + lane) * 16;
+    // Input item `it` of a strip: 4 pixels (4 C <= 16 raw bytes) of one input row, i.e. one 16-byte
+    // group of the expanded patch; the items of a row cover the whole pitch.  A thread owns items
+    // tid, tid + 512, ... (at most kRawItems: the host sizes the strips for that); indices past the
+    // strip's last item repeat it.
+    auto item_geom = [&](const Strip &s, int k, int t, int &row, int &g, unsigned &off) {
+        const int gpr = a.pitch >> 4;
+        const int it = min(k * kThreads + t, s.in_rows * gpr - 1);
+        row = (int)(((unsigned long long)(unsigned)it * a.g_magic) >> 32);
+        g = it - row * gpr;
+        off = s.start + (unsigned)((row * a.W + 4 * g) * a.C);              // (rows are contiguous in memory)
+    };
+    // Raw input of a strip -> registers: one 16-byte load per item from the 4-byte boundary below
+    // its first byte, issued a strip ahead and consumed by expand().  Bytes past the end of the
+    // tensor read as zero; a load that straddles the end may be dropped whole by the range check,
+    // so the (at most one) lane that has it fetches the valid bytes one by one.
+    auto load_raw = [&](const Strip &s, v4i(&raw)[kRawItems]) {
+        const int t = opaque(tid);
+#pragma unroll
+        for (int k = 0; k < kRawItems; ++k) {
+            int row, g;
+            unsigned off;
+            item_geom(s, k, t, row, g, off);
+            const unsigned base4 = off & ~3u;
+            v4i d = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(xrs, (int)base4, 0, 0));
+            if (base4 < a.x_bytes && base4 + 16 > a.x_bytes) {
+                unsigned w4[4] = {0u, 0u, 0u, 0u};
+                const unsigned char *src = (const unsigned char *)a.x;
+#pragma unroll
+                for (int b = 0; b < 16; ++b)
+                    if (base4 + b < a.x_bytes) w4[b >> 2] |= (unsigned)src[base4 + b] << (8 * (b & 3));
+                d = v4i{(int)w4[0], (int)w4[1], (int)w4[2], (int)w4[3]};
             }
+            raw[k] = d;
         }
     };
-    // `stage` -> patch: C bytes per pixel become 4 (rows are contiguous in memory: pixel i of the
-    // strip's input sits at raw byte sh16 + i * C); the tail of every patch row is zeroed.
-    auto expand_strip = [&](const Strip &s, const int tid) {
-        const unsigned sh16 = s.start & 15u;
-        if (a.C == 3) {
-            // One item = 4 pixels = 12 raw bytes -> one 16-byte store; the items of a row cover the whole
-            // pitch, pixels past the row's end become zeros.  All of a thread's reads are issued before
-            // its first store (the compiler cannot tell that `stage` and the patch are disjoint).
-            constexpr int EU = 5;
-            const int gpr = a.pitch >> 4;
-            const int total = s.in_rows * gpr;
-            const unsigned lim = sh16 + (unsigned)(s.in_rows * a.W * 3);
-            for (int base = 0; base < total; base += EU * kThreads) {
-                unsigned d[EU][4], sh[EU];
-                int dst[EU], col[EU];
+    // registers -> patch: C bytes per pixel become 4 (the 4th .. meet zero weights), pixels past
+    // the row's end become zeros, one 16-byte store per item.
+    auto expand = [&](const Strip &s, v4i(&raw)[kRawItems]) {
+        const int t = opaque(tid);
 #pragma unroll
-                for (int k = 0; k < EU; ++k) {
-                    const int it = min(base + k * kThreads + tid, total - 1);     // (a repeat rewrites the same bytes)
-                    const int row = (int)(((unsigned long long)(unsigned)it * a.g_magic) >> 32);
-                    const int g = it - row * gpr;
-                    const unsigned off = min(sh16 + (unsigned)((row * a.W + 4 * g) * 3), lim);
-                    const unsigned *src = reinterpret_cast<const unsigned *>(stage + (off & ~3u));
+        for (int k = 0; k < kRawItems; ++k) {
+            int row, g;
+            unsigned off;
+            item_geom(s, k, t, row, g, off);
+            const unsigned sh = off & 3u;
+            const unsigned d0 = (unsigned)raw[k][0], d1 = (unsigned)raw[k][1], d2 = (unsigned)raw[k][2],
+                           d3 = (unsigned)raw[k][3];
+            const unsigned n0 = __builtin_amdgcn_alignbyte(d1, d0, sh);
+            const unsigned n1 = __builtin_amdgcn_alignbyte(d2, d1, sh);
+            const unsigned n2 = __builtin_amdgcn_alignbyte(d3, d2, sh);
+            v4i px;
+            if (a.C == 3) {
+                px[0] = (int)(n0 & 0xffffffu);
+                px[1] = (int)(__builtin_amdgcn_alignbyte(n1, n0, 3u) & 0xffffffu);
+                px[2] = (int)(__builtin_amdgcn_alignbyte(n2, n1, 2u) & 0xffffffu);
+                px[3] = (int)(n2 >> 8);
+            } else if (a.C == 1) {
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) d[k][u] = src[u];
-                    sh[k] = off & 3u;
-                    col[k] = 4 * g;
-                    dst[k] = row * a.pitch + g * 16;
-                }
-#pragma unroll
-                for (int k = 0; k < EU; ++k) {
-                    const unsigned n0 = __builtin_amdgcn_alignbyte(d[k][1], d[k][0], sh[k]);
-                    const unsigned n1 = __builtin_amdgcn_alignbyte(d[k][2], d[k][1], sh[k]);
-                    const unsigned n2 = __builtin_amdgcn_alignbyte(d[k][3], d[k][2], sh[k]);
-                    v4i px;
-                    px[0] = (int)(n0 & 0xffffffu);
-                    px[1] = (int)(__builtin_amdgcn_alignbyte(n1, n0, 3u) & 0xffffffu);
-                    px[2] = (int)(__builtin_amdgcn_alignbyte(n2, n1, 2u) & 0xffffffu);
-                    px[3] = (int)(n2 >> 8);
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) px[u] = col[k] + u < a.W ? px[u] : 0;
-                    *reinterpret_cast<v4i *>(patch + dst[k]) = px;
-                }
+                for (int u = 0; u < 4; ++u) px[u] = (int)((n0 >> (8 * u)) & 0xffu);
+            } else if (a.C == 2) {
+                px[0] = (int)(n0 & 0xffffu);
+                px[1] = (int)(n0 >> 16);
+                px[2] = (int)(n1 & 0xffffu);
+                px[3] = (int)(n1 >> 16);
+            } else {                                   // C == 4: item offsets are multiples of 16
+                px = raw[k];
             }
-            return;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) px[u] = 4 * g + u < a.W ? px[u] : 0;
+            *reinterpret_cast<v4i *>(patch + row * a.pitch + g * 16) = px;
         }
-        const int total = s.in_rows * a.W;
-        const unsigned mask = a.C >= 4 ? 0xffffffffu : ((1u << (8 * a.C)) - 1u);
-        for (int i = tid; i < total; i += kThreads) {
-            const int row = (int)(((unsigned long long)(unsigned)i * a.w_magic) >> 32);
-            const int col = i - row * a.W;
-            const unsigned off = sh16 + (unsigned)(i * a.C);
-            const unsigned lo = *reinterpret_cast<const unsigned *>(stage + (off & ~3u));
-            const unsigned hi = *reinterpret_cast<const unsigned *>(stage + (off & ~3u) + 4);
-            const unsigned v = __builtin_amdgcn_alignbyte(hi, lo, off & 3u) & mask;
-            *reinterpret_cast<unsigned *>(patch + row * a.pitch + col * 4) = v;
-        }
-        const int padw = a.pitch / 4 - a.W;
-        for (int i = tid; i < s.in_rows * padw; i += kThreads)
-            *reinterpret_cast<unsigned *>(patch + (i / padw) * a.pitch + (a.W + i % padw) * 4) = 0u;
     };
+
+    const int kd = a.K / 4;                           // dwords per output pixel
+    int8_t *y = (int8_t *)a.y;
+    // Output items k0 .. k1 - 1 of this thread for strip ps (item = 4 channels of one final pixel):
+    // (pool and) store, channel-contiguous, from the LDS image.  The strip's output rows are
+    // contiguous in memory.
+    auto pool_items = [&](const Strip &ps, int k0, int k1, int ptid) {
+        const int total = ps.orows * a.Qo * kd;
+        int8_t *ystrip = y + ((size_t)ps.n * a.Po + ps.o0) * a.Qo * a.K;
+        for (int k = k0; k < k1; ++k) {
+            const int idx = k * kThreads + ptid;
+            const int idc = min(idx, total - 1);
+            const int op = (int)(((unsigned long long)(unsigned)idc * a.kd_magic) >> 32);
+            const int cd = idc - op * kd;
+            const int orow = (int)(((unsigned long long)(unsigned)op * a.qo_magic) >> 32), oq = op - orow * a.Qo;
+            unsigned o;
+            if (a.pool) {
+                const unsigned char *src = image + ((2 * orow) * a.Q + 2 * oq) * kOutPitch + cd * 4;
+                unsigned v[9];
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int s = 0; s < 3; ++s)
+                        v[r * 3 + s] = *reinterpret_cast<const unsigned *>(src + (r * a.Q + s) * kOutPitch);
+                MaxI8x4 m;
+#pragma unroll
+                for (int i = 0; i < 9; ++i) m.add(v[i]);
+                o = m.get();
+            } else {
+                o = *reinterpret_cast<const unsigned *>(image + (orow * a.Q + oq) * kOutPitch + cd * 4);
+            }
+            if (idx < total) *reinterpret_cast<unsigned *>(ystrip + (size_t)idx * 4) = o;
+        }
+    };
+    auto pool_item_count = [&](const Strip &ps) { return (ps.orows * a.Qo * kd + kThreads - 1) / kThreads; };
 
     // ---- once per workgroup: weights and accumulator start values ----------------------------------
     {
@@ -242,32 +272,38 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
         __builtin_amdgcn_s_waitcnt(0);
         return;
     }
-    Strip cur = strip_of(sidx);
-    request_strip(cur);
+    Strip cur = strip_of(sidx), prv = cur;
+    int prv_items = 0;                                // output items per thread still owed for strip prv
+    v4i raw[kRawItems];
+    load_raw(cur, raw);
+    __builtin_amdgcn_s_waitcnt(0);                    // the weights have landed (this wavefront's share)
 
     const FastRequant fr = make_fast_requant(epi);
     const bool fast = fast_requant_ok(epi);
-    const int kd = a.K / 4;                           // dwords per output pixel
-    int8_t *y = (int8_t *)a.y;
 
+    // Per strip: expand | barrier | reduction, with the previous strip's pool-and-store items worked
+    // off between its steps (they read the image, the reduction reads the patch; the two wavefronts
+    // of a SIMD overlap one's vector work with the other's matrix work) | barrier | requantize into
+    // the image.  The next strip's raw rows are in flight from the first barrier on.
     for (;;) {
-        __builtin_amdgcn_s_waitcnt(0);                // this strip's raw rows (and the weights) have landed
-        if (tail_lds >= 0) {
-            const unsigned char *src = (const unsigned char *)a.x;
-            for (unsigned b = 0; tail_off + b < a.x_bytes; ++b) stage[tail_lds + b] = src[tail_off + b];
+        expand(cur, raw);
+        lds_barrier();                                // patch complete (and, before it, the image of strip prv)
+        const int next = sidx + 1;
+        Strip nxt = cur;
+        if (next < s_end) {
+            nxt = strip_of(next);
+            load_raw(nxt, raw);
         }
-        __syncthreads();                              // ... for everyone; the previous image is consumed
-        expand_strip(cur, opaque(tid));
-        lds_barrier();                                // patch complete, `stage` free
 
         // ---- reduction: A from the resident weights, B from the patch ---------------------------
         // (register v of lane l in a 32x32 tile: channel 8*(v/4) + 4*(l/32) + v%4, pixel l%32)
         const int npix = cur.npix;
         const int ml = opaque(lane), frow = ml & 31, fk = ml >> 5;
+        const int ptid = opaque(tid);
         const unsigned wl_addr = (unsigned)(size_t)MPQ_LDS(wl) + (unsigned)(frow * a.Kp);
         v16i acc[kRowTiles][kColTiles];
         {
-            // (asm reads: a compiler-visible LDS load would first wait for the loads in flight)
+            // (asm reads: kept apart from the compiler's own bookkeeping of LDS traffic)
             v4i b4[kRowTiles][4];
 #pragma unroll
             for (int i = 0; i < kRowTiles; ++i)
@@ -298,6 +334,7 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             const int py = (int)(((unsigned long long)(unsigned)pix * a.q_magic) >> 32), px = pix - py * a.Q;
             bbase[j] = patch_addr + (unsigned)(py * a.stride * a.pitch + px * a.stride * 4);
         }
+        int pdone = 0;                                // output items of strip prv already worked off
         if (tile_live[0]) {      // uniform per wavefront: tiles are assigned in order
             // A step multiplies chunks 2 ks and 2 ks + 1 (lane halves fk = 0, 1) of the R * cpt chunks
             // of a weight row; this lane's chunk kc = 2 ks + fk is chunk kj of kernel row kr.  The
@@ -320,7 +357,8 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
                 kj -= wrap ? a.cpt : 0;
                 boff += wrap ? wrap_add : 32u;
             };
-            // YOUNGER: a fetch issued after this set's is still in flight (LDS reads return in order)
+            // YOUNGER: a fetch issued after this set's is still in flight (LDS reads return in order;
+            // reads the compiler issued in between only make the wait stricter)
             auto multiply = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles], auto tail_tag, auto younger_tag) {
                 if constexpr (decltype(younger_tag)::value) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(kRowTiles + kColTiles));
                 else asm volatile("s_waitcnt lgkmcnt(0)");
@@ -343,6 +381,10 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             for (int p = 0; p < (full >> 1); ++p) {
                 fetch(af[1], bf[1]);
                 multiply(af[0], bf[0], std::false_type{}, std::true_type{});
+                if (pdone < prv_items) {               // one output item of the previous strip per pair of steps
+                    pool_items(prv, pdone, pdone + 1, ptid);
+                    ++pdone;
+                }
                 fetch(af[0], bf[0]);
                 multiply(af[1], bf[1], std::false_type{}, std::true_type{});
             }
@@ -356,15 +398,8 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
                 else lds_wait();
             }
         }
-        lds_barrier();                                // everyone is done reading the patch
-        const int next = sidx + 1;
-        Strip nxt = cur;
-        if (next < s_end) {                           // the next strip's rows arrive behind the epilogue
-            nxt = strip_of(next);
-            request_strip(nxt);
-        } else {
-            tail_lds = -1;
-        }
+        pool_items(prv, pdone, prv_items, ptid);      // what the steps did not cover (all of it for an idle wavefront)
+        lds_barrier();                                // everyone is done with the patch and with the old image
 
         // ---- requantize into the LDS output image [pixel][kOutPitch] --------------------------
         // (channels K..95 of a pixel hold zero-weight results and land in the image's row padding)
@@ -397,51 +432,16 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
         };
         if (fast) requantize(std::true_type{});
         else requantize(std::false_type{});
-        lds_barrier();
+        // (no barrier here: the image is next read behind the barrier that follows the next expand)
 
-        // ---- (pool and) store, channel-contiguous ---------------------------------------------
-        // (a thread's LDS reads for PU items are issued together; items past the end repeat the last one)
-        const int total = cur.orows * a.Qo * kd;
-        int8_t *ystrip = y + ((size_t)cur.n * a.Po + cur.o0) * a.Qo * a.K;        // the strip's rows are contiguous
-        constexpr int PU = 3;
-        const int ptid = opaque(tid);
-        for (int base = 0; base < total; base += PU * kThreads) {
-            unsigned v[PU][9];
-#pragma unroll
-            for (int k = 0; k < PU; ++k) {
-                const int idx = min(base + k * kThreads + ptid, total - 1);
-                const int op = (int)(((unsigned long long)(unsigned)idx * a.kd_magic) >> 32);
-                const int cd = idx - op * kd;
-                const int orow = (int)(((unsigned long long)(unsigned)op * a.qo_magic) >> 32), oq = op - orow * a.Qo;
-                if (a.pool) {
-                    const unsigned char *src = image + ((2 * orow) * a.Q + 2 * oq) * kOutPitch + cd * 4;
-#pragma unroll
-                    for (int r = 0; r < 3; ++r)
-#pragma unroll
-                        for (int s = 0; s < 3; ++s)
-                            v[k][r * 3 + s] = *reinterpret_cast<const unsigned *>(src + (r * a.Q + s) * kOutPitch);
-                } else {
-                    v[k][0] = *reinterpret_cast<const unsigned *>(image + (orow * a.Q + oq) * kOutPitch + cd * 4);
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < PU; ++k) {
-                const int idx = base + k * kThreads + ptid;
-                unsigned o = v[k][0];
-                if (a.pool) {
-                    MaxI8x4 m;
-#pragma unroll
-                    for (int i = 0; i < 9; ++i) m.add(v[k][i]);
-                    o = m.get();
-                }
-                if (idx < total) *reinterpret_cast<unsigned *>(ystrip + (size_t)idx * 4) = o;
-            }
-        }
-
+        prv = cur;
+        prv_items = pool_item_count(cur);
         if (next >= s_end) break;
         sidx = next;
         cur = nxt;
     }
+    lds_barrier();                                    // the last strip's image is complete
+    pool_items(prv, 0, prv_items, opaque(tid));
 }
 
 }  // namespace
@@ -482,7 +482,8 @@ hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_
     a.pitch = (int)round_up((size_t)need_px * 4, 16);
     if ((a.pitch / 16) % 2 == 0) a.pitch += 16;          // odd number of 16-byte chunks per row
     a.g_magic = (unsigned)(((1ull << 32) + a.pitch / 16 - 1) / (a.pitch / 16));
-    // rows per strip: as many final rows as keep the strip within 512 convolution outputs
+    // rows per strip: as many final rows as keep the strip within 512 convolution outputs, its
+    // raw input within kRawItems loads per thread, and weights + patch + image within the LDS
     int rps = a.pool ? (kMaxPixels / c.Q - 1) / 2 : kMaxPixels / c.Q;
     if (rps < 1) return hipErrorNotSupported;
     if (rps > Po) rps = Po;
@@ -490,18 +491,15 @@ hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_
         if (rps < 1) return hipErrorNotSupported;
         const int crows = a.pool ? 2 * rps + 1 : rps;
         a.max_in_rows = (crows - 1) * a.stride + c.R;
+        if ((long long)a.max_in_rows * (a.pitch / 16) > (long long)kRawItems * kThreads) continue;
         a.lds_w = (int)round_up((size_t)kMaxK * a.Kp + 16, 1024);
         a.lds_patch = (int)round_up((size_t)a.max_in_rows * a.pitch + 64, 1024);
-        // the output image of a strip overwrites the strip's consumed patch and may run on past it
-        const size_t img = (size_t)crows * c.Q * kOutPitch + 16;
-        a.lds_extra = img > (size_t)a.lds_patch ? (int)round_up(img - a.lds_patch, 1024) : 0;
-        // + 1 KiB: the last wavefront-wide raw copy may run up to 63 chunks past the data
-        a.lds_stage = (int)round_up((size_t)a.max_in_rows * c.W * c.C + 64 + 1024, 1024);
-        if (a.lds_w + 1024 + a.lds_patch + a.lds_extra + a.lds_stage <= 160 * 1024) break;
+        a.lds_image = (int)round_up((size_t)crows * c.Q * kOutPitch + 16, 1024);
+        if (a.lds_w + 1024 + a.lds_patch + a.lds_image <= 160 * 1024) break;
     }
     a.rows_per_strip = rps;
     a.strips = (Po + rps - 1) / rps;
-    const size_t lds_bytes = (size_t)a.lds_w + 1024 + (size_t)a.lds_patch + a.lds_extra + a.lds_stage;
+    const size_t lds_bytes = (size_t)a.lds_w + 1024 + (size_t)a.lds_patch + a.lds_image;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)conv_first_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -140,6 +140,11 @@ CONV_CASES = [
     (3, 128, 13, 13, 400, 3, 3, 1, 1, 2, True, (3, 2), 0, 0, 0),       # image-aligned tiles, pool in the epilogue, ragged channels (200 per group)
     (2, 64, 12, 14, 128, 3, 3, 1, 1, 1, True, (3, 2), 0, 0, -7),       # image-aligned, non-square image, z_y != 0
     (2, 64, 12, 14, 128, 3, 3, 1, 1, 1, False, (3, 2), 0, 0, 0),       # image-aligned + pool without ReLU (general requantize)
+    (3, 1, 21, 23, 24, 5, 7, 4, 0, 1, True, (0, 0), 0, 0, 0),          # row path, C = 1, tensor size not a multiple of 4
+    (1, 2, 19, 27, 16, 4, 6, 4, 0, 1, True, (3, 2), 0, 0, 0),          # row path, C = 2, fused pool on a 4 x 6 output
+    (2, 4, 20, 20, 32, 8, 8, 4, 0, 1, False, (0, 0), 3, 0, -2),        # row path, C = 4, general requantize
+    (1, 3, 15, 15, 8, 7, 7, 4, 0, 1, True, (0, 0), 0, 0, 0),           # row path, one short strip, 675-byte tensor
+    (5, 3, 67, 51, 64, 11, 11, 4, 0, 1, True, (3, 2), 0, 0, 0),        # row path, several strips per image, ragged last strip
 ]
 
 
