@@ -63,6 +63,7 @@ struct FirstArgs {
     int strips;           // per image
     int cpt, nchunks;     // chunks per kernel row (3), R * cpt
     int Kp;               // packed weight row length in bytes
+    int Kl;               // weight row pitch in LDS: the row, zeros up to a whole number of step triples, odd chunk count
     int pitch;            // bytes per expanded patch row (multiple of 16, > W * 4)
     int max_in_rows;      // input rows a full strip needs
     unsigned q_magic, qo_magic, kd_magic, w_magic, g_magic;   // ceil(2^32 / d) for d = Q, Qo, K / 4, W, pitch / 16
@@ -141,29 +142,34 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
 
     // Input item `it` of a strip: 4 pixels (4 C <= 16 raw bytes) of one input row, i.e. one 16-byte
     // group of the expanded patch; the items of a row cover the whole pitch.  A thread owns items
-    // tid, tid + 512, ... (at most kRawItems: the host sizes the strips for that); indices past the
-    // strip's last item repeat it.
-    auto item_geom = [&](const Strip &s, int k, int t, int &row, int &g, unsigned &off) {
+    // tid, tid + 512, ... (at most kRawItems: the host sizes the strips for that).  Their place in
+    // the patch (e_dst) and in the strip's raw bytes (e_rel; rows are contiguous in memory) is the
+    // same for every strip; items past a short strip's last row move bytes nobody reads.
+    int e_dst[kRawItems];
+    unsigned e_rel[kRawItems];
+    {
         const int gpr = a.pitch >> 4;
-        const int it = min(k * kThreads + t, s.in_rows * gpr - 1);
-        row = (int)(((unsigned long long)(unsigned)it * a.g_magic) >> 32);
-        g = it - row * gpr;
-        off = s.start + (unsigned)((row * a.W + 4 * g) * a.C);              // (rows are contiguous in memory)
-    };
+#pragma unroll
+        for (int k = 0; k < kRawItems; ++k) {
+            const int it = min(k * kThreads + tid, a.max_in_rows * gpr - 1);
+            const int row = (int)(((unsigned long long)(unsigned)it * a.g_magic) >> 32);
+            const int g = it - row * gpr;
+            e_dst[k] = row * a.pitch + g * 16;
+            e_rel[k] = (unsigned)((row * a.W + 4 * g) * a.C);
+        }
+    }
     // Raw input of a strip -> registers: one 16-byte load per item from the 4-byte boundary below
     // its first byte, issued a strip ahead and consumed by expand().  Bytes past the end of the
     // tensor read as zero; a load that straddles the end may be dropped whole by the range check,
     // so the (at most one) lane that has it fetches the valid bytes one by one.
     auto load_raw = [&](const Strip &s, v4i(&raw)[kRawItems]) {
-        const int t = opaque(tid);
+        // (uniform: only the last strips of the tensor can reach its end)
+        const bool near_end = (unsigned long long)s.start + (unsigned)(a.max_in_rows * (a.pitch >> 2) * a.C) + 32u > a.x_bytes;
 #pragma unroll
         for (int k = 0; k < kRawItems; ++k) {
-            int row, g;
-            unsigned off;
-            item_geom(s, k, t, row, g, off);
-            const unsigned base4 = off & ~3u;
+            const unsigned base4 = (s.start + e_rel[k]) & ~3u;
             v4i d = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(xrs, (int)base4, 0, 0));
-            if (base4 < a.x_bytes && base4 + 16 > a.x_bytes) {
+            if (near_end && base4 < a.x_bytes && base4 + 16 > a.x_bytes) {
                 unsigned w4[4] = {0u, 0u, 0u, 0u};
                 const unsigned char *src = (const unsigned char *)a.x;
 #pragma unroll
@@ -174,61 +180,72 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             raw[k] = d;
         }
     };
-    // registers -> patch: C bytes per pixel become 4 (the 4th .. meet zero weights), pixels past
-    // the row's end become zeros, one 16-byte store per item.
-    auto expand = [&](const Strip &s, v4i(&raw)[kRawItems]) {
-        const int t = opaque(tid);
+    // registers -> patch: pixel u of an item goes to bytes 4 u .. 4 u + 3, one 16-byte store per
+    // item.  Only the C low bytes of a pixel, and only pixels inside the row, ever meet a non-zero
+    // weight (the packed rows hold zeros for channels C..3 and for taps past the kernel's
+    // width), so the remaining bytes are left as they fall: the next pixel's, or the next row's.
+    auto expand_c = [&](const Strip &s, v4i(&raw)[kRawItems], auto c_tag) {
+        constexpr int C = decltype(c_tag)::value;
 #pragma unroll
         for (int k = 0; k < kRawItems; ++k) {
-            int row, g;
-            unsigned off;
-            item_geom(s, k, t, row, g, off);
-            const unsigned sh = off & 3u;
+            const unsigned sh = (s.start + e_rel[k]) & 3u;
             const unsigned d0 = (unsigned)raw[k][0], d1 = (unsigned)raw[k][1], d2 = (unsigned)raw[k][2],
                            d3 = (unsigned)raw[k][3];
             const unsigned n0 = __builtin_amdgcn_alignbyte(d1, d0, sh);
             const unsigned n1 = __builtin_amdgcn_alignbyte(d2, d1, sh);
             const unsigned n2 = __builtin_amdgcn_alignbyte(d3, d2, sh);
             v4i px;
-            if (a.C == 3) {
-                px[0] = (int)(n0 & 0xffffffu);
-                px[1] = (int)(__builtin_amdgcn_alignbyte(n1, n0, 3u) & 0xffffffu);
-                px[2] = (int)(__builtin_amdgcn_alignbyte(n2, n1, 2u) & 0xffffffu);
-                px[3] = (int)(n2 >> 8);
-            } else if (a.C == 1) {
-#pragma unroll
-                for (int u = 0; u < 4; ++u) px[u] = (int)((n0 >> (8 * u)) & 0xffu);
-            } else if (a.C == 2) {
-                px[0] = (int)(n0 & 0xffffu);
-                px[1] = (int)(n0 >> 16);
-                px[2] = (int)(n1 & 0xffffu);
-                px[3] = (int)(n1 >> 16);
-            } else {                                   // C == 4: item offsets are multiples of 16
-                px = raw[k];
+            if constexpr (C == 3) {
+                px = v4i{(int)n0, (int)__builtin_amdgcn_alignbyte(n1, n0, 3u), (int)__builtin_amdgcn_alignbyte(n2, n1, 2u),
+                         (int)(n2 >> 8)};
+            } else if constexpr (C == 1) {
+                px = v4i{(int)n0, (int)(n0 >> 8), (int)(n0 >> 16), (int)(n0 >> 24)};
+            } else if constexpr (C == 2) {
+                px = v4i{(int)n0, (int)(n0 >> 16), (int)n1, (int)(n1 >> 16)};
+            } else {                                   // C == 4: item offsets are multiples of 4
+                px = v4i{(int)n0, (int)n1, (int)n2, (int)d3};
             }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) px[u] = 4 * g + u < a.W ? px[u] : 0;
-            *reinterpret_cast<v4i *>(patch + row * a.pitch + g * 16) = px;
+            *reinterpret_cast<v4i *>(patch + e_dst[k]) = px;
         }
+    };
+    auto expand = [&](const Strip &s, v4i(&raw)[kRawItems]) {
+        if (a.C == 3) expand_c(s, raw, std::integral_constant<int, 3>{});
+        else if (a.C == 1) expand_c(s, raw, std::integral_constant<int, 1>{});
+        else if (a.C == 2) expand_c(s, raw, std::integral_constant<int, 2>{});
+        else expand_c(s, raw, std::integral_constant<int, 4>{});
     };
 
     const int kd = a.K / 4;                           // dwords per output pixel
     int8_t *y = (int8_t *)a.y;
-    // Output items k0 .. k1 - 1 of this thread for strip ps (item = 4 channels of one final pixel):
-    // (pool and) store, channel-contiguous, from the LDS image.  The strip's output rows are
-    // contiguous in memory.
-    auto pool_items = [&](const Strip &ps, int k0, int k1, int ptid) {
+    // Output item idx = k * 512 + tid of a strip: 4 channels (dword cd) of final pixel (orow, oq),
+    // idx = (orow * Qo + oq) * kd + cd.  A thread walks its items in order, so the position
+    // advances by a fixed step with two carries instead of being divided out per item.
+    struct OutPos {
+        int cd, oq, orow;
+    };
+    OutPos out_first;
+    {
+        const int op = (int)(((unsigned long long)(unsigned)tid * a.kd_magic) >> 32);
+        out_first.cd = tid - op * kd;
+        out_first.orow = (int)(((unsigned long long)(unsigned)op * a.qo_magic) >> 32);
+        out_first.oq = op - out_first.orow * a.Qo;
+    }
+    const int step_op = kThreads / kd, step_cd = kThreads - step_op * kd;
+    const int step_orow = step_op / a.Qo, step_oq = step_op - step_orow * a.Qo;
+    // Items k0 .. k1 - 1 of this thread for strip ps (pos: the position of item k0, advanced on
+    // return): (pool and) store, channel-contiguous, from the LDS image.  The strip's output rows
+    // are contiguous in memory.  An item past the strip's last reads item 0's place and stores nothing.
+    auto pool_items = [&](const Strip &ps, int k0, int k1, int ptid, OutPos &pos) {
         const int total = ps.orows * a.Qo * kd;
         int8_t *ystrip = y + ((size_t)ps.n * a.Po + ps.o0) * a.Qo * a.K;
         for (int k = k0; k < k1; ++k) {
             const int idx = k * kThreads + ptid;
-            const int idc = min(idx, total - 1);
-            const int op = (int)(((unsigned long long)(unsigned)idc * a.kd_magic) >> 32);
-            const int cd = idc - op * kd;
-            const int orow = (int)(((unsigned long long)(unsigned)op * a.qo_magic) >> 32), oq = op - orow * a.Qo;
+            const bool live = idx < total;
+            const int cd = live ? pos.cd : out_first.cd, oq = live ? pos.oq : out_first.oq,
+                      orow = live ? pos.orow : out_first.orow;
             unsigned o;
             if (a.pool) {
-                const unsigned char *src = image + ((2 * orow) * a.Q + 2 * oq) * kOutPitch + cd * 4;
+                const unsigned char *src = image + __umul24(__umul24(2 * orow, a.Q) + 2 * oq, kOutPitch) + cd * 4;
                 unsigned v[9];
 #pragma unroll
                 for (int r = 0; r < 3; ++r)
@@ -240,9 +257,16 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
                 for (int i = 0; i < 9; ++i) m.add(v[i]);
                 o = m.get();
             } else {
-                o = *reinterpret_cast<const unsigned *>(image + (orow * a.Q + oq) * kOutPitch + cd * 4);
+                o = *reinterpret_cast<const unsigned *>(image + __umul24(__umul24(orow, a.Q) + oq, kOutPitch) + cd * 4);
             }
-            if (idx < total) *reinterpret_cast<unsigned *>(ystrip + (size_t)idx * 4) = o;
+            if (live) *reinterpret_cast<unsigned *>(ystrip + (size_t)idx * 4) = o;
+            pos.cd += step_cd;
+            const int c1 = pos.cd >= kd;
+            pos.cd -= c1 ? kd : 0;
+            pos.oq += step_oq + c1;
+            const int c2 = pos.oq >= a.Qo;
+            pos.oq -= c2 ? a.Qo : 0;
+            pos.orow += step_orow + c2;
         }
     };
     auto pool_item_count = [&](const Strip &ps) { return (ps.orows * a.Qo * kd + kThreads - 1) / kThreads; };
@@ -251,9 +275,13 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
     {
         const __amdgpu_buffer_rsrc_t wrs =
             __builtin_amdgcn_make_buffer_rsrc((void *)a.w, (short)0, a.K * a.Kp, 0x00020000);
-        const int wchunks = kMaxK * a.Kp / 16;
-        for (int c = wave * 64; c < wchunks; c += kThreads)      // rows >= K read past the buffer: zeros
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MPQ_LDS(wl + c * 16), 16, (c + lane) * 16, 0, 0, 0);
+        const int cpr = a.Kl / 16, wchunks = kMaxK * cpr;          // chunks per LDS row
+        for (int c = wave * 64; c < wchunks; c += kThreads) {
+            // chunks past the packed row (and rows >= K) are pointed past the buffer: zeros
+            const int r = (c + lane) / cpr, cc = (c + lane) - r * cpr;
+            const unsigned off = cc * 16 < a.Kp ? (unsigned)(r * a.Kp + cc * 16) : 0x7ffffff0u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wrs, MPQ_LDS(wl + c * 16), 16, off, 0, 0, 0);
+        }
         // bias - z_x * sum(w): the epilogue's per-channel constant of the expanded form
         if (tid < kMaxK) {
             int v = 0;
@@ -300,7 +328,7 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
         const int npix = cur.npix;
         const int ml = opaque(lane), frow = ml & 31, fk = ml >> 5;
         const int ptid = opaque(tid);
-        const unsigned wl_addr = (unsigned)(size_t)MPQ_LDS(wl) + (unsigned)(frow * a.Kp);
+        const unsigned wl_addr = (unsigned)(size_t)MPQ_LDS(wl) + (unsigned)(frow * a.Kl);
         v16i acc[kRowTiles][kColTiles];
         {
             // (asm reads: kept apart from the compiler's own bookkeeping of LDS traffic)
@@ -335,20 +363,26 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             bbase[j] = patch_addr + (unsigned)(py * a.stride * a.pitch + px * a.stride * 4);
         }
         int pdone = 0;                                // output items of strip prv already worked off
+        OutPos ppos = out_first;
         if (tile_live[0]) {      // uniform per wavefront: tiles are assigned in order
-            // A step multiplies chunks 2 ks and 2 ks + 1 (lane halves fk = 0, 1) of the R * cpt chunks
-            // of a weight row; this lane's chunk kc = 2 ks + fk is chunk kj of kernel row kr.  The
-            // offsets advance without branches, the steps come in pairs (fragment sets 0 and 1, the
-            // next step's fragments requested before this step is multiplied), and an odd chunk
-            // count leaves a last half step in which the fk = 1 lanes contribute nothing.
-            const int full = a.nchunks >> 1, tail = a.nchunks & 1;
+            // A step multiplies chunks 2 ks and 2 ks + 1 (lane halves fk = 0, 1) of a weight row; this
+            // lane's chunk kc = 2 ks + fk is chunk kj of kernel row kr.  The offsets advance without
+            // branches.  Three fragment sets rotate, each requested two steps before it is
+            // multiplied: one step of matrix work does not cover the LDS latency, and a wavefront
+            // that runs alone (its SIMD partner is at the barrier or in vector work) would wait on
+            // every step.  The weight rows in LDS are zero-filled up to a whole number of step
+            // triples, so the loop needs no odd or half step (those left the accumulators in
+            // different registers per path, i.e. dozens of copies behind the last matrix
+            // instructions); the patch bytes that meet the zero weights are whatever follows the
+            // pixel's last run in LDS.
+            const int triples = (a.nchunks + 5) / 6;
             const unsigned wrap_add = (unsigned)(a.pitch - a.cpt * 16 + 32);
             int kj = fk;                               // fk < cpt
             unsigned aoff = (unsigned)(fk * 16), boff = (unsigned)(fk * 16);
-            v4i af[2][kRowTiles], bf[2][kColTiles];
+            v4i af[3][kRowTiles], bf[3][kColTiles];
             auto fetch = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles]) {
 #pragma unroll
-                for (int i = 0; i < kRowTiles; ++i) fa[i] = lds_read16(wl_addr + (unsigned)(i * 32 * a.Kp) + aoff);
+                for (int i = 0; i < kRowTiles; ++i) fa[i] = lds_read16(wl_addr + (unsigned)(i * 32 * a.Kl) + aoff);
 #pragma unroll
                 for (int j = 0; j < kColTiles; ++j) fb[j] = lds_read16(bbase[j] + boff);
                 aoff += 32u;
@@ -357,48 +391,38 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
                 kj -= wrap ? a.cpt : 0;
                 boff += wrap ? wrap_add : 32u;
             };
-            // YOUNGER: a fetch issued after this set's is still in flight (LDS reads return in order;
-            // reads the compiler issued in between only make the wait stricter)
-            auto multiply = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles], auto tail_tag, auto younger_tag) {
-                if constexpr (decltype(younger_tag)::value) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(kRowTiles + kColTiles));
-                else asm volatile("s_waitcnt lgkmcnt(0)");
+            // (the two fetches issued after this set's are still in flight; LDS reads return in
+            // order, and reads the compiler issued in between only make the wait stricter)
+            auto multiply = [&](v4i(&fa)[kRowTiles], v4i(&fb)[kColTiles]) {
+                asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(2 * (kRowTiles + kColTiles)));
 #pragma unroll
                 for (int i = 0; i < kRowTiles; ++i) lds_arrived(fa[i]);
 #pragma unroll
-                for (int j = 0; j < kColTiles; ++j) {
-                    lds_arrived(fb[j]);
-                    if constexpr (decltype(tail_tag)::value)
-                        if (fk) fb[j] = v4i{0, 0, 0, 0};
-                }
+                for (int j = 0; j < kColTiles; ++j) lds_arrived(fb[j]);
 #pragma unroll
                 for (int i = 0; i < kRowTiles; ++i)
 #pragma unroll
                     for (int j = 0; j < kColTiles; ++j)       // (a dead second tile recomputes pixel 0)
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
             };
-            // (a fetch past the last chunk reads valid LDS addresses and is never multiplied)
+            // (the fetches past the last step read valid LDS addresses and are never multiplied)
             fetch(af[0], bf[0]);
-            for (int p = 0; p < (full >> 1); ++p) {
-                fetch(af[1], bf[1]);
-                multiply(af[0], bf[0], std::false_type{}, std::true_type{});
-                if (pdone < prv_items) {               // one output item of the previous strip per pair of steps
-                    pool_items(prv, pdone, pdone + 1, ptid);
+            fetch(af[1], bf[1]);
+            for (int p = 0; p < triples; ++p) {
+                fetch(af[2], bf[2]);
+                multiply(af[0], bf[0]);
+                if (pdone < prv_items) {               // one output item of the previous strip per three steps
+                    pool_items(prv, pdone, pdone + 1, ptid, ppos);
                     ++pdone;
                 }
                 fetch(af[0], bf[0]);
-                multiply(af[1], bf[1], std::false_type{}, std::true_type{});
-            }
-            if (full & 1) {
+                multiply(af[1], bf[1]);
                 fetch(af[1], bf[1]);
-                multiply(af[0], bf[0], std::false_type{}, std::true_type{});
-                if (tail) multiply(af[1], bf[1], std::true_type{}, std::false_type{});
-                else lds_wait();
-            } else {
-                if (tail) multiply(af[0], bf[0], std::true_type{}, std::false_type{});
-                else lds_wait();
+                multiply(af[2], bf[2]);
             }
+            lds_wait();
         }
-        pool_items(prv, pdone, prv_items, ptid);      // what the steps did not cover (all of it for an idle wavefront)
+        pool_items(prv, pdone, prv_items, ptid, ppos);      // what the steps did not cover (all of it for an idle wavefront)
         lds_barrier();                                // everyone is done with the patch and with the old image
 
         // ---- requantize into the LDS output image [pixel][kOutPitch] --------------------------
@@ -441,7 +465,10 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
         cur = nxt;
     }
     lds_barrier();                                    // the last strip's image is complete
-    pool_items(prv, 0, prv_items, opaque(tid));
+    {
+        OutPos lpos = out_first;
+        pool_items(prv, 0, prv_items, tid, lpos);
+    }
 }
 
 }  // namespace
@@ -467,6 +494,11 @@ hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_
     a.cpt = pl.tap_elems / kChunkBytes;
     a.nchunks = c.R * a.cpt;
     a.Kp = pl.Kp;
+    {
+        int lc = (int)round_up((size_t)a.nchunks, 6);     // chunks of a whole number of step triples
+        if (lc % 2 == 0) lc += 1;                          // odd row pitch: bank-conflict free fragment reads
+        a.Kl = lc * 16;
+    }
     a.x_bytes = (unsigned long long)c.N * c.H * c.W * c.C;
     if (a.x_bytes >= 0x7ffffff0ull || c.W > 4096) return hipErrorNotSupported;
     a.wsum_off = pl.wsum_off;
@@ -492,7 +524,7 @@ hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_
         const int crows = a.pool ? 2 * rps + 1 : rps;
         a.max_in_rows = (crows - 1) * a.stride + c.R;
         if ((long long)a.max_in_rows * (a.pitch / 16) > (long long)kRawItems * kThreads) continue;
-        a.lds_w = (int)round_up((size_t)kMaxK * a.Kp + 16, 1024);
+        a.lds_w = (int)round_up((size_t)kMaxK * a.Kl + 16, 1024);
         a.lds_patch = (int)round_up((size_t)a.max_in_rows * a.pitch + 64, 1024);
         a.lds_image = (int)round_up((size_t)crows * c.Q * kOutPitch + 16, 1024);
         if (a.lds_w + 1024 + a.lds_patch + a.lds_image <= 160 * 1024) break;
