@@ -20,33 +20,44 @@ inline int grid_for(size_t work, int threads, int max_blocks = 256 * 32) {
 // 2^-51); rounding that approximation gives the same integer as rounding the correctly rounded
 // quotient unless it lies within 2^-40 (relative) of a rounding boundary k + 1/2, and only then
 // is the division carried out.
+// NARROW (8- and 16-bit storage): the clamp is taken on the rounded double against lo - zp and
+// hi - zp (exact small integers), so the conversion is a single 32-bit one and no 64-bit integer
+// arithmetic is left; the 32-bit storage type keeps the wide form.
+template <bool NARROW>
 __device__ __forceinline__ int quant_one(float r, double scale, double inv_scale, int zp, int lo, int hi) {
     const double v = (double)r;
-    if (v != v) return zp;
     const double ta = v * inv_scale;
     double t = __builtin_rint(ta);
     const double d = __builtin_fabs(__builtin_fabs(ta - t) - 0.5);
     if (d <= __builtin_fabs(ta) * 0x1p-40) t = __builtin_rint(v / scale);
-    t = t > 4.0e9 ? 4.0e9 : (t < -4.0e9 ? -4.0e9 : t);
-    long long o = (long long)t + (long long)zp;
-    o = o < lo ? lo : (o > hi ? hi : o);
-    return (int)o;
+    if constexpr (NARROW) {
+        t = __builtin_fmin(__builtin_fmax(t, (double)(lo - zp)), (double)(hi - zp));
+        const int o = (int)t + zp;
+        return v != v ? zp : o;
+    } else {
+        if (v != v) return zp;
+        t = t > 4.0e9 ? 4.0e9 : (t < -4.0e9 ? -4.0e9 : t);
+        long long o = (long long)t + (long long)zp;
+        o = o < lo ? lo : (o > hi ? hi : o);
+        return (int)o;
+    }
 }
 
 template <typename OutT>
 __global__ void __launch_bounds__(kThreads)
 quantize_kernel(const float *__restrict__ src, OutT *__restrict__ dst, size_t n, float scale,
                 int zp, int lo, int hi, int vec_ok) {
+    constexpr bool NARROW = sizeof(OutT) < 4;
     const double s = (double)scale, inv = 1.0 / s;
     size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t nthreads = (size_t)gridDim.x * blockDim.x;
     size_t n4 = vec_ok ? n / 4 : 0;
     auto emit = [&](size_t i, float4 v) {
         OutT o[4];
-        o[0] = (OutT)quant_one(v.x, s, inv, zp, lo, hi);
-        o[1] = (OutT)quant_one(v.y, s, inv, zp, lo, hi);
-        o[2] = (OutT)quant_one(v.z, s, inv, zp, lo, hi);
-        o[3] = (OutT)quant_one(v.w, s, inv, zp, lo, hi);
+        o[0] = (OutT)quant_one<NARROW>(v.x, s, inv, zp, lo, hi);
+        o[1] = (OutT)quant_one<NARROW>(v.y, s, inv, zp, lo, hi);
+        o[2] = (OutT)quant_one<NARROW>(v.z, s, inv, zp, lo, hi);
+        o[3] = (OutT)quant_one<NARROW>(v.w, s, inv, zp, lo, hi);
         if constexpr (sizeof(OutT) == 1) {
             reinterpret_cast<uint32_t *>(dst)[i] = *reinterpret_cast<uint32_t *>(o);
         } else if constexpr (sizeof(OutT) == 2) {
@@ -65,7 +76,7 @@ quantize_kernel(const float *__restrict__ src, OutT *__restrict__ dst, size_t n,
         for (int u = 0; u < 4; ++u) emit(i + u * nthreads, v[u]);
     }
     for (; i < n4; i += nthreads) emit(i, reinterpret_cast<const float4 *>(src)[i]);
-    for (size_t j = n4 * 4 + tid; j < n; j += nthreads) dst[j] = (OutT)quant_one(src[j], s, inv, zp, lo, hi);
+    for (size_t j = n4 * 4 + tid; j < n; j += nthreads) dst[j] = (OutT)quant_one<NARROW>(src[j], s, inv, zp, lo, hi);
 }
 
 template <typename InT>
