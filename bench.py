@@ -23,8 +23,8 @@ import numpy as np
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)     # ~0.13 s of timed device work: long enough for the clocks to settle
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--dtype", default="int8", choices=["int8", "fp16", "int16"])
     ap.add_argument("--eager", action="store_true", help="issue every call from the host instead of replaying a HIP graph")
@@ -119,13 +119,18 @@ def main():
         hw = (P, Q)
     macs_img = sum(macs_layer)
 
-    # The step is ~10 short kernel launches; replaying it as a HIP graph keeps host launch
-    # latency out of the measurement (--eager issues the calls one by one instead).
+    # The step is 7 short kernel launches.  Replaying it as a HIP graph keeps host launch latency
+    # out of the measurement, and one graph holds several consecutive steps: a graph launch itself
+    # costs ~30 us on this stack (measured: 286 us per step with one step per graph, 256 us with
+    # five), which a serving loop amortises the same way.  The timed region runs exactly
+    # args.steps steps: steps / per_graph replays (--eager issues the calls one by one instead).
     y_eager = step().clone()
     torch.cuda.synchronize()
+    per_graph = 1
     if args.eager:
-        run_step = step
+        run_once = step
     else:
+        per_graph = next(u for u in (5, 4, 3, 2, 1) if args.steps % u == 0 and args.warmup % u == 0)
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -134,18 +139,19 @@ def main():
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            y_graph = step()
-        run_step = graph.replay
+            for _ in range(per_graph):
+                y_graph = step()
+        run_once = graph.replay
         for _ in range(3):          # every replay must reproduce the eager result
             graph.replay()
             torch.cuda.synchronize()
             assert torch.equal(y_graph, y_eager), "graph replay differs from eager execution"
-    for _ in range(args.warmup):
-        run_step()
+    for _ in range(args.warmup // per_graph):
+        run_once()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
+    for _ in range(args.steps // per_graph):
+        run_once()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / args.steps
@@ -194,6 +200,7 @@ def main():
         "value": round(tops, 3), "unit": "TFLOP/s" if dt == mb.FP16 else "TOP/s",
         "images_per_s": round(img_s, 1),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "steps_per_graph_launch": per_graph,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"int8": "int8 (int32 acc)", "fp16": "fp16 (fp32 acc)", "int16": "int16 (int64 acc)"}[args.dtype],
         "data": "synthetic",
