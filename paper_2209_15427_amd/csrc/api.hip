@@ -62,7 +62,8 @@ Plan make_plan(const mpq_conv_desc &d, int dtype, int in_w) {
         else if (CgB % 64 == 0) CB = 64;
         if (CB >= 32 && CB % kChunkBytes == 0) {
             const int cbc = CB / kChunkBytes, ksp = (d.r * d.s * cbc + 3) / 4;
-            if (ksp >= kPatchMinSteps) {
+            // (a 1x1 kernel: the fully-connected kernel reads the same layout, one step per block)
+            if (ksp >= kPatchMinSteps || (d.r == 1 && d.s == 1 && d.groups == 1 && cbc == 4 && CgB >= 256)) {
                 p.f_cbc = cbc;
                 p.f_nphase = CgB / CB;
                 p.f_ksp = ksp;
@@ -175,11 +176,13 @@ mpq_status geometry(const mpq_tensor &x, const mpq_conv_desc &d, Geometry *g) {
 struct WsLayout {
     size_t pad_off, pad_bytes;    // channel-padded copy of the input (row mode)
     size_t mid_off, mid_bytes;    // unpooled convolution output
+    size_t fc_off, fc_bytes;      // fully-connected layer: x in fragment order + partial sums
     size_t total;
 };
 
+// (num_experts > 0: the rows are expert-grouped, row groups are padded per expert)
 WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, const Geometry &g,
-                   int out_dtype) {
+                   int out_dtype, int num_experts = 0) {
     WsLayout w;
     std::memset(&w, 0, sizeof(w));
     size_t off = 0;
@@ -193,6 +196,13 @@ WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, 
         w.mid_bytes = round_up((size_t)x.n * g.P * g.Q * d.k * dtype_size(out_dtype), 256);
         off += w.mid_bytes;
     }
+    if (x.h == 1 && x.w == 1 && d.r == 1 && d.s == 1 && d.groups == 1 && pl.frag_bytes > 0 && pl.f_ksp == 1 &&
+        ((size_t)x.c * pl.esize) % 64 == 0 && x.n >= 1) {
+        const FcShape fs = fc_frag_shape(x.n, d.k, (size_t)x.c * pl.esize, num_experts);
+        w.fc_off = off;
+        w.fc_bytes = fs.xf_bytes + fs.part_bytes;
+        off += w.fc_bytes;
+    }
     w.total = off;
     return w;
 }
@@ -205,8 +215,11 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     mpq_status s = geometry(x, d, &g);
     if (s != MPQ_OK) return s;
     Plan pl = make_plan(d, x.dtype, x.w);
-    WsLayout wl = ws_layout(x, d, pl, g, y_dtype);
-    if (wl.total > 0 && (ws == nullptr || ws_bytes < wl.total || !aligned16(ws))) return MPQ_ERR_WORKSPACE;
+    WsLayout wl = ws_layout(x, d, pl, g, y_dtype, seg ? seg->num_experts : 0);
+    // (the fully-connected scratch is optional: without it the layer runs on the kernels that need none)
+    const size_t ws_required = wl.fc_bytes > 0 ? wl.fc_off : wl.total;
+    if (ws_required > 0 && (ws == nullptr || ws_bytes < ws_required || !aligned16(ws))) return MPQ_ERR_WORKSPACE;
+    const bool fc_ws = wl.fc_bytes > 0 && ws != nullptr && ws_bytes >= wl.total && aligned16(ws);
     if ((long long)x.n * g.P * g.Q > 0x7ffffc00ll) return MPQ_ERR_UNSUPPORTED;
 
     ConvArgs a;
@@ -243,6 +256,10 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     if (!seg && gemv_eligible(a) && (a.N < 4 || a.K <= 16)) {
         // batch < 4 (or <= 16 outputs): memory-bound, one pass over the larger matrix on the dot units
         err = launch_gemv(a, st);
+    } else if (fc_ws && d.pool_k == 0 && fc_frag_eligible(a)) {
+        // a matrix product on 4..512 rows (or an expert's rows): fragment-ordered operands, the
+        // reduction axis split over workgroups
+        err = launch_fc_frag(a, wsb + wl.fc_off, st);
     } else if (fc_stream_eligible(a)) {
         // a matrix product on up to a few hundred rows (or an expert's rows): weights streamed once
         // per 128 rows through the matrix cores
@@ -441,9 +458,9 @@ mpq_conv_desc mpq_gemm_desc(int32_t k_in, int32_t n_out, int32_t relu) {
 }
 
 size_t mpq_gemm_workspace_bytes(const mpq_tensor *x, int32_t n_out) {
-    (void)x;
-    (void)n_out;
-    return 0;
+    if (!x || n_out < 1 || x->c < 1) return 0;
+    mpq_conv_desc d = mpq_gemm_desc(x->c, n_out, 0);
+    return mpq_conv2d_workspace_bytes(x, &d);
 }
 
 mpq_status mpq_gemm(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q, const void *bias,
@@ -513,7 +530,7 @@ mpq_status moe_plan(const mpq_tensor &x, int E, const mpq_moe_layer *layers, int
         size_t act = (size_t)x.n * g.Po * g.Qo * ly.desc.k * dtype_size(x.dtype);
         if (act > max_act) max_act = act;
         Plan pl = make_plan(ly.desc, x.dtype, in.w);
-        size_t lw = ws_layout(in, ly.desc, pl, g, x.dtype).total;
+        size_t lw = ws_layout(in, ly.desc, pl, g, x.dtype, E).total;
         if (lw > max_ws) max_ws = lw;
         if (ly.w_stride < pl.total) return MPQ_ERR_WORKSPACE;
     }

@@ -149,6 +149,15 @@ bool gemv_eligible(const ConvArgs &a);
 hipError_t launch_gemv(const ConvArgs &a, hipStream_t st);
 bool fc_stream_eligible(const ConvArgs &a);
 hipError_t launch_fc_stream(const ConvArgs &a, hipStream_t st);
+// fragment-ordered FC (fc_frag.hip): tiling + workspace of a layer, eligibility, launch (ws_fc: xf_bytes +
+// part_bytes of 16-byte aligned scratch)
+struct FcShape {
+    int nrt, groups, ftiles, nk32, ks, jper, rows_pad, Npad;
+    size_t xf_bytes, part_bytes;
+};
+FcShape fc_frag_shape(int n_rows, int K_out, size_t Kbytes, int num_experts);
+bool fc_frag_eligible(const ConvArgs &a);
+hipError_t launch_fc_frag(const ConvArgs &a, void *ws_fc, hipStream_t st);
 
 // MoE helpers
 hipError_t launch_route(const void *logits, int logits_dtype, int B, int E, int *expert, int *counts,

@@ -1,0 +1,439 @@
+// Fully-connected layer on 4..512 rows (or an expert's share of the batch): both operands are read
+// in MFMA fragment order, the reduction axis is split over workgroups.
+//
+// acc[m, n] = sum_k x[m, k] w[n, k] on the raw codes (expanded zero-point form, section
+// "Quantized Operations"), then the same fused epilogue as the other kernels.
+//
+// The weights have a fragment-ordered copy next to the packed rows (see Plan): for a 32-feature
+// tile, reduction step j (32 bytes of the axis) is one 1 KiB block in which lane l holds row
+// l % 32, bytes 32 j + 16 (l / 32) .. + 16 -- exactly the A operand of one matrix instruction, so
+// a wavefront-wide 16-byte load is one contiguous KiB.  Three launches:
+//   1. x_to_fragments: the rows of x (a few MB at most, L2 resident) are copied into the same
+//      order, 32-row tiles, zero rows behind a row group's end.
+//   2. fc_frag_kernel: a workgroup owns 128 features (one 32-feature tile per wavefront) x one row
+//      group (32 NRT rows) x one slice of the reduction axis.  A wavefront streams its weight
+//      fragments from HBM into registers, several iterations ahead; the row group's x fragments
+//      come from L2 once per workgroup and are shared through LDS; the partial tile goes to the
+//      workspace as raw 32-bit accumulators.  Slices exist to put >= 512 workgroups on the
+//      chip: with 4096 features and 256 rows there are only 64 tiles.
+//   3. fc_reduce: sums the slices in a fixed order (deterministic, also for fp32), adds
+//      bias - z_x * sum(w), requantizes and stores.
+// In the expert-grouped launch a row group never crosses an expert boundary and takes that
+// expert's weights, bias and epilogue constants.
+#include <type_traits>
+
+#include "mfma_tile.h"
+
+namespace mpq {
+
+namespace {
+
+using namespace tile;
+
+constexpr int kFeatTile = 128;         // features per workgroup (4 wavefronts x 32)
+constexpr int kMaxSlices = 8;          // slices of the reduction axis at most
+
+struct FcArgs {
+    const char *x;          // [N][Kb] bytes
+    const char *w;          // packed weights (fragment copy at frag_off, sum(w) at wsum_off)
+    const void *bias;
+    void *y;
+    char *xf;               // workspace: x in fragment order, [row tile][nk32][1024]
+    char *part;             // workspace: [ks][rows_pad][Npad] raw 32-bit partial sums
+    int N, K;               // rows, output features
+    int Kb;                 // reduction bytes per row
+    int nk32;               // 32-byte reduction steps
+    int nrt;                // 32-row tiles per row group
+    int groups;             // row groups in the grid (an upper bound in the expert-grouped launch)
+    int ftiles;             // 128-feature tiles
+    int f_rt;               // 32-feature tiles that exist
+    int ks, jper;           // slices of the reduction axis, steps per slice
+    int rows_pad, Npad;
+    size_t frag_off, wsum_off;
+    Epi epi;
+    SegTable seg;
+};
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() carries a fence that also waits
+// for every global load in flight, i.e. for the fragments requested iterations ahead.
+__device__ __forceinline__ void lds_only_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Row group g in expert-aligned order: expert e owns ceil(rows_e / R) consecutive groups.
+struct GroupInfo {
+    int e, m_begin, m_end;
+    bool ok;
+};
+__device__ __forceinline__ GroupInfo find_group(const FcArgs &f, int g, int R) {
+    GroupInfo gi;
+    gi.e = 0;
+    gi.ok = false;
+    gi.m_begin = gi.m_end = 0;
+    if (!f.seg.offsets) {
+        gi.m_begin = g * R;
+        gi.m_end = min(f.N, gi.m_begin + R);
+        gi.ok = gi.m_begin < f.N;
+        return gi;
+    }
+    int base = 0;
+    for (int e = 0; e < f.seg.num_experts; ++e) {
+        const int lo = f.seg.offsets[e], hi = f.seg.offsets[e + 1];
+        const int ng = (hi - lo + R - 1) / R;
+        if (g < base + ng) {
+            gi.e = e;
+            gi.m_begin = lo + (g - base) * R;
+            gi.m_end = min(hi, gi.m_begin + R);
+            gi.ok = true;
+            return gi;
+        }
+        base += ng;
+    }
+    return gi;
+}
+
+// x -> fragment order.  One thread per 16-byte chunk in output order: the stores are whole
+// lines (16-byte pieces of a line written from different wavefronts cost a read-modify-write
+// each), the reads are 32-byte pieces of 32 rows.
+__global__ void __launch_bounds__(kThreads) x_to_fragments_kernel(FcArgs f) {
+    const int R = 32 * f.nrt;
+    const size_t total = (size_t)f.groups * f.nrt * f.nk32 * 64;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += nthreads) {
+        const int l = (int)(idx & 63);
+        const size_t t = idx >> 6;
+        const int j = (int)(t % f.nk32);
+        const int rt = (int)(t / f.nk32);            // row tile in the grid
+        const int g = rt / f.nrt, i = rt - g * f.nrt;
+        const GroupInfo gi = find_group(f, g, R);
+        const int m = gi.m_begin + i * 32 + (l & 31);
+        v4i v = {0, 0, 0, 0};
+        if (gi.ok && m < gi.m_end)
+            v = *reinterpret_cast<const v4i *>(f.x + (size_t)m * f.Kb + (size_t)j * 32 + (l >> 5) * kChunkBytes);
+        *reinterpret_cast<v4i *>(f.xf + idx * kChunkBytes) = v;
+    }
+}
+
+// NRT: 32-row tiles per row group; U: reduction steps per iteration.
+// An iteration multiplies U steps.  The row group's x fragments of an iteration (U NRT KiB) are
+// fetched once per workgroup -- a quarter by each wavefront, two iterations ahead -- and
+// shared through a double-buffered LDS tile (one barrier per iteration): read per wavefront they
+// made the kernel L2-bound (1.25 KiB per matrix instruction).  A wavefront's own weight fragments
+// come straight from HBM into a ring of four register sets, three iterations ahead; they are
+// issued after the x loads of the same iteration, so waiting for those does not wait for them.
+template <typename T, int NRT, int U>
+__global__ void __launch_bounds__(kThreads, 2) fc_frag_kernel(FcArgs f) {
+    typedef typename Mma<T>::Acc Acc;
+    constexpr int NB = U * NRT / 4;                    // x fragments a wavefront fetches per iteration
+    static_assert((U * NRT) % 4 == 0, "the x fragments of an iteration are split over four wavefronts");
+    constexpr int kPitch = 36;                         // dwords per row of the epilogue's 32 x 32 tile (32 + 4: 16-byte accesses spread over the banks)
+    constexpr int kBufV4 = U * NRT * 64 > 2 * 32 * kPitch / 4 ? U * NRT * 64 : 2 * 32 * kPitch / 4;
+    __shared__ v4i bl[2][kBufV4];                      // [buffer][(step * NRT + row tile) * 64 + lane]; the epilogue's tiles
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ft = blockIdx.x % f.ftiles;
+    const int rest = blockIdx.x / f.ftiles;
+    const int g = rest % f.groups, ks = rest / f.groups;
+    const GroupInfo gi = find_group(f, g, 32 * NRT);
+    if (!gi.ok) return;                                // (uniform over the workgroup, before any barrier)
+
+    const int art = ft * 4 + wave;                     // this wavefront's 32-feature tile
+    const bool tile_live = art < f.f_rt;
+    const char *wbase = f.w + (f.seg.offsets ? (size_t)gi.e * f.seg.w_stride : 0);
+    const char *afrag = wbase + f.frag_off + (size_t)(tile_live ? art : f.f_rt - 1) * f.nk32 * 1024 + lane * kChunkBytes;
+    const char *bfrag = f.xf + (size_t)(g * NRT) * f.nk32 * 1024 + lane * kChunkBytes;
+
+    Acc acc[NRT];
+#pragma unroll
+    for (int i = 0; i < NRT; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0;
+
+    const int jb = ks * f.jper, je = min(jb + f.jper, f.nk32);
+    const int iters = (je - jb + U - 1) / U;
+    const v4i zero = {0, 0, 0, 0};
+    v4i A[4][U], Bq[2][NB];
+    // (a step past the slice re-reads a valid block; its weights are replaced by zeros where they
+    // are multiplied -- a select right behind the load would wait for it there and then)
+    auto load_A = [&](auto slot_tag, int it) {
+        constexpr int S = decltype(slot_tag)::value;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = jb + it * U + u;
+            A[S][u] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(afrag + (size_t)(j < je ? j : jb) * 1024));
+        }
+    };
+    auto load_B = [&](auto ring_tag, int it) {
+        constexpr int Rg = decltype(ring_tag)::value;
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            const int fi = wave + 4 * k, u = fi / NRT, i = fi - u * NRT;
+            const int j = jb + it * U + u;
+            Bq[Rg][k] = *reinterpret_cast<const v4i *>(bfrag + ((size_t)i * f.nk32 + (j < je ? j : jb)) * 1024);
+        }
+    };
+    auto store_B = [&](auto ring_tag, int buf) {
+        constexpr int Rg = decltype(ring_tag)::value;
+#pragma unroll
+        for (int k = 0; k < NB; ++k) bl[buf][(wave + 4 * k) * 64 + lane] = Bq[Rg][k];
+    };
+    auto iteration = [&](auto slot_tag, int it) {
+        constexpr int S = decltype(slot_tag)::value;
+        if (it >= iters) return;                       // uniform
+        const bool more = it + 1 < iters;
+        // x fragments of iteration it + 2 (register set S % 2, whose last content went to LDS an
+        // iteration ago), then weight fragments of iteration it + 3
+        if (it + 2 < iters) load_B(std::integral_constant<int, S % 2>{}, it + 2);
+        load_A(std::integral_constant<int, (S + 3) % 4>{}, it + 3);
+        const int buf = it & 1;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const v4i av = jb + it * U + u < je ? A[S][u] : zero;
+#pragma unroll
+            for (int i = 0; i < NRT; ++i) acc[i] = Mma<T>::run(av, bl[buf][(u * NRT + i) * 64 + lane], acc[i]);
+        }
+        if (more) store_B(std::integral_constant<int, (S + 1) % 2>{}, buf ^ 1);
+        lds_only_barrier();                            // buffer buf is consumed, buffer buf ^ 1 is complete
+    };
+    load_B(std::integral_constant<int, 0>{}, 0);
+    load_B(std::integral_constant<int, 1>{}, 1);
+    load_A(std::integral_constant<int, 0>{}, 0);
+    load_A(std::integral_constant<int, 1>{}, 1);
+    load_A(std::integral_constant<int, 2>{}, 2);
+    store_B(std::integral_constant<int, 0>{}, 0);
+    lds_only_barrier();
+    for (int t = 0; t < iters; t += 4) {
+        iteration(std::integral_constant<int, 0>{}, t);
+        iteration(std::integral_constant<int, 1>{}, t + 1);
+        iteration(std::integral_constant<int, 2>{}, t + 2);
+        iteration(std::integral_constant<int, 3>{}, t + 3);
+    }
+    if (!tile_live) return;
+
+    // Register v of lane l: feature 8 (v / 4) + 4 (l / 32) + v % 4, row l % 32.  The tile is turned
+    // through LDS (the x buffers are free: the last iteration ended with a barrier) so that a
+    // store instruction writes 8 rows x 128 contiguous bytes instead of 64 separate 16-byte pieces.
+    // (Elements are taken out one by one: hipcc turned a bit_cast of acc[i][v] into element 0
+    // for every v.)
+    static_assert(4 * 32 * kPitch * 4 <= (int)sizeof(bl), "one 32 x 32 tile per wavefront");
+    int *tile_lds = reinterpret_cast<int *>(&bl[0][0]) + wave * 32 * kPitch;
+    const int frow = lane & 31, fk = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < NRT; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v4i o;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if constexpr (sizeof(T) == 1) {
+                    const int e = acc[i][4 * q + u];
+                    o[u] = e;
+                } else {
+                    const float e = acc[i][4 * q + u];
+                    o[u] = __float_as_int(e);
+                }
+            }
+            *reinterpret_cast<v4i *>(tile_lds + frow * kPitch + 8 * q + 4 * fk) = o;
+        }
+        // (a wavefront reads back only what it wrote itself: no barrier, the compiler orders the LDS traffic)
+        char *dst = f.part + (((size_t)ks * f.rows_pad + (size_t)(g * NRT + i) * 32) * f.Npad + art * 32) * 4;
+#pragma unroll
+        for (int p8 = 0; p8 < 4; ++p8) {
+            const int row = 8 * p8 + (lane >> 3);
+            const v4i o = *reinterpret_cast<const v4i *>(tile_lds + row * kPitch + 4 * (lane & 7));
+            *reinterpret_cast<v4i *>(dst + ((size_t)row * f.Npad + 4 * (lane & 7)) * 4) = o;
+        }
+    }
+}
+
+// Sum of the slices + epilogue; one thread per (row, 4 consecutive features).
+template <typename T>
+__global__ void __launch_bounds__(kThreads) fc_reduce_kernel(FcArgs f) {
+    const int R = 32 * f.nrt;
+    const int kq = f.K / 4;
+    const size_t total = (size_t)f.N * kq;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += nthreads) {
+        const int m = (int)(idx / kq), n = 4 * (int)(idx - (size_t)m * kq);
+        // row m of the batch -> its place in the group-padded row order
+        int e = 0, grow = m;
+        if (f.seg.offsets) {
+            int base = 0;
+            for (; e < f.seg.num_experts; ++e) {
+                const int lo = f.seg.offsets[e], hi = f.seg.offsets[e + 1];
+                if (m < hi) {
+                    grow = base * R + (m - lo);
+                    break;
+                }
+                base += (hi - lo + R - 1) / R;
+            }
+            if (e == f.seg.num_experts) continue;      // (a row behind the last offset: not part of the launch)
+        }
+        const char *wbase = f.w + (f.seg.offsets ? (size_t)e * f.seg.w_stride : 0);
+        const char *bias = (const char *)f.bias;
+        if (bias && f.seg.offsets) bias += (size_t)e * f.seg.bias_stride * 4;
+        const Epi epi = f.seg.offsets ? f.seg.epi[e] : f.epi;
+        const bool raw = epi.kind == kEpiRawI32 || epi.kind == kEpiRawF32;
+        const size_t o = (size_t)m * f.K + n;
+        if constexpr (sizeof(T) == 1) {
+            int t[4] = {0, 0, 0, 0};
+            v4i p[kMaxSlices];                         // all slices requested before the first is added
+#pragma unroll
+            for (int s = 0; s < kMaxSlices; ++s)
+                p[s] = *reinterpret_cast<const v4i *>(f.part + (((size_t)(s < f.ks ? s : 0) * f.rows_pad + grow) * f.Npad + n) * 4);
+#pragma unroll
+            for (int s = 0; s < kMaxSlices; ++s)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) t[u] += s < f.ks ? p[s][u] : 0;
+            const int *wsum = reinterpret_cast<const int *>(wbase + f.wsum_off);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (bias) t[u] += reinterpret_cast<const int *>(bias)[n + u];
+                if (epi.zx != 0) t[u] -= epi.zx * wsum[n + u];
+            }
+            if (raw) {
+                *reinterpret_cast<v4i *>((int *)f.y + o) = v4i{t[0], t[1], t[2], t[3]};
+            } else {
+                unsigned packed = 0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) packed |= ((unsigned)requant32(t[u], epi) & 0xffu) << (8 * u);
+                *reinterpret_cast<unsigned *>((int8_t *)f.y + o) = packed;
+            }
+        } else {
+            float t[4] = {0.f, 0.f, 0.f, 0.f};
+            v4i p[kMaxSlices];
+#pragma unroll
+            for (int s = 0; s < kMaxSlices; ++s)
+                p[s] = *reinterpret_cast<const v4i *>(f.part + (((size_t)(s < f.ks ? s : 0) * f.rows_pad + grow) * f.Npad + n) * 4);
+#pragma unroll
+            for (int s = 0; s < kMaxSlices; ++s)          // fixed order: the result does not depend on the launch
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int pu = p[s][u];
+                    t[u] += s < f.ks ? __int_as_float(pu) : 0.f;
+                }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (bias) t[u] += reinterpret_cast<const float *>(bias)[n + u];
+                if (epi.relu) t[u] = t[u] > 0.f ? t[u] : 0.f;
+            }
+            if (raw) {
+                *reinterpret_cast<float4 *>((float *)f.y + o) = make_float4(t[0], t[1], t[2], t[3]);
+            } else {
+                typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+                *reinterpret_cast<v4h *>((_Float16 *)f.y + o) = v4h{(_Float16)t[0], (_Float16)t[1], (_Float16)t[2], (_Float16)t[3]};
+            }
+        }
+    }
+}
+
+inline int grid_for(size_t work, int threads, int max_blocks = 256 * 16) {
+    size_t b = (work + threads - 1) / threads;
+    if (b < 1) b = 1;
+    if (b > (size_t)max_blocks) b = max_blocks;
+    return (int)b;
+}
+
+template <typename T, int NRT, int U>
+hipError_t launch_main(const FcArgs &f, hipStream_t st) {
+    const long long blocks = (long long)f.ftiles * f.groups * f.ks;
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
+    fc_frag_kernel<T, NRT, U><<<(unsigned)blocks, kThreads, 0, st>>>(f);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_typed(const FcArgs &f, hipStream_t st) {
+    const size_t chunks = (size_t)f.groups * f.nrt * f.nk32 * 64;
+    x_to_fragments_kernel<<<grid_for(chunks, kThreads), kThreads, 0, st>>>(f);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (f.nrt == 1) e = launch_main<T, 1, 8>(f, st);
+    else if (f.nrt == 2) e = launch_main<T, 2, 4>(f, st);
+    else e = launch_main<T, 4, 4>(f, st);
+    if (e != hipSuccess) return e;
+    fc_reduce_kernel<T><<<grid_for((size_t)f.N * (f.K / 4), kThreads), kThreads, 0, st>>>(f);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Tiling of a fully-connected layer on n_rows rows (num_experts > 0: expert-grouped rows) and the
+// workspace it needs.  Deterministic in the shapes: the workspace query and the launch agree.
+FcShape fc_frag_shape(int n_rows, int K_out, size_t Kbytes, int num_experts) {
+    FcShape s;
+    s.nrt = num_experts > 0 ? 4 : (n_rows <= 32 ? 1 : (n_rows <= 64 ? 2 : 4));
+    const int R = 32 * s.nrt;
+    s.groups = (n_rows + R - 1) / R + (num_experts > 0 ? num_experts : 0);
+    if (s.groups < 1) s.groups = 1;
+    s.ftiles = (K_out + kFeatTile - 1) / kFeatTile;
+    s.nk32 = (int)(Kbytes / 32);
+    // slices of the reduction axis: enough workgroups for two per CU, at least 8 steps per slice
+    int real_groups = (n_rows + R - 1) / R;
+    if (real_groups < 1) real_groups = 1;
+    int ks = (512 + s.ftiles * real_groups - 1) / (s.ftiles * real_groups);
+    if (ks > kMaxSlices) ks = kMaxSlices;
+    if (ks > s.nk32 / 8) ks = s.nk32 / 8;
+    if (ks < 1) ks = 1;
+    s.jper = (s.nk32 + ks - 1) / ks;
+    s.ks = (s.nk32 + s.jper - 1) / s.jper;
+    s.rows_pad = s.groups * R;
+    s.Npad = s.ftiles * kFeatTile;
+    s.xf_bytes = round_up((size_t)s.rows_pad * Kbytes, 256);
+    s.part_bytes = round_up((size_t)s.ks * s.rows_pad * s.Npad * 4, 256);
+    return s;
+}
+
+// 1x1 "convolution" on a 1x1 image (a matrix product), dense, with the fragment-ordered weight
+// copy; int8 needs z_w = 0 (every expert's, in a grouped launch).
+bool fc_frag_eligible(const ConvArgs &a) {
+    if (a.R != 1 || a.S != 1 || a.H != 1 || a.W != 1 || a.groups != 1) return false;
+    if (a.in_dtype != MPQ_INT8 && a.in_dtype != MPQ_FP16) return false;
+    const Plan &pl = a.plan;
+    if (pl.mode != kModeTap || pl.frag_bytes == 0 || pl.f_ksp != 1 || pl.f_cbc != 4) return false;
+    const size_t Kb = (size_t)a.C * pl.esize;
+    if (Kb % 64 != 0 || Kb / 32 < 8 || a.K % 4 != 0) return false;
+    if ((reinterpret_cast<uintptr_t>(a.x) % 16) || (reinterpret_cast<uintptr_t>(a.w) % 16) ||
+        (reinterpret_cast<uintptr_t>(a.y) % 16) || (a.bias && reinterpret_cast<uintptr_t>(a.bias) % 16))
+        return false;
+    if (a.in_dtype == MPQ_INT8) {
+        if (a.epi.zw != 0) return false;
+        if (a.seg.offsets)
+            for (int e = 0; e < a.seg.num_experts; ++e)
+                if (a.seg.epi[e].zw != 0) return false;
+    }
+    if (a.seg.offsets) return a.seg.w_stride % 16 == 0 && a.N >= 1;
+    return a.N >= 4 && a.N <= 512;
+}
+
+hipError_t launch_fc_frag(const ConvArgs &a, void *ws_fc, hipStream_t st) {
+    const Plan &pl = a.plan;
+    const size_t Kb = (size_t)a.C * pl.esize;
+    const FcShape s = fc_frag_shape(a.N, a.K, Kb, a.seg.offsets ? a.seg.num_experts : 0);
+    FcArgs f;
+    f.x = (const char *)a.x;
+    f.w = (const char *)a.w;
+    f.bias = a.bias;
+    f.y = a.y;
+    f.xf = (char *)ws_fc;
+    f.part = (char *)ws_fc + s.xf_bytes;
+    f.N = a.N;
+    f.K = a.K;
+    f.Kb = (int)Kb;
+    f.nk32 = s.nk32;
+    f.nrt = s.nrt;
+    f.groups = s.groups;
+    f.ftiles = s.ftiles;
+    f.f_rt = pl.f_rt;
+    f.ks = s.ks;
+    f.jper = s.jper;
+    f.rows_pad = s.rows_pad;
+    f.Npad = s.Npad;
+    f.frag_off = pl.frag_off;
+    f.wsum_off = pl.wsum_off;
+    f.epi = a.epi;
+    f.seg = a.seg;
+    if (a.in_dtype == MPQ_INT8) return launch_typed<int8_t>(f, st);
+    return launch_typed<_Float16>(f, st);
+}
+
+}  // namespace mpq

@@ -118,6 +118,8 @@ class Chain:
             self.views.append((xv, yv))
             if spec.kind != "fc":
                 ws_need = max(ws_need, mb.mpq_conv2d_workspace_bytes(xv(None), L.desc))
+            else:
+                ws_need = max(ws_need, mb.mpq_gemm_workspace_bytes(xv(None), oshape[3]))
             shape = oshape
         self.ws_bytes = ws_need
         self.ws = alloc_bytes(ws_need)

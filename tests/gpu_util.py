@@ -51,7 +51,8 @@ def run_conv(x_dev, xq, w_dev_kcrs, wq, bias_dev, desc, dtype, yq=(1.0, 0), out_
     return y
 
 
-def run_gemm(x_dev, xq, w_dev, wq, bias_dev, relu, dtype, yq=(1.0, 0), out_dtype=None):
+def run_gemm(x_dev, xq, w_dev, wq, bias_dev, relu, dtype, yq=(1.0, 0), out_dtype=None, workspace=True):
+    """workspace=False: call without the optional scratch (the layer then runs on the kernels that need none)."""
     out_dtype = dtype if out_dtype is None else out_dtype
     m, k = x_dev.shape
     n = w_dev.shape[0]
@@ -60,7 +61,9 @@ def run_gemm(x_dev, xq, w_dev, wq, bias_dev, relu, dtype, yq=(1.0, 0), out_dtype
     y = torch.full((m, n), 77, dtype=mb.TORCH_DTYPE[out_dtype], device="cuda")
     xv = mb.tensor(x_dev, dtype, m, 1, 1, k, xq[0], xq[1])
     yv = mb.tensor(y, out_dtype, m, 1, 1, n, yq[0], yq[1])
-    mb.mpq_gemm(xv, packed, wq[0], wq[1], bias_dev, yv, relu, None, 0)
+    nws = mb.mpq_gemm_workspace_bytes(xv, n) if workspace else 0
+    ws = pl.alloc_bytes(nws) if nws else None
+    mb.mpq_gemm(xv, packed, wq[0], wq[1], bias_dev, yv, relu, ws, nws)
     torch.cuda.synchronize()
     return y
 

@@ -219,6 +219,9 @@ FC_CASES = [  # M, K, N, relu, zx
     (256, 512, 384, True, 0), (100, 800, 500, True, -6), (64, 500, 10, False, 0), (256, 2304, 4, False, 0),
     (3, 100, 7, False, 2),
     (130, 1040, 96, True, 3), (40, 256, 36, False, 0), (512, 128, 64, True, 0),     # streamed-weight MFMA kernel: ragged rows / features / axis
+    # fragment-ordered kernel (reduction axis a multiple of 64 bytes): ragged rows and features, 1 / 2 / 4 row
+    # tiles per group, several slices of the reduction axis, more than one row group
+    (130, 1088, 100, True, 3), (48, 4608, 260, True, 0), (7, 9216, 516, False, 0), (300, 640, 132, True, -2),
 ]
 
 
@@ -246,6 +249,23 @@ def test_int_gemm(dtype, case):
     if dtype == mb.INT8:      # raw accumulators (gating logits)
         y = gu.run_gemm(xd, (s_x, zx), wd, (s_w, 0), bd, False, dtype, out_dtype=mb.INT32)
         assert np.array_equal(y.cpu().numpy().astype(np.int64), t)
+
+
+@pytest.mark.parametrize("case", [FC_CASES[i] for i in (4, 9, 12)], ids=["f4", "f9", "f12"])
+def test_int8_gemm_without_workspace(case):
+    """The scratch of mpq_gemm_workspace_bytes is optional: without it the layer runs on the kernels that need none."""
+    M, K, N, relu, zx = case
+    seed = 4500 + 13 * FC_CASES.index(case)
+    x = gen.integers(seed, (M, K), -128, 127)
+    w = gen.integers(seed + 1, (N, K), -127, 127)
+    b = gen.integers(seed + 2, (N,), -9000, 9000)
+    t = o.gemm_acc(x, zx, w, 0, b)
+    s_x, s_w = np.float32(0.02), np.float32(0.004)
+    s_y = np.float32(float(s_x) * float(s_w) * float(np.std(t)) * 3.0 / 127)
+    y = gu.run_gemm(torch.from_numpy(x.astype(np.int8)).to("cuda"), (s_x, zx), torch.from_numpy(w.astype(np.int8)).to("cuda"),
+                    (s_w, 0), torch.from_numpy(b.astype(np.int32)).to("cuda"), relu, mb.INT8, (s_y, 0), workspace=False)
+    mult, shift = o.scale_quant_vals(s_x, s_w, s_y, 31)
+    assert np.array_equal(y.cpu().numpy().astype(np.int32), o.requant(t, mult, 31, shift, 0, "int8", relu))
 
 
 def test_int16_gemm_accumulates_beyond_int32():
