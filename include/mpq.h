@@ -153,6 +153,10 @@ mpq_status mpq_conv2d(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q
  * same arithmetic and dtype rules as mpq_conv2d (the paper's InnerProduct layers, section
  * "ImageNet Configuration").  x is [M, K] (n=M, h=w=1, c=K); weights are logically [N, K],
  * packed with mpq_pack_weights(mpq_gemm_desc(K, N, relu)).
+ *   ws       device scratch, 256-byte aligned.  mpq_gemm_workspace_bytes() is what the fastest
+ *            kernel for 4..512 rows wants (a re-ordered copy of x and partial sums of the split
+ *            reduction axis); it is optional: with ws = NULL or fewer bytes the layer runs on
+ *            kernels that need none, with identical results for the integer types.
  * ------------------------------------------------------------------------------------------- */
 mpq_conv_desc mpq_gemm_desc(int32_t k_in, int32_t n_out, int32_t relu);
 size_t mpq_gemm_workspace_bytes(const mpq_tensor *x, int32_t n_out);
