@@ -138,8 +138,10 @@ __global__ void __launch_bounds__(kThreads, 2) fc_frag_kernel(FcArgs f) {
     const int art = ft * 4 + wave;                     // this wavefront's 32-feature tile
     const bool tile_live = art < f.f_rt;
     const char *wbase = f.w + (f.seg.offsets ? (size_t)gi.e * f.seg.w_stride : 0);
-    const char *afrag = wbase + f.frag_off + (size_t)(tile_live ? art : f.f_rt - 1) * f.nk32 * 1024 + lane * kChunkBytes;
-    const char *bfrag = f.xf + (size_t)(g * NRT) * f.nk32 * 1024 + lane * kChunkBytes;
+    // (uniform bases + 32-bit lane offsets: the loads below are issued by inline asm)
+    const char *abase = wbase + f.frag_off;
+    const unsigned avoff = (unsigned)(tile_live ? art : f.f_rt - 1) * (unsigned)f.nk32 * 1024u + (unsigned)lane * kChunkBytes;
+    const unsigned bvoff = (unsigned)(g * NRT) * (unsigned)f.nk32 * 1024u + (unsigned)lane * kChunkBytes;
 
     Acc acc[NRT];
 #pragma unroll
@@ -151,14 +153,16 @@ __global__ void __launch_bounds__(kThreads, 2) fc_frag_kernel(FcArgs f) {
     const int iters = (je - jb + U - 1) / U;
     const v4i zero = {0, 0, 0, 0};
     v4i A[4][U], Bq[2][NB];
-    // (a step past the slice re-reads a valid block; its weights are replaced by zeros where they
-    // are multiplied -- a select right behind the load would wait for it there and then)
+    // The global loads are not modelled by the compiler (it would wait for the youngest load whenever
+    // it needs the oldest): every iteration issues exactly NB + U of them -- a step past the slice
+    // re-reads a valid block, and its weights are replaced by zeros where they are multiplied -- and
+    // the waits below count what was issued behind the fragments they are for.
     auto load_A = [&](auto slot_tag, int it) {
         constexpr int S = decltype(slot_tag)::value;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int j = jb + it * U + u;
-            A[S][u] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(afrag + (size_t)(j < je ? j : jb) * 1024));
+            A[S][u] = global_read<0>(abase, avoff + (unsigned)(j < je ? j : jb) * 1024u);
         }
     };
     auto load_B = [&](auto ring_tag, int it) {
@@ -167,30 +171,37 @@ __global__ void __launch_bounds__(kThreads, 2) fc_frag_kernel(FcArgs f) {
         for (int k = 0; k < NB; ++k) {
             const int fi = wave + 4 * k, u = fi / NRT, i = fi - u * NRT;
             const int j = jb + it * U + u;
-            Bq[Rg][k] = *reinterpret_cast<const v4i *>(bfrag + ((size_t)i * f.nk32 + (j < je ? j : jb)) * 1024);
+            Bq[Rg][k] = global_read<0>(f.xf, bvoff + (unsigned)(i * f.nk32 + (j < je ? j : jb)) * 1024u);
         }
     };
     auto store_B = [&](auto ring_tag, int buf) {
         constexpr int Rg = decltype(ring_tag)::value;
 #pragma unroll
-        for (int k = 0; k < NB; ++k) bl[buf][(wave + 4 * k) * 64 + lane] = Bq[Rg][k];
+        for (int k = 0; k < NB; ++k) {
+            lds_arrived(Bq[Rg][k]);
+            bl[buf][(wave + 4 * k) * 64 + lane] = Bq[Rg][k];
+        }
     };
     auto iteration = [&](auto slot_tag, int it) {
         constexpr int S = decltype(slot_tag)::value;
         if (it >= iters) return;                       // uniform
-        const bool more = it + 1 < iters;
         // x fragments of iteration it + 2 (register set S % 2, whose last content went to LDS an
         // iteration ago), then weight fragments of iteration it + 3
-        if (it + 2 < iters) load_B(std::integral_constant<int, S % 2>{}, it + 2);
+        load_B(std::integral_constant<int, S % 2>{}, it + 2);
         load_A(std::integral_constant<int, (S + 3) % 4>{}, it + 3);
+        wait_vmcnt<3 * (NB + U)>();                    // the weights of this iteration: three iterations of loads are younger
         const int buf = it & 1;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
+            lds_arrived(A[S][u]);
             const v4i av = jb + it * U + u < je ? A[S][u] : zero;
 #pragma unroll
             for (int i = 0; i < NRT; ++i) acc[i] = Mma<T>::run(av, bl[buf][(u * NRT + i) * 64 + lane], acc[i]);
         }
-        if (more) store_B(std::integral_constant<int, (S + 1) % 2>{}, buf ^ 1);
+        if (it + 1 < iters) {
+            wait_vmcnt<NB + 2 * U>();                  // the x fragments of the next iteration
+            store_B(std::integral_constant<int, (S + 1) % 2>{}, buf ^ 1);
+        }
         lds_only_barrier();                            // buffer buf is consumed, buffer buf ^ 1 is complete
     };
     load_B(std::integral_constant<int, 0>{}, 0);
@@ -198,6 +209,7 @@ __global__ void __launch_bounds__(kThreads, 2) fc_frag_kernel(FcArgs f) {
     load_A(std::integral_constant<int, 0>{}, 0);
     load_A(std::integral_constant<int, 1>{}, 1);
     load_A(std::integral_constant<int, 2>{}, 2);
+    wait_vmcnt<0>();
     store_B(std::integral_constant<int, 0>{}, 0);
     lds_only_barrier();
     for (int t = 0; t < iters; t += 4) {
@@ -206,6 +218,7 @@ __global__ void __launch_bounds__(kThreads, 2) fc_frag_kernel(FcArgs f) {
         iteration(std::integral_constant<int, 2>{}, t + 2);
         iteration(std::integral_constant<int, 3>{}, t + 3);
     }
+    wait_vmcnt<0>();                                   // the fragments requested past the slice
     if (!tile_live) return;
 
     // Register v of lane l: feature 8 (v / 4) + 4 (l / 32) + v % 4, row l % 32.  The tile is turned
