@@ -48,8 +48,8 @@ FUSED_POOL_BY_DTYPE = {"int8": ("conv1", "conv5"), "fp16": ("conv5",), "int16": 
 # `bench.py --profile-layer NAME` (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter
 # reads for `--profile-layer copy`); the summaries are under profiles/.  None: not measured.
 MEASURED_TRAFFIC = {
-    ("conv1", "int8", 256): (2 * 20513.6 + 25178.1) * 1024, ("conv2", "int8", 256): (2 * 18333.1 + 46656.0) * 1024,
-    ("conv3", "int8", 256): (2 * 9104.4 + 16224.0) * 1024, ("conv4", "int8", 256): (2 * 12482.9 + 16264.1) * 1024,
+    ("conv1", "int8", 256): (2 * 20405.1 + 17496.1) * 1024, ("conv2", "int8", 256): (2 * 18354.9 + 46656.0) * 1024,
+    ("conv3", "int8", 256): (2 * 9105.4 + 16224.0) * 1024, ("conv4", "int8", 256): (2 * 12493.1 + 16264.1) * 1024,
     ("conv5", "int8", 256): (2 * 11824.0 + 2304.0) * 1024,
 }
 
