@@ -66,6 +66,7 @@ struct FirstArgs {
     int Kl;               // weight row pitch in LDS: the row, zeros up to a whole number of step triples, odd chunk count
     int pitch;            // bytes per expanded patch row (multiple of 16, > W * 4)
     int max_in_rows;      // input rows a full strip needs
+    int items_old, items_young;   // output items per thread of wavefronts 0..3 / 4..7 (see OutPos)
     unsigned q_magic, qo_magic, kd_magic, w_magic, g_magic;   // ceil(2^32 / d) for d = Q, Qo, K / 4, W, pitch / 16
     unsigned long long x_bytes;
     size_t wsum_off;
@@ -217,32 +218,37 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
 
     const int kd = a.K / 4;                           // dwords per output pixel
     int8_t *y = (int8_t *)a.y;
-    // Output item idx = k * 512 + tid of a strip: 4 channels (dword cd) of final pixel (orow, oq),
-    // idx = (orow * Qo + oq) * kd + cd.  A thread walks its items in order, so the position
-    // advances by a fixed step with two carries instead of being divided out per item.
+    // Output item idx of a strip: 4 channels (dword cd) of final pixel (orow, oq),
+    // idx = (orow * Qo + oq) * kd + cd.  The items are dealt out in runs of 256: wavefronts 0..3
+    // (the older wavefront of each SIMD, which wins the matrix pipe and finishes its reduction
+    // steps early) take the first items_old runs, wavefronts 4..7 the items_young runs behind
+    // them.  A thread walks its items in order, so the position advances by a fixed step with
+    // two carries instead of being divided out per item.
     struct OutPos {
         int cd, oq, orow;
     };
+    constexpr int kRun = kThreads / 2;
+    const int out_idx0 = wave < 4 ? tid : a.items_old * kRun + (tid - kRun);
+    const int my_items = wave < 4 ? a.items_old : a.items_young;
     OutPos out_first;
     {
-        const int op = (int)(((unsigned long long)(unsigned)tid * a.kd_magic) >> 32);
-        out_first.cd = tid - op * kd;
+        const int op = (int)(((unsigned long long)(unsigned)out_idx0 * a.kd_magic) >> 32);
+        out_first.cd = out_idx0 - op * kd;
         out_first.orow = (int)(((unsigned long long)(unsigned)op * a.qo_magic) >> 32);
         out_first.oq = op - out_first.orow * a.Qo;
     }
-    const int step_op = kThreads / kd, step_cd = kThreads - step_op * kd;
+    const int step_op = kRun / kd, step_cd = kRun - step_op * kd;
     const int step_orow = step_op / a.Qo, step_oq = step_op - step_orow * a.Qo;
     // Items k0 .. k1 - 1 of this thread for strip ps (pos: the position of item k0, advanced on
     // return): (pool and) store, channel-contiguous, from the LDS image.  The strip's output rows
     // are contiguous in memory.  An item past the strip's last reads item 0's place and stores nothing.
-    auto pool_items = [&](const Strip &ps, int k0, int k1, int ptid, OutPos &pos) {
+    auto pool_items = [&](const Strip &ps, int k0, int k1, OutPos &pos) {
         const int total = ps.orows * a.Qo * kd;
         int8_t *ystrip = y + ((size_t)ps.n * a.Po + ps.o0) * a.Qo * a.K;
         for (int k = k0; k < k1; ++k) {
-            const int idx = k * kThreads + ptid;
+            const int idx = out_idx0 + k * kRun;
             const bool live = idx < total;
-            const int cd = live ? pos.cd : out_first.cd, oq = live ? pos.oq : out_first.oq,
-                      orow = live ? pos.orow : out_first.orow;
+            const int cd = live ? pos.cd : 0, oq = live ? pos.oq : 0, orow = live ? pos.orow : 0;
             unsigned o;
             if (a.pool) {
                 const unsigned char *src = image + __umul24(__umul24(2 * orow, a.Q) + 2 * oq, kOutPitch) + cd * 4;
@@ -269,7 +275,6 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             pos.orow += step_orow + c2;
         }
     };
-    auto pool_item_count = [&](const Strip &ps) { return (ps.orows * a.Qo * kd + kThreads - 1) / kThreads; };
 
     // ---- once per workgroup: weights and accumulator start values ----------------------------------
     {
@@ -327,7 +332,6 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
         // (register v of lane l in a 32x32 tile: channel 8*(v/4) + 4*(l/32) + v%4, pixel l%32)
         const int npix = cur.npix;
         const int ml = opaque(lane), frow = ml & 31, fk = ml >> 5;
-        const int ptid = opaque(tid);
         const unsigned wl_addr = (unsigned)(size_t)MPQ_LDS(wl) + (unsigned)(frow * a.Kl);
         v16i acc[kRowTiles][kColTiles];
         {
@@ -362,8 +366,13 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
             const int py = (int)(((unsigned long long)(unsigned)pix * a.q_magic) >> 32), px = pix - py * a.Q;
             bbase[j] = patch_addr + (unsigned)(py * a.stride * a.pitch + px * a.stride * 4);
         }
-        int pdone = 0;                                // output items of strip prv already worked off
+        // The previous strip's output items (they read the image, the reduction reads the patch):
+        // wavefronts 0..3 work theirs off before their reduction steps, wavefronts 4..7 behind
+        // them, so that on every SIMD one wavefront is in vector work while the other has the
+        // matrix pipe to itself.  (Both kinds of work in the same order on both wavefronts ran
+        // one after the other: the pipe idled during the vector work.)
         OutPos ppos = out_first;
+        if (wave < 4) pool_items(prv, 0, prv_items, ppos);
         if (tile_live[0]) {      // uniform per wavefront: tiles are assigned in order
             // A step multiplies chunks 2 ks and 2 ks + 1 (lane halves fk = 0, 1) of a weight row; this
             // lane's chunk kc = 2 ks + fk is chunk kj of kernel row kr.  The offsets advance without
@@ -406,23 +415,23 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
             };
             // (the fetches past the last step read valid LDS addresses and are never multiplied)
+            // (raised priority: the matrix instructions go ahead of the other wavefront's vector work,
+            // which still runs at about two thirds of its rate in their shadow)
+            __builtin_amdgcn_s_setprio(2);
             fetch(af[0], bf[0]);
             fetch(af[1], bf[1]);
             for (int p = 0; p < triples; ++p) {
                 fetch(af[2], bf[2]);
                 multiply(af[0], bf[0]);
-                if (pdone < prv_items) {               // one output item of the previous strip per three steps
-                    pool_items(prv, pdone, pdone + 1, ptid, ppos);
-                    ++pdone;
-                }
                 fetch(af[0], bf[0]);
                 multiply(af[1], bf[1]);
                 fetch(af[1], bf[1]);
                 multiply(af[2], bf[2]);
             }
             lds_wait();
+            __builtin_amdgcn_s_setprio(0);
         }
-        pool_items(prv, pdone, prv_items, ptid, ppos);      // what the steps did not cover (all of it for an idle wavefront)
+        if (wave >= 4) pool_items(prv, 0, prv_items, ppos);
         lds_barrier();                                // everyone is done with the patch and with the old image
 
         // ---- requantize into the LDS output image [pixel][kOutPitch] --------------------------
@@ -459,7 +468,7 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
         // (no barrier here: the image is next read behind the barrier that follows the next expand)
 
         prv = cur;
-        prv_items = pool_item_count(cur);
+        prv_items = my_items;
         if (next >= s_end) break;
         sidx = next;
         cur = nxt;
@@ -467,7 +476,7 @@ __global__ void __launch_bounds__(kThreads, 1) conv_first_kernel(FirstArgs a) {
     lds_barrier();                                    // the last strip's image is complete
     {
         OutPos lpos = out_first;
-        pool_items(prv, 0, prv_items, tid, lpos);
+        pool_items(prv, 0, prv_items, lpos);
     }
 }
 
@@ -530,6 +539,12 @@ hipError_t launch_conv_first(const ConvArgs &c, int pool_k, int pool_s, void *y_
         if (a.lds_w + 1024 + a.lds_patch + a.lds_image <= 160 * 1024) break;
     }
     a.rows_per_strip = rps;
+    {
+        // output items (4 channels of a final pixel) per full strip, in runs of 256, half to wavefronts 0..3
+        const int runs = (rps * Qo * (c.K / 4) + kThreads / 2 - 1) / (kThreads / 2);
+        a.items_old = (runs + 1) / 2;
+        a.items_young = runs - a.items_old;
+    }
     a.strips = (Po + rps - 1) / rps;
     const size_t lds_bytes = (size_t)a.lds_w + 1024 + (size_t)a.lds_patch + a.lds_image;
     static bool attr_set = false;
