@@ -618,6 +618,7 @@ mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype lo
     if (launch_gather_rows(x->data, wsb + wl.buf_off[0], d_perm, B, row_in, st) != hipSuccess)
         return MPQ_ERR_DEVICE;
     int cur = 0;
+    bool scattered = false;
     for (int i = 0; i < L; ++i) {
         const mpq_moe_layer &ly = layers[i];
         mpq_tensor in;
@@ -632,14 +633,19 @@ mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype lo
             in.h = sh.h[i]; in.w = sh.w[i]; in.c = sh.c[i];
         }
         segs[i].offsets = d_offsets;
+        if (i == L - 1) {          // the last layer may write straight into sample order
+            segs[i].out_perm = d_perm;
+            segs[i].out_perm_y = y->data;
+            segs[i].out_perm_done = &scattered;
+        }
         s = run_conv(in, ly.w_packed, ly.bias, wsb + wl.buf_off[cur ^ 1], x->dtype, ly.desc, segs[i].epi[0],
                      &segs[i], wsb + wl.layer_ws_off, wl.layer_ws_bytes, st);
         if (s != MPQ_OK) return s;
         cur ^= 1;
     }
-    // scatter rows back to sample order
+    // scatter rows back to sample order (unless the last layer's kernel did)
     size_t row_out = (size_t)sh.h[L] * sh.w[L] * sh.c[L] * es;
-    if (launch_scatter_rows(wsb + wl.buf_off[cur], y->data, d_perm, B, row_out, st) != hipSuccess)
+    if (!scattered && launch_scatter_rows(wsb + wl.buf_off[cur], y->data, d_perm, B, row_out, st) != hipSuccess)
         return MPQ_ERR_DEVICE;
     return MPQ_OK;
 }

@@ -83,6 +83,12 @@ struct SegTable {
     int num_experts;
     int bias_stride;       // elements between experts' bias vectors
     size_t w_stride;       // bytes between experts' packed weights
+    // Optional, last layer only: row m of the output goes to row out_perm[m] of out_perm_y instead of
+    // row m of y (the scatter back to sample order).  A kernel that honours it sets *out_perm_done
+    // (a host flag); the others write y as usual.
+    const int *out_perm;
+    void *out_perm_y;
+    bool *out_perm_done;
     Epi epi[kMaxExperts];
 };
 

@@ -285,7 +285,8 @@ __global__ void __launch_bounds__(kThreads) fc_reduce_kernel(FcArgs f) {
         if (bias && f.seg.offsets) bias += (size_t)e * f.seg.bias_stride * 4;
         const Epi epi = f.seg.offsets ? f.seg.epi[e] : f.epi;
         const bool raw = epi.kind == kEpiRawI32 || epi.kind == kEpiRawF32;
-        const size_t o = (size_t)m * f.K + n;
+        // (expert-grouped launch with a scatter: the row goes straight to its sample's place)
+        const size_t o = (size_t)(f.seg.out_perm ? f.seg.out_perm[m] : m) * f.K + n;
         if constexpr (sizeof(T) == 1) {
             int t[4] = {0, 0, 0, 0};
             v4i p[kMaxSlices];                         // all slices requested before the first is added
@@ -426,7 +427,9 @@ hipError_t launch_fc_frag(const ConvArgs &a, void *ws_fc, hipStream_t st) {
     f.x = (const char *)a.x;
     f.w = (const char *)a.w;
     f.bias = a.bias;
-    f.y = a.y;
+    const bool scatter = a.seg.offsets && a.seg.out_perm && a.seg.out_perm_y &&
+                         (reinterpret_cast<uintptr_t>(a.seg.out_perm_y) % 16) == 0;
+    f.y = scatter ? a.seg.out_perm_y : a.y;
     f.xf = (char *)ws_fc;
     f.part = (char *)ws_fc + s.xf_bytes;
     f.N = a.N;
@@ -445,6 +448,8 @@ hipError_t launch_fc_frag(const ConvArgs &a, void *ws_fc, hipStream_t st) {
     f.wsum_off = pl.wsum_off;
     f.epi = a.epi;
     f.seg = a.seg;
+    if (!scatter) f.seg.out_perm = nullptr;
+    if (scatter && a.seg.out_perm_done) *a.seg.out_perm_done = true;
     if (a.in_dtype == MPQ_INT8) return launch_typed<int8_t>(f, st);
     return launch_typed<_Float16>(f, st);
 }
