@@ -195,6 +195,9 @@ maxpool_kernel(const T *__restrict__ x, T *__restrict__ y, int N, int H, int W, 
 // There is no packed 8-bit max: the even and the odd bytes of every dword are moved to the high
 // byte of a 16-bit lane (where the byte's sign is the lane's sign), the running maxima are kept in
 // that split form (packed 16-bit max), and the halves are merged once at the end.
+// KW: the window size when it is known at compile time (all of a window's loads are then issued
+// before the first max), 0: taken from k.
+template <int KW>
 __global__ void __launch_bounds__(kThreads)
 maxpool_i8x16_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, int N, int H, int W, int C,
                      int P, int Q, int k, int st) {
@@ -212,16 +215,26 @@ maxpool_i8x16_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y, int N
         v2s me[4], mo[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) me[u] = mo[u] = v2s{(short)-32768, (short)-32768};
-        for (int r = 0; r < k; ++r)
-            for (int s = 0; s < k; ++s) {
-                const v4u v = *reinterpret_cast<const v4u *>(base + ((size_t)r * W + s) * C);
+        auto take = [&](const v4u v) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const unsigned e = (v[u] << 8) & 0xff00ff00u, o = v[u] & 0xff00ff00u;
-                    me[u] = __builtin_elementwise_max(me[u], __builtin_bit_cast(v2s, e));
-                    mo[u] = __builtin_elementwise_max(mo[u], __builtin_bit_cast(v2s, o));
-                }
+            for (int u = 0; u < 4; ++u) {
+                const unsigned e = (v[u] << 8) & 0xff00ff00u, o = v[u] & 0xff00ff00u;
+                me[u] = __builtin_elementwise_max(me[u], __builtin_bit_cast(v2s, e));
+                mo[u] = __builtin_elementwise_max(mo[u], __builtin_bit_cast(v2s, o));
             }
+        };
+        if constexpr (KW > 0) {
+            v4u w[KW * KW];
+#pragma unroll
+            for (int r = 0; r < KW; ++r)
+#pragma unroll
+                for (int s = 0; s < KW; ++s) w[r * KW + s] = *reinterpret_cast<const v4u *>(base + ((size_t)r * W + s) * C);
+#pragma unroll
+            for (int i = 0; i < KW * KW; ++i) take(w[i]);
+        } else {
+            for (int r = 0; r < k; ++r)
+                for (int s = 0; s < k; ++s) take(*reinterpret_cast<const v4u *>(base + ((size_t)r * W + s) * C));
+        }
         v4u m;
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -375,7 +388,9 @@ hipError_t launch_maxpool(const void *x, void *y, int N, int H, int W, int C, in
         const int cv = C / 16;
         int ty = kThreads / cv;
         if (ty > Q) ty = Q;
-        maxpool_i8x16_kernel<<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const int8_t *)x, (int8_t *)y, N, H, W, C, P, Q, k, s);
+        if (k == 3) maxpool_i8x16_kernel<3><<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const int8_t *)x, (int8_t *)y, N, H, W, C, P, Q, k, s);
+        else if (k == 2) maxpool_i8x16_kernel<2><<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const int8_t *)x, (int8_t *)y, N, H, W, C, P, Q, k, s);
+        else maxpool_i8x16_kernel<0><<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const int8_t *)x, (int8_t *)y, N, H, W, C, P, Q, k, s);
     } else if (dtype == MPQ_FP16 && C % 8 == 0 && C / 8 <= kThreads && aligned && (long long)N * P <= 0x7fffffffll) {
         const int cv = C / 8;
         int ty = kThreads / cv;
