@@ -319,7 +319,8 @@ def bench_fc(torch, mb, pl, cf, calib, dtype_name):
         xs = pl.to_storage(x, dt, s_x, 0)
         es = 1 if dtype_name == "int8" else 2
         wbytes = L.N * L.K * es
-        copies = max(2, int(320e6 // lay.packed_bytes) + 1)
+        # (the batch-1 kernel streams the row-major weights: wbytes of every copy, not its fragment-ordered twin)
+        copies = max(2, int(320e6 // wbytes) + 1)
         stride = (lay.packed_bytes + 255) // 256 * 256
         big = pl.alloc_bytes(stride * copies)
         for c in range(copies):
