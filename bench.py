@@ -102,7 +102,7 @@ def main():
         else:
             i = [L.name for L in cf.ALEXNET_CONVS].index(args.profile_layer)
             ins = [x_store] + chain.acts[:-1]
-            call = (lambda: chain.run_layer(i, ins[i])) if cf.ALEXNET_CONVS[i].name in FUSED_POOL else conv_only_call(mb, chain, ins, i, dt)
+            call = (lambda: chain.run_layer(i, ins[i])) if cf.ALEXNET_CONVS[i].name in FUSED_POOL else conv_only_call(mb, pl, chain, ins, i, dt)
         for _ in range(args.steps):
             call()
         torch.cuda.synchronize()
@@ -181,7 +181,7 @@ def main():
         if L.name in FUSED_POOL:
             conv_only_us[L.name] = layer_us[L.name]
             continue
-        conv_only_us[L.name] = time_call(conv_only_call(mb, chain, ins, i, dt))
+        conv_only_us[L.name] = time_call(conv_only_call(mb, pl, chain, ins, i, dt))
     ops_of = {n: 2.0 * macs_layer[names.index(n)] * B for n in names}
     kernels = {n: {"us": round(conv_only_us[n], 2), "achieved": round(ops_of[n] / (conv_only_us[n] * 1e-6) / 1e12, 1),
                    "frac": round(ops_of[n] / (conv_only_us[n] * 1e-6) / 1e12 / PEAK[args.dtype], 4),
@@ -224,7 +224,7 @@ def main():
     print(json.dumps(out))
 
 
-def conv_only_call(mb, chain, ins, i, dt):
+def conv_only_call(mb, pl, chain, ins, i, dt):
     """The convolution of layer i of the chain as one mpq_conv2d call without its max-pool."""
     import torch
     from workloads import configs as cf
@@ -237,8 +237,10 @@ def conv_only_call(mb, chain, ins, i, dt):
     s_x = chain.s_in if i == 0 else chain.layers[i - 1].y_scale
     xv = mb.tensor(ins[i], dt, n, h, w_, c, s_x)
     yv = mb.tensor(tmp, dt, n, P, Q, L.K, lay.y_scale)
-    # the views hold raw pointers: the closure keeps the output buffer (and the input) alive
-    return lambda _keep=(tmp, ins[i]): mb.mpq_conv2d(xv, lay.packed, lay.w_scale, 0, lay.bias, yv, d, None, 0)
+    nws = mb.mpq_conv2d_workspace_bytes(xv, d)       # (first-layer plans keep a channel-padded copy of the input there)
+    ws = pl.alloc_bytes(nws) if nws else None
+    # the views hold raw pointers: the closure keeps the output buffer, the input and the workspace alive
+    return lambda _keep=(tmp, ins[i], ws): mb.mpq_conv2d(xv, lay.packed, lay.w_scale, 0, lay.bias, yv, d, ws, nws)
 
 
 def graph_time(torch, fn, iters=10, reps=10):

@@ -220,7 +220,7 @@ hipError_t launch_one(ConvArgs a, hipStream_t st) {
 template <typename T>
 hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
     const int Kg = a.plan.Kg;
-    bool wide = Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0);
+    bool wide = wide_channel_tiles(Kg);
     if (wide) {
         // few pixel tiles (a fully-connected layer, an expert's share of the batch): the narrow
         // tile doubles the number of workgroups that stream the weights

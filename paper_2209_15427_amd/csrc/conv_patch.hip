@@ -361,7 +361,7 @@ bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, bo
     if (a.cbc != 4 && a.ksp > kPatchMaxSteps) return false;
     const int Hv = a.H + 2 * a.pad_h, Wv = a.W + 2 * a.pad_w, PQ = a.P * a.Q;
     const int Kg = pl.Kg;
-    const bool wide = Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0);
+    const bool wide = wide_channel_tiles(Kg);
     const bool raw_out = a.epi.kind == kEpiRawI32 || a.epi.kind == kEpiRawF32;
     if (wide && a.cbc == 4 && PQ > 128 && PQ <= kImageBP && !raw_out && !a.seg.offsets) {
         // worth it when the pool can be fused, or when the images make one wave of workgroups
@@ -412,7 +412,7 @@ namespace {
 template <typename T>
 hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
     const int Kg = a.plan.Kg;
-    const bool wide = Kg % 128 == 0 || (Kg > 128 && Kg % 64 != 0);
+    const bool wide = wide_channel_tiles(Kg);
     const bool uni = a.cbc == 4;                       // 64-byte channel blocks: one tap per step
     if (a.tile_px) return launch_one<T, 128, kImageBP, 2, 2, kPatchSlots, 2, true>(a, st);
     if (wide) {

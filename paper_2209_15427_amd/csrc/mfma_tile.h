@@ -69,6 +69,10 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 // Division by a run-time constant: with magic = ceil(2^32 / d), d >= 2, the high half of v * magic
 // is floor(v / d) for every v with v * d < 2^32 (the host checks the range it uses).
 __device__ __forceinline__ unsigned udiv_magic(unsigned v, unsigned magic) { return __umulhi(v, magic); }
+// 128-channel tiles whenever they cover the group with no more rows than 64-channel tiles would
+// (128, 256, ... and e.g. 96 or 200 channels): the same matrix work, and the pixel operand is
+// fetched once per 128 channels instead of once per 64.
+inline bool wide_channel_tiles(int Kg) { return (Kg + 127) / 128 * 128 <= (Kg + 63) / 64 * 64; }
 inline unsigned magic_u32(unsigned d) { return d < 2 ? 0u : (unsigned)(((1ull << 32) + d - 1) / d); }
 inline bool magic_exact(unsigned long long vmax, unsigned d) { return vmax * d < (1ull << 32); }
 // the launchers' part of ConvArgs; false when the grid is too large for the magic divisions
