@@ -40,9 +40,10 @@ def parse():
 PEAK = {"int8": 5000.0, "fp16": 2500.0, "int16": 1250.0}   # dense MFMA, TOP/s (int16: int8 peak / 4)
 HBM_PEAK_GBS = 8000.0
 
-# Layers whose max-pool runs inside the convolution kernel (one kernel per layer call).
+# Layers whose max-pool runs inside the convolution kernel (conv2: in the epilogue of row tiles, plus a
+# small kernel for the pooling windows that straddle two tiles).
 FUSED_POOL = ()
-FUSED_POOL_BY_DTYPE = {"int8": ("conv1", "conv5"), "fp16": ("conv5",), "int16": ()}
+FUSED_POOL_BY_DTYPE = {"int8": ("conv1", "conv2", "conv5"), "fp16": ("conv2", "conv5"), "int16": ()}
 
 # HBM bytes per launch (fetch + write) of the convolution kernels, from rocprofv3 --pmc runs of
 # `bench.py --profile-layer NAME` (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter

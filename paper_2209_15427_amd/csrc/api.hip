@@ -176,6 +176,7 @@ mpq_status geometry(const mpq_tensor &x, const mpq_conv_desc &d, Geometry *g) {
 struct WsLayout {
     size_t pad_off, pad_bytes;    // channel-padded copy of the input (row mode)
     size_t mid_off, mid_bytes;    // unpooled convolution output
+    size_t pp_off, pp_bytes;      // row-tiled convolution with the pool in its epilogue: windows that straddle two tiles
     size_t fc_off, fc_bytes;      // fully-connected layer: x in fragment order + partial sums
     size_t total;
 };
@@ -195,6 +196,15 @@ WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, 
         w.mid_off = off;
         w.mid_bytes = round_up((size_t)x.n * g.P * g.Q * d.k * dtype_size(out_dtype), 256);
         off += w.mid_bytes;
+    }
+    if (d.pool_k == 3 && d.pool_s == 2 && d.stride_h == 1 && d.stride_w == 1 && out_dtype != MPQ_INT16) {
+        int tr = 0, ti = 1;
+        pool_row_tiling(g.P, g.Q, &tr, &ti);
+        if (tr > 0) {
+            w.pp_off = off;
+            w.pp_bytes = round_up((size_t)x.n * (ti - 1) * 2 * g.Qo * d.k * dtype_size(out_dtype), 256);
+            off += w.pp_bytes;
+        }
     }
     if (x.h == 1 && x.w == 1 && d.r == 1 && d.s == 1 && d.groups == 1 && pl.frag_bytes > 0 && pl.f_ksp == 1 &&
         ((size_t)x.c * pl.esize) % 64 == 0 && x.n >= 1) {
@@ -297,11 +307,18 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
         }
         a.x_bytes = (unsigned long long)a.N * a.H * a.W * a.C * pl.esize;
         bool pool_fused = false;
-        if (conv_patch_prepare(a, d.pool_k == 3 && d.pool_s == 2, g.Po, g.Qo, y_data, &pool_fused)) {
+        void *pool_part = (wl.pp_bytes > 0 && ((size_t)d.k * dtype_size(y_dtype)) % 16 == 0) ? (void *)(wsb + wl.pp_off) : nullptr;
+        if (conv_patch_prepare(a, d.pool_k == 3 && d.pool_s == 2, g.Po, g.Qo, y_data, pool_part, &pool_fused)) {
             err = launch_conv_patch(a, st);
-            if (err == hipSuccess && pool_fused) return MPQ_OK;
+            if (err == hipSuccess && pool_fused) {
+                if (a.tiles_img > 1 &&
+                    launch_pool_fixup(a.pool_part, y_data, x.n, g.Po, g.Qo, d.k, a.tile_px / a.Q, a.tiles_img, y_dtype, st) != hipSuccess)
+                    return MPQ_ERR_DEVICE;
+                return MPQ_OK;
+            }
         } else {
             a.tile_px = 0;
+            a.tiles_img = 1;
             a.pool = 0;
             err = conv_mfma_dma_eligible(a) ? launch_conv_mfma_dma(a, st) : launch_conv_mfma(a, st);
         }

@@ -111,7 +111,10 @@ struct ConvArgs {
     int tap_px;            // input pixels one tap spans (1, or the padded row length in row mode)
     int ptiles;            // pixel tiles in the grid (filled by the launcher)
     int big_patch;         // patch kernel: the single-phase variant with one large patch buffer
-    int tile_px;           // 0: a pixel tile is BP consecutive output pixels; else image-aligned tiles of P Q pixels
+    int tile_px;           // 0: a pixel tile is BP consecutive output pixels; else image-aligned tiles: tile_px pixels
+                           // (whole rows) per tile, tiles_img tiles per image (1: the tile is the image)
+    int tiles_img;
+    void *pool_part;       // tiles_img > 1 with a fused pool: the windows that straddle two tiles, [n][boundary][part 0/1][Qo][K]
     int pool;              // image-aligned tiles only: store the 3x3 / stride-2 max-pool of the output (Po x Qo)
     int Po, Qo;
     unsigned magic_ct, magic_pt;   // magic_u32 of the channel / pixel tile counts (filled by the launcher)
@@ -121,6 +124,7 @@ struct ConvArgs {
     // block, and ceil(2^32 / d) for d = Wv, Hv * Wv, cbc
     int cbc, nphase, ksp;
     unsigned magic_wv, magic_hw, magic_cbc, magic_s, magic_pq, magic_q;
+    unsigned magic_qo;     // ceil(2^32 / Qo) for the pooled epilogue
     unsigned fill_word;    // the input zero-point replicated over 32 bits (out-of-image taps)
     unsigned long long x_bytes;   // size of the input tensor the kernel sees
     Plan plan;
@@ -147,7 +151,13 @@ hipError_t launch_conv_generic(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_mfma(const ConvArgs &a, hipStream_t st);
 bool conv_mfma_dma_eligible(const ConvArgs &a);
 hipError_t launch_conv_mfma_dma(const ConvArgs &a, hipStream_t st);
-bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, bool *fused);
+bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, void *pool_part, bool *fused);
+// Row tiling of an image for the patch kernel's fused 3x3 / stride-2 pool when the image has more than one tile's
+// pixels: rows per tile (0: not possible) and tiles per image
+void pool_row_tiling(int P, int Q, int *tile_rows, int *tiles_img);
+// max of the two partial rows of every pooling window that straddles two row tiles -> the pooled tensor
+hipError_t launch_pool_fixup(const void *part, void *y_pool, int N, int Po, int Qo, int K, int tile_rows, int tiles_img,
+                             int dtype, hipStream_t st);
 hipError_t launch_conv_patch(const ConvArgs &a, hipStream_t st);
 hipError_t launch_conv_first(const ConvArgs &a, int pool_k, int pool_s, void *y_final, int Po, int Qo,
                              hipStream_t st);

@@ -305,11 +305,9 @@ __global__ void __launch_bounds__(kThreads, WPE) conv_patch_kernel(ConvArgs a) {
     step(NoSlot{}, NoPrev{}, integral_constant<int, kEndAll>{}, 0);
     bare_barrier();                        // everyone is done with the patch buffers
 
-    if constexpr (BP == kImageBP) {
-        if (a.pool) {
-            TL::template finish<true>(acc, lds, a, t);
-            return;
-        }
+    if (a.pool) {
+        TL::template finish<true>(acc, lds, a, t);
+        return;
     }
     TL::template finish<false>(acc, lds, a, t);
 }
@@ -321,7 +319,7 @@ hipError_t launch_one(ConvArgs a, hipStream_t st) {
     long long rows = (long long)a.N * PQ;
     int ptiles = (int)((rows + BP - 1) / BP);
     if (a.seg.offsets) ptiles += a.seg.num_experts;
-    if (a.tile_px) ptiles = a.N;                       // image-aligned: one pixel tile per image
+    if (a.tile_px) ptiles = a.N * a.tiles_img;         // image-aligned tiles
     long long blocks = (long long)ptiles * ctiles * a.groups;
     if (blocks <= 0) return hipSuccess;
     if (!set_tile_counts(a, ptiles, ctiles)) return hipErrorInvalidValue;
@@ -338,15 +336,29 @@ constexpr int kBP = 256;
 
 }  // namespace
 
+void pool_row_tiling(int P, int Q, int *tile_rows, int *tiles_img) {
+    *tile_rows = 0;
+    *tiles_img = 1;
+    if (Q < 3 || P < 3 || 3 * Q > kBP) return;
+    const int max_rows = kBP / Q;
+    const int ti = (P + max_rows - 1) / max_rows;
+    const int tr = (P + ti - 1) / ti;                  // rows per tile, balanced
+    if (ti < 2 || tr < 3 || P - (ti - 1) * tr < 1) return;
+    *tile_rows = tr;
+    *tiles_img = ti;
+}
+
 // Fills the patch-kernel fields of `a` and says whether the layer fits: stride 1, tap-mode plan,
 // zero padding value (see the header), every tile's virtual run within one patch buffer.
 // A layer whose image has 129..192 output pixels gets image-aligned tiles (one image per pixel
 // tile: 256 images x 2 groups of conv5 are exactly one wave of 512 workgroups); with those, a
 // 3x3 / stride-2 max-pool (`pool`, output Po x Qo at `y_pool`) is taken in the epilogue: *fused
 // says so, and a.y then is the pooled tensor.
-bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, bool *fused) {
+bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, void *pool_part, bool *fused) {
     *fused = false;
     a.tile_px = 0;
+    a.tiles_img = 1;
+    a.pool_part = nullptr;
     a.pool = 0;
     const Plan &pl = a.plan;
     if (pl.mode != kModeTap || a.stride_h != 1 || a.stride_w != 1) return false;
@@ -370,15 +382,39 @@ bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, bo
         const bool pool_ok = pool && (reinterpret_cast<uintptr_t>(y_pool) % 16) == 0;
         if (pool_ok || blocks_img <= 512) a.tile_px = PQ;
     }
+    // A larger image whose 3x3 / stride-2 pool can be taken in the epilogue: tiles of whole rows (conv2:
+    // 27 rows = 3 tiles of 9 rows = 243 of 256 pixels, and 3 x 256 images x 2 groups is a whole number of
+    // waves of 512 workgroups); the windows that straddle two tiles go through pool_part.
+    if (!a.tile_px && pool && pool_part && PQ > kImageBP && !raw_out && !a.seg.offsets &&
+        (reinterpret_cast<uintptr_t>(y_pool) % 16) == 0 && (reinterpret_cast<uintptr_t>(pool_part) % 16) == 0) {
+        int tr = 0, ti = 0;
+        pool_row_tiling(a.P, a.Q, &tr, &ti);
+        if (tr > 0) {
+            a.tile_px = tr * a.Q;
+            a.tiles_img = ti;
+            a.pool_part = pool_part;
+        }
+    }
     // largest virtual run any tile (kBP consecutive output pixels, or one image) can need
     long long worst = 0;
     auto virt = [&](long long m) {
         const long long n = m / PQ, rem = m % PQ;
         return (n * Hv + rem / a.Q) * Wv + rem % a.Q;
     };
-    for (int s0 = 0; s0 < (a.tile_px ? 1 : PQ); ++s0) {
-        const long long span = virt((long long)s0 + (a.tile_px ? PQ : kBP) - 1) + (long long)(a.R - 1) * Wv + (a.S - 1) - virt(s0) + 1;
-        if (span > worst) worst = span;
+    auto worst_span = [&]() {
+        long long w = 0;
+        for (int s0 = 0; s0 < (a.tile_px ? 1 : PQ); ++s0) {      // (image-aligned tiles start a row: one case)
+            const long long span = virt((long long)s0 + (a.tile_px ? a.tile_px : kBP) - 1) + (long long)(a.R - 1) * Wv + (a.S - 1) - virt(s0) + 1;
+            if (span > w) w = span;
+        }
+        return w;
+    };
+    worst = worst_span();
+    if (a.tiles_img > 1 && worst * CB > kPatchBytes) {           // row tiles that do not fit: plain tiles, pool outside
+        a.tile_px = 0;
+        a.tiles_img = 1;
+        a.pool_part = nullptr;
+        worst = worst_span();
     }
     a.big_patch = 0;
     if (worst * CB > kPatchBytes) {
@@ -396,11 +432,12 @@ bool conv_patch_prepare(ConvArgs &a, bool pool, int Po, int Qo, void *y_pool, bo
     if (a.S < 2 || a.Q < 2 || PQ < 2 || !magic_exact((unsigned long long)a.N * PQ + kBP, (unsigned)PQ)) return false;
     a.magic_pq = magic_u32((unsigned)PQ);
     a.magic_q = magic_u32((unsigned)a.Q);
-    if (a.tile_px && pool && (reinterpret_cast<uintptr_t>(y_pool) % 16) == 0 && Po >= 1 && Qo >= 1 &&
+    if (a.tile_px && pool && (reinterpret_cast<uintptr_t>(y_pool) % 16) == 0 && Po >= 1 && Qo >= 2 &&
         2 * (Po - 1) + 3 <= a.P && 2 * (Qo - 1) + 3 <= a.Q) {
         a.pool = 1;
         a.Po = Po;
         a.Qo = Qo;
+        a.magic_qo = magic_u32((unsigned)Qo);
         a.y = y_pool;
         *fused = true;
     }
@@ -414,7 +451,7 @@ hipError_t launch_typed(const ConvArgs &a, hipStream_t st) {
     const int Kg = a.plan.Kg;
     const bool wide = wide_channel_tiles(Kg);
     const bool uni = a.cbc == 4;                       // 64-byte channel blocks: one tap per step
-    if (a.tile_px) return launch_one<T, 128, kImageBP, 2, 2, kPatchSlots, 2, true>(a, st);
+    if (a.tile_px && a.tiles_img == 1) return launch_one<T, 128, kImageBP, 2, 2, kPatchSlots, 2, true>(a, st);
     if (wide) {
         if (uni) return launch_one<T, 128, kBP, 2, 2, kPatchSlots, 2, true>(a, st);
         if (a.big_patch) return launch_one<T, 128, kBP, 2, 2, kBigSlots, 2, false>(a, st);

@@ -272,6 +272,48 @@ frag_pack_kernel(const unsigned char *__restrict__ packed, unsigned char *__rest
     }
 }
 
+// Row-tiled convolution with the pool in its epilogue: a pooling window that straddles two row tiles
+// was left as two partial rows, [n][boundary][part][Qo][K]; their maximum is row
+// (boundary's first row of the lower tile - 1) / 2 of the pooled tensor.  16 bytes per thread.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+pool_fixup_kernel(const char *__restrict__ part, char *__restrict__ y, int N, int Po, int Qo, int Kbytes, int tile_rows,
+                  int tiles_img) {
+    typedef int v4i __attribute__((ext_vector_type(4)));
+    const int kc = Kbytes / 16;
+    const size_t total = (size_t)N * (tiles_img - 1) * Qo * kc;
+    const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += nthreads) {
+        const int c = (int)(idx % kc);
+        size_t t = idx / kc;
+        const int oq = (int)(t % Qo);
+        t /= Qo;
+        const int b = (int)(t % (tiles_img - 1)), n = (int)(t / (tiles_img - 1));
+        const int orow = ((b + 1) * tile_rows - 1) / 2;
+        if (orow >= Po) continue;
+        const char *p0 = part + ((((size_t)n * (tiles_img - 1) + b) * 2 + 0) * Qo + oq) * Kbytes + (size_t)c * 16;
+        const char *p1 = p0 + (size_t)Qo * Kbytes;
+        const v4i a0 = *reinterpret_cast<const v4i *>(p0), a1 = *reinterpret_cast<const v4i *>(p1);
+        v4i o;
+        if constexpr (sizeof(T) == 1) {
+            typedef short v2s __attribute__((ext_vector_type(2)));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned w0 = (unsigned)a0[u], w1 = (unsigned)a1[u];
+                const v2s me = __builtin_elementwise_max(__builtin_bit_cast(v2s, (w0 << 8) & 0xff00ff00u),
+                                                         __builtin_bit_cast(v2s, (w1 << 8) & 0xff00ff00u));
+                const v2s mo = __builtin_elementwise_max(__builtin_bit_cast(v2s, w0 & 0xff00ff00u),
+                                                         __builtin_bit_cast(v2s, w1 & 0xff00ff00u));
+                o[u] = (int)((__builtin_bit_cast(unsigned, mo) & 0xff00ff00u) | ((__builtin_bit_cast(unsigned, me) >> 8) & 0x00ff00ffu));
+            }
+        } else {
+            typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+            o = __builtin_bit_cast(v4i, __builtin_elementwise_max(__builtin_bit_cast(v8h, a0), __builtin_bit_cast(v8h, a1)));
+        }
+        *reinterpret_cast<v4i *>(y + (((size_t)n * Po + orow) * Qo + oq) * Kbytes + (size_t)c * 16) = o;
+    }
+}
+
 // fp16, 8 channels (16 bytes) per thread, same mapping as the int8 kernel above.
 __global__ void __launch_bounds__(kThreads)
 maxpool_f16x8_kernel(const _Float16 *__restrict__ x, _Float16 *__restrict__ y, int N, int H, int W, int C,
@@ -375,6 +417,22 @@ hipError_t launch_pad_channels(const void *x, void *xp, int N, int H, int W, int
     else
         pad_channels_kernel<int16_t><<<grid, kThreads, 0, st>>>((const int16_t *)x, (int16_t *)xp, N, H, W,
                                                                 C, Wp, Cpad, (int16_t)fill);
+    return hipGetLastError();
+}
+
+hipError_t launch_pool_fixup(const void *part, void *y_pool, int N, int Po, int Qo, int K, int tile_rows, int tiles_img,
+                             int dtype, hipStream_t st) {
+    if (tiles_img < 2 || N == 0) return hipSuccess;
+    const int es = dtype == MPQ_INT8 ? 1 : 2;
+    const int Kbytes = K * es;
+    if (Kbytes % 16 != 0) return hipErrorInvalidValue;
+    const size_t total = (size_t)N * (tiles_img - 1) * Qo * (Kbytes / 16);
+    if (dtype == MPQ_INT8)
+        pool_fixup_kernel<int8_t><<<grid_for(total, kThreads), kThreads, 0, st>>>((const char *)part, (char *)y_pool, N, Po, Qo,
+                                                                                Kbytes, tile_rows, tiles_img);
+    else
+        pool_fixup_kernel<_Float16><<<grid_for(total, kThreads), kThreads, 0, st>>>((const char *)part, (char *)y_pool, N, Po,
+                                                                                  Qo, Kbytes, tile_rows, tiles_img);
     return hipGetLastError();
 }
 

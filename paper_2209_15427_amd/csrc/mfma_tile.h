@@ -158,12 +158,13 @@ __device__ __forceinline__ bool decode_tile(const ConvArgs &a, TileCtx &t) {
     t.bias = (const char *)a.bias;
     t.epi = a.epi;
     if (a.tile_px) {
-        // image-aligned tiles: pixel tile pt is image pt (tile_px = P Q <= BP pixels; not used with
-        // expert-grouped launches)
-        t.m0 = t.m_begin = pt * a.tile_px;
-        t.m_end = t.m0 + a.tile_px;
+        // image-aligned tiles: tile tt of image n is tile_px pixels (whole rows, <= BP; the image's
+        // last tile may be shorter); not used with expert-grouped launches
+        const int n = a.tiles_img > 1 ? pt / a.tiles_img : pt, tt = pt - n * a.tiles_img;
+        t.m0 = t.m_begin = n * PQ + tt * a.tile_px;
+        t.m_end = min(t.m0 + a.tile_px, (n + 1) * PQ);
         t.ch0 = ct * BC;
-        return pt < a.N;
+        return n < a.N;
     }
     if (a.seg.offsets) {
         int e = 0, tile_base = 0;
@@ -328,22 +329,43 @@ struct Tile {
         constexpr int CHUNK_ELEMS = 16 / ES;
         char *yb = (char *)a.y;
         if constexpr (POOL) {
-            const int PoQo = a.Po * a.Qo, n = m0 / a.tile_px;
-            for (int idx = tid; idx < PoQo * CH16; idx += kThreads) {
-                const int op = idx / CH16, c16 = idx % CH16;
+            // The tile holds convolution rows r0 .. r0 + rt - 1 of image n.  Pooling window i (rows
+            // 2 i .. 2 i + 2) is written to the pooled tensor when the tile holds all three rows;
+            // a window that straddles two row tiles leaves the maximum over the rows it has here in
+            // pool_part (part 0: the window starts in this tile, part 1: it ends here), and a small
+            // kernel takes the maximum of the two parts.
+            const int PQ = a.P * a.Q, PoQo = a.Po * a.Qo;
+            const int n = m0 / PQ, r0 = (m0 - n * PQ) / a.Q, rt = (m_end - m0) / a.Q;
+            const int tt = a.tiles_img > 1 ? (m0 - n * PQ) / a.tile_px : 0;
+            const int i_lo = r0 >= 2 ? (r0 - 1) / 2 : 0;
+            const int i_hi = min(a.Po - 1, (r0 + rt - 1) / 2);
+            const int per_win = a.Qo * CH16;
+            for (int idx = tid; idx < (i_hi - i_lo + 1) * per_win; idx += kThreads) {
+                const int oqc = idx / CH16, c16 = idx % CH16;               // (CH16 is a power of two)
+                const int wdx = (int)udiv_magic((unsigned)oqc, a.magic_qo), oq = oqc - wdx * a.Qo;
                 const int ch = ch0 + c16 * CHUNK_ELEMS;
                 if (ch >= pl.Kg) continue;
-                const int orow = op / a.Qo, oq = op - orow * a.Qo;
+                const int orow = i_lo + wdx;
+                const int rlo = max(2 * orow, r0) - r0, rhi = min(2 * orow + 2, r0 + rt - 1) - r0;   // tile-local rows
                 MaxAcc<T> mx;
 #pragma unroll
                 for (int r = 0; r < 3; ++r)
+                    if (rlo + r <= rhi) {
 #pragma unroll
-                    for (int sx = 0; sx < 3; ++sx) {
-                        const int row = (2 * orow + r) * a.Q + 2 * oq + sx;
-                        mx.add(*reinterpret_cast<const v4i *>(lds + row * ROWB + ((c16 ^ (row & (CH16 - 1))) << 4)));
+                        for (int sx = 0; sx < 3; ++sx) {
+                            const int row = (rlo + r) * a.Q + 2 * oq + sx;
+                            mx.add(*reinterpret_cast<const v4i *>(lds + row * ROWB + ((c16 ^ (row & (CH16 - 1))) << 4)));
+                        }
                     }
                 const v4i v = mx.get();
-                char *dst = yb + (((size_t)n * PoQo + op) * a.K + (size_t)(g * pl.Kg + ch)) * ES;
+                char *dst;
+                if (rhi - rlo == 2) {
+                    dst = yb + (((size_t)n * PoQo + (size_t)orow * a.Qo + oq) * a.K + (size_t)(g * pl.Kg + ch)) * ES;
+                } else {
+                    const int part = 2 * orow >= r0 ? 0 : 1, bnd = part == 0 ? tt : tt - 1;
+                    dst = (char *)a.pool_part +
+                          (((((size_t)n * (a.tiles_img - 1) + bnd) * 2 + part) * a.Qo + oq) * a.K + (size_t)(g * pl.Kg + ch)) * ES;
+                }
                 if (a.y_vec16 && ch + CHUNK_ELEMS <= pl.Kg) {
                     *reinterpret_cast<v4i *>(dst) = v;
                 } else {

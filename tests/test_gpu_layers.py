@@ -145,6 +145,9 @@ CONV_CASES = [
     (2, 4, 20, 20, 32, 8, 8, 4, 0, 1, False, (0, 0), 3, 0, -2),        # row path, C = 4, general requantize
     (1, 3, 15, 15, 8, 7, 7, 4, 0, 1, True, (0, 0), 0, 0, 0),           # row path, one short strip, 675-byte tensor
     (5, 3, 67, 51, 64, 11, 11, 4, 0, 1, True, (3, 2), 0, 0, 0),        # row path, several strips per image, ragged last strip
+    (2, 32, 20, 21, 64, 3, 3, 1, 1, 1, True, (3, 2), 0, 0, 0),         # pool in the epilogue of row tiles: 2 tiles of 10 rows, 64-channel tiles
+    (2, 64, 17, 30, 128, 3, 3, 1, 1, 1, True, (3, 2), 0, 0, 4),        # row tiles 6 + 6 + 5 rows, 64-byte channel blocks, z_y != 0
+    (3, 48, 27, 27, 200, 5, 5, 1, 2, 1, False, (3, 2), 0, 0, 0),       # row tiles 3 x 9 rows, ragged channels, no ReLU
 ]
 
 
@@ -181,8 +184,8 @@ def test_conv_is_deterministic():
 # ---------------------------------------------------------------------------------------------
 # fp16 convolution
 # ---------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("case", [CONV_CASES[i] for i in (0, 1, 2, 3, 5, 7, 8, 11, 12)],
-                         ids=["c0", "c1", "c2", "c3", "c5", "c7", "c8", "c11", "c12"])
+@pytest.mark.parametrize("case", [CONV_CASES[i] for i in (0, 1, 2, 3, 5, 7, 8, 11, 12, 19, 20)],
+                         ids=["c0", "c1", "c2", "c3", "c5", "c7", "c8", "c11", "c12", "c19", "c20"])
 def test_fp16_conv(case):
     _say("fp16 conv", case)
     N, C, H, W, K, R, S, stride, pad, groups, relu, pool = case[:12]
