@@ -74,6 +74,19 @@ Plan make_plan(const mpq_conv_desc &d, int dtype, int in_w) {
             }
         }
     }
+    // int16: digit planes for the int8 kernels (an int32 partial sum holds 2^16 products of a byte
+    // with an unsigned byte)
+    if (dtype == MPQ_INT16 && p.Kdim < 65536) {
+        const Plan p8 = make_plan(d, MPQ_INT8, in_w);
+        if (p8.mode != kModeGeneric && p8.Kg % 4 == 0) {
+            p.dg_off = p.total;
+            p.dg_stride = round_up(p8.total, 256);
+            p.dg_tmp_off = p.dg_off + 3 * p.dg_stride;
+            p.dg_tmp_stride = round_up((size_t)d.k * p.Kdim, 256);
+            p.dg_tap_off = p.dg_tmp_off + 3 * p.dg_tmp_stride;
+            p.total = p.dg_tap_off + round_up((size_t)d.k * (d.r + 1) * (d.s + 1) * 4, 256);
+        }
+    }
     return p;
 }
 
@@ -152,6 +165,9 @@ mpq_status build_epi(int in_dtype, int out_dtype, const mpq_qparams &xq, const m
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) % 16) == 0; }
 
+// (the optional tail of a workspace is used when the caller passed the full size)
+bool fc_ws_ok(const void *ws, size_t ws_bytes, size_t total) { return ws != nullptr && ws_bytes >= total && aligned16(ws); }
+
 struct Geometry {
     int P, Q;      // convolution output
     int Po, Qo;    // after pooling
@@ -178,8 +194,22 @@ struct WsLayout {
     size_t mid_off, mid_bytes;    // unpooled convolution output
     size_t pp_off, pp_bytes;      // row-tiled convolution with the pool in its epilogue: windows that straddle two tiles
     size_t fc_off, fc_bytes;      // fully-connected layer: x in fragment order + partial sums
+    // int16 layer run as int8 digit planes: the two planes of x, six int32 partial convolutions,
+    // and the workspace of one int8 convolution
+    size_t dg_off, dg_bytes, dg_x_stride, dg_raw_off, dg_raw_stride, dg_sub_off, dg_sub_bytes;
     size_t total;
 };
+
+// Below this many multiply-accumulates a digit-plane run (ten launches) loses to the direct kernel.
+constexpr long long kDigitMinMacs = 1ll << 24;
+
+mpq_conv_desc digit_desc(const mpq_conv_desc &d) {
+    mpq_conv_desc d8 = d;
+    d8.pool_k = 0;
+    d8.pool_s = 0;
+    d8.relu = 0;
+    return d8;
+}
 
 // (num_experts > 0: the rows are expert-grouped, row groups are padded per expert)
 WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, const Geometry &g,
@@ -213,8 +243,67 @@ WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, 
         w.fc_bytes = fs.xf_bytes + fs.part_bytes;
         off += w.fc_bytes;
     }
+    const long long macs = (long long)x.n * g.P * g.Q * d.k * pl.Kdim;
+    if (pl.dg_stride > 0 && out_dtype == MPQ_INT16 && num_experts == 0 && macs >= kDigitMinMacs) {
+        mpq_tensor x8 = x;
+        x8.dtype = MPQ_INT8;
+        const mpq_conv_desc d8 = digit_desc(d);
+        Geometry g8 = g;
+        g8.Po = g.P;
+        g8.Qo = g.Q;
+        const WsLayout sub = ws_layout(x8, d8, make_plan(d8, MPQ_INT8, x.w), g8, MPQ_INT32);
+        w.dg_off = off;
+        w.dg_x_stride = round_up((size_t)x.n * x.h * x.w * x.c, 256);
+        w.dg_raw_off = 2 * w.dg_x_stride;
+        w.dg_raw_stride = round_up((size_t)x.n * g.P * g.Q * d.k * 4, 256);
+        w.dg_sub_off = w.dg_raw_off + 6 * w.dg_raw_stride;
+        w.dg_sub_bytes = sub.total;
+        w.dg_bytes = w.dg_sub_off + round_up(sub.total, 256);
+        off += w.dg_bytes;
+    }
     w.total = off;
     return w;
+}
+
+mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias, void *y_data,
+                    int y_dtype, const mpq_conv_desc &d, const Epi &epi, const SegTable *seg,
+                    void *ws, size_t ws_bytes, hipStream_t st);
+
+// An int16 convolution as six int8 convolutions of digit planes (conv_i16.hip) plus the int64
+// recombination with the layer's epilogue; conv_out receives the unpooled int16 result.
+mpq_status run_conv_digits(const mpq_tensor &x, const void *w_packed, const void *bias, void *conv_out,
+                           const mpq_conv_desc &d, const Epi &epi, const Plan &pl, const Geometry &g,
+                           const WsLayout &wl, char *wsb, hipStream_t st) {
+    char *dg = wsb + wl.dg_off;
+    const size_t count = (size_t)x.n * x.h * x.w * x.c;
+    if (launch_i16_split_x(x.data, dg, dg + wl.dg_x_stride, count, st) != hipSuccess) return MPQ_ERR_DEVICE;
+    const mpq_conv_desc d8 = digit_desc(d);
+    Epi e8;
+    std::memset(&e8, 0, sizeof(e8));
+    e8.kind = kEpiRawI32;
+    e8.sb = 31;
+    const char *wp = reinterpret_cast<const char *>(w_packed);
+    for (int xd = 0; xd < 2; ++xd) {
+        mpq_tensor x8 = x;
+        x8.data = dg + xd * wl.dg_x_stride;
+        x8.dtype = MPQ_INT8;
+        for (int wd = 0; wd < 3; ++wd) {
+            void *raw = dg + wl.dg_raw_off + (size_t)(xd * 3 + wd) * wl.dg_raw_stride;
+            mpq_status s = run_conv(x8, wp + pl.dg_off + wd * pl.dg_stride, nullptr, raw, MPQ_INT32, d8, e8, nullptr,
+                                    wl.dg_sub_bytes ? dg + wl.dg_sub_off : nullptr, wl.dg_sub_bytes, st);
+            if (s != MPQ_OK) return s;
+        }
+    }
+    I16Combine cb;
+    cb.wsum = reinterpret_cast<const int *>(wp + pl.wsum_off);
+    cb.tappre = reinterpret_cast<const int *>(wp + pl.dg_tap_off);
+    cb.K = d.k; cb.P = g.P; cb.Q = g.Q; cb.H = x.h; cb.W = x.w; cb.R = d.r; cb.S = d.s;
+    cb.stride_h = d.stride_h; cb.stride_w = d.stride_w; cb.pad_h = d.pad_h; cb.pad_w = d.pad_w;
+    const size_t total = (size_t)x.n * g.P * g.Q * d.k;
+    if (launch_i16_combine(reinterpret_cast<const int *>(dg + wl.dg_raw_off), wl.dg_raw_stride / 4, (const int *)bias,
+                           conv_out, total, cb, epi, st) != hipSuccess)
+        return MPQ_ERR_DEVICE;
+    return MPQ_OK;
 }
 
 // Everything mpq_conv2d and the MoE layer loop need to launch one convolution.
@@ -227,9 +316,9 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     Plan pl = make_plan(d, x.dtype, x.w);
     WsLayout wl = ws_layout(x, d, pl, g, y_dtype, seg ? seg->num_experts : 0);
     // (the fully-connected scratch is optional: without it the layer runs on the kernels that need none)
-    const size_t ws_required = wl.fc_bytes > 0 ? wl.fc_off : wl.total;
+    const size_t ws_required = wl.dg_bytes > 0 ? wl.dg_off : wl.fc_bytes > 0 ? wl.fc_off : wl.total;
     if (ws_required > 0 && (ws == nullptr || ws_bytes < ws_required || !aligned16(ws))) return MPQ_ERR_WORKSPACE;
-    const bool fc_ws = wl.fc_bytes > 0 && ws != nullptr && ws_bytes >= wl.total && aligned16(ws);
+    const bool fc_ws = wl.fc_bytes > 0 && fc_ws_ok(ws, ws_bytes, wl.total);
     if ((long long)x.n * g.P * g.Q > 0x7ffffc00ll) return MPQ_ERR_UNSUPPORTED;
 
     ConvArgs a;
@@ -263,9 +352,17 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     if (seg && seg->w_stride % 256 != 0) use_mfma = false;
 
     hipError_t err = hipSuccess;
+    // int16 on the matrix cores: byte-digit planes through the int8 kernels.  Needs the optional part
+    // of the workspace and no weight zero-point.
+    const bool digits = wl.dg_bytes > 0 && !seg && fc_ws_ok(ws, ws_bytes, wl.total) && epi.kind == kEpiRequant &&
+                        epi.zw == 0 && aligned16(x.data) &&
+                        aligned16(w_packed) && aligned16(conv_out) && (bias == nullptr || aligned16(bias));
     if (!seg && gemv_eligible(a) && (a.N < 4 || a.K <= 16)) {
         // batch < 4 (or <= 16 outputs): memory-bound, one pass over the larger matrix on the dot units
         err = launch_gemv(a, st);
+    } else if (digits) {
+        s = run_conv_digits(x, w_packed, bias, conv_out, d, epi, pl, g, wl, wsb, st);
+        if (s != MPQ_OK) return s;
     } else if (fc_ws && d.pool_k == 0 && fc_frag_eligible(a)) {
         // a matrix product on 4..512 rows (or an expert's rows): fragment-ordered operands, the
         // reduction axis split over workgroups
@@ -439,7 +536,21 @@ mpq_status mpq_pack_weights(const void *w_kcrs, const mpq_conv_desc *d, mpq_dtyp
     Plan p = make_plan(*d, dtype, 0);
     if (packed_bytes < p.total) return MPQ_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(packed) % 256 != 0) return MPQ_ERR_WORKSPACE;
-    return launch_pack(w_kcrs, packed, *d, p, dtype, (hipStream_t)stream) == hipSuccess ? MPQ_OK : MPQ_ERR_DEVICE;
+    hipStream_t st = (hipStream_t)stream;
+    if (launch_pack(w_kcrs, packed, *d, p, dtype, st) != hipSuccess) return MPQ_ERR_DEVICE;
+    if (p.dg_stride > 0) {
+        // int16: the three byte-digit planes, each packed as an int8 layer of the same shape
+        char *pk = reinterpret_cast<char *>(packed);
+        if (launch_i16_split_w(w_kcrs, pk + p.dg_tmp_off, (size_t)d->k * p.Kdim, p.dg_tmp_stride, st) != hipSuccess ||
+            launch_i16_tappre(w_kcrs, reinterpret_cast<int *>(pk + p.dg_tap_off), d->k, p.Cg, d->r, d->s, st) != hipSuccess)
+            return MPQ_ERR_DEVICE;
+        const Plan p8 = make_plan(*d, MPQ_INT8, 0);
+        for (int wd = 0; wd < 3; ++wd)
+            if (launch_pack(pk + p.dg_tmp_off + wd * p.dg_tmp_stride, pk + p.dg_off + wd * p.dg_stride, *d, p8, MPQ_INT8,
+                            st) != hipSuccess)
+                return MPQ_ERR_DEVICE;
+    }
+    return MPQ_OK;
 }
 
 size_t mpq_conv2d_workspace_bytes(const mpq_tensor *x, const mpq_conv_desc *d) {

@@ -56,6 +56,12 @@ struct Plan {
     // l % 32 of the tile, chunk 2 * half + l / 32 of the step (zeros past the last tap / row).
     int f_cbc, f_nphase, f_ksp, f_rt;   // f_rt: 32-row tiles per group
     size_t frag_off, frag_bytes;
+    // int16 layers whose shape the int8 matrix-core kernels accept also carry the weights as three
+    // int8 digit planes (high byte, low byte / 2, lowest bit), each packed by the layer's int8 plan,
+    // dg_stride bytes apart from dg_off (dg_stride = 0: none); dg_tmp_off: the planes in KCRS order,
+    // dg_tmp_stride apart, which the packing reads;
+    // dg_tap_off: int32 [K][(R + 1)(S + 1)] prefix sums over taps of the int16 weights.
+    size_t dg_off, dg_stride, dg_tmp_off, dg_tmp_stride, dg_tap_off;
 };
 
 // Epilogue selector + constants (per tensor; per expert in the MoE launches).
@@ -143,6 +149,17 @@ hipError_t launch_to_fp16(const float *src, void *dst, size_t n, hipStream_t st)
 hipError_t launch_from_fp16(const void *src, float *dst, size_t n, hipStream_t st);
 hipError_t launch_pack(const void *w_kcrs, void *packed, const mpq_conv_desc &d, const Plan &p,
                        int dtype, hipStream_t st);
+hipError_t launch_i16_split_w(const void *w16, void *planes, size_t count, size_t plane_stride, hipStream_t st);
+hipError_t launch_i16_split_x(const void *x16, void *hi, void *lo, size_t count, hipStream_t st);
+// geometry and weight-sum tables the recombination of an int16 layer's digit-plane convolutions needs
+struct I16Combine {
+    const int *wsum;      // [K] sum of a channel's int16 weights
+    const int *tappre;    // [K][(R + 1)(S + 1)] prefix sums of the same per tap
+    int K, P, Q, H, W, R, S, stride_h, stride_w, pad_h, pad_w;
+};
+hipError_t launch_i16_tappre(const void *w16, int *tappre, int K, int Cg, int R, int S, hipStream_t st);
+hipError_t launch_i16_combine(const int *raw, size_t raw_stride, const int *bias, void *y, size_t total,
+                              const I16Combine &g, const Epi &epi, hipStream_t st);
 hipError_t launch_pad_channels(const void *x, void *xp, int N, int H, int W, int C, int Wp, int Cpad,
                                int esize, int fill, hipStream_t st);
 hipError_t launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int k, int s, int dtype,

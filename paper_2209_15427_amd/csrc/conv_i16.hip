@@ -1,0 +1,180 @@
+// int16 layers on the int8 matrix cores, exactly (the int16 x int16 -> int64 accumulation of
+// section "Quantized Operations").  Both operands are cut into byte digits whose int8 products the
+// int8 kernels accumulate in int32, and the six partial convolutions are recombined in int64:
+//
+//   x = 256 xh + xl            xh = x >> 8 in [-128, 127],  xl = x & 255 in [0, 255]
+//   w = 256 wh + 2 wm + wb     wh = w >> 8,  wm = (w & 255) >> 1 in [0, 127],  wb = w & 1
+//
+// The low byte of x is stored as xl' = xl - 128; the weight digits need no offset, so no per-pixel
+// input sums appear.  With C(.,.) the zero-padded int8 convolution of two digit planes and V the
+// sum of the int16 weights over the taps that fall inside the image (a per-channel constant away
+// from the border, a sum of per-tap weight sums on it):
+//   sum (x - z_x) w = 65536 C(xh,wh) + 512 C(xh,wm) + 256 [C(xh,wb) + C(xl',wh)] + 2 C(xl',wm)
+//                     + C(xl',wb) + (128 - z_x) V
+// This file holds the digit splits, the weight-sum table and the recombination with the layer's
+// epilogue; the convolutions themselves are the int8 kernels.
+#include "common.h"
+#include "epilogue.h"
+
+namespace mpq {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// weights, KCRS order: three int8 planes, plane_stride bytes apart
+__global__ void __launch_bounds__(kThreads) i16_split_w_kernel(const int16_t *__restrict__ w, int8_t *__restrict__ planes,
+                                                               size_t count, size_t plane_stride) {
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * kThreads;
+    for (; i < count; i += step) {
+        const int v = w[i];
+        const int lo = v & 255;
+        planes[i] = (int8_t)(v >> 8);
+        planes[plane_stride + i] = (int8_t)(lo >> 1);
+        planes[2 * plane_stride + i] = (int8_t)(lo & 1);
+    }
+}
+
+// activations: high bytes and (low byte - 128); eight elements per thread, the tail one by one
+__global__ void __launch_bounds__(kThreads) i16_split_x_kernel(const int16_t *__restrict__ x, int8_t *__restrict__ hi,
+                                                               int8_t *__restrict__ lo, size_t count) {
+    const size_t vecs = count / 8;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * kThreads;
+    for (size_t v = i; v < vecs; v += step) {
+        const uint4 q = reinterpret_cast<const uint4 *>(x)[v];
+        const unsigned d[4] = {q.x, q.y, q.z, q.w};
+        unsigned h[2], l[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            // bytes 1 and 3 of each dword are the high bytes, 0 and 2 the low bytes
+            h[j] = __builtin_amdgcn_perm(d[2 * j + 1], d[2 * j], 0x07050301u);
+            l[j] = __builtin_amdgcn_perm(d[2 * j + 1], d[2 * j], 0x06040200u) ^ 0x80808080u;
+        }
+        reinterpret_cast<uint2 *>(hi)[v] = make_uint2(h[0], h[1]);
+        reinterpret_cast<uint2 *>(lo)[v] = make_uint2(l[0], l[1]);
+    }
+    for (size_t e = vecs * 8 + i; e < count; e += step) {
+        const int v = x[e];
+        hi[e] = (int8_t)(v >> 8);
+        lo[e] = (int8_t)((v & 255) - 128);
+    }
+}
+
+// two-dimensional prefix sums of the per-tap weight sums:
+// tappre[k][r * (S + 1) + s] = sum over r' < r, s' < s, c of w[k][c][r'][s']   (r <= R, s <= S),
+// so that the weight sum over any clipped window of taps is four table entries
+__global__ void __launch_bounds__(kThreads) i16_tappre_kernel(const int16_t *__restrict__ w, int *__restrict__ tappre,
+                                                              int K, int Cg, int R, int S) {
+    const int per_k = (R + 1) * (S + 1);
+    const int i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= K * per_k) return;
+    const int k = i / per_k, t = i % per_k;
+    const int r_end = t / (S + 1), s_end = t % (S + 1);
+    const int16_t *wk = w + (size_t)k * Cg * R * S;
+    int sum = 0;
+    for (int c = 0; c < Cg; ++c)
+        for (int r = 0; r < r_end; ++r)
+            for (int sx = 0; sx < s_end; ++sx) sum += wk[((size_t)c * R + r) * S + sx];
+    tappre[i] = sum;
+}
+
+// t = the formula above + bias, then the layer's rescale; raw[j] is the j-th partial convolution
+// in the formula's order (hh, hm, hb, lh, lm, lb)
+template <int V>
+__global__ void __launch_bounds__(kThreads) i16_combine_kernel(const int *__restrict__ raw, size_t raw_stride,
+                                                               const int *__restrict__ bias, int16_t *__restrict__ y,
+                                                               size_t total, I16Combine g, Epi epi) {
+    const int K = g.K;
+    const int S1 = g.S + 1, per_k = (g.R + 1) * S1;
+    size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * V;
+    const size_t step = (size_t)gridDim.x * kThreads * V;
+    for (; i < total; i += step) {
+        // taps of this output pixel that lie inside the image
+        const size_t m = i / (size_t)K;
+        const int q = (int)(m % (size_t)g.Q), p = (int)((m / (size_t)g.Q) % (size_t)g.P);
+        const int h0 = p * g.stride_h - g.pad_h, w0 = q * g.stride_w - g.pad_w;
+        // (clamped to the table for windows that lie wholly in the padding)
+        const int r_lo = min(max(-h0, 0), g.R), r_hi = min(max(g.H - h0, r_lo), g.R);
+        const int s_lo = min(max(-w0, 0), g.S), s_hi = min(max(g.W - w0, s_lo), g.S);
+        const bool interior = r_lo == 0 && s_lo == 0 && r_hi == g.R && s_hi == g.S;
+        int c[6][V];
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            if constexpr (V == 4) {
+                const int4 q = *reinterpret_cast<const int4 *>(raw + j * raw_stride + i);
+                c[j][0] = q.x; c[j][1] = q.y; c[j][2] = q.z; c[j][3] = q.w;
+            } else {
+                c[j][0] = raw[j * raw_stride + i];
+            }
+        }
+        const int k0 = (int)(i % (size_t)K);
+        int16_t out[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            long long t = ((long long)c[0][e] << 16) + ((long long)c[1][e] << 9) +
+                          (((long long)c[2][e] + (long long)c[3][e]) << 8) + ((long long)c[4][e] << 1) + (long long)c[5][e];
+            const int k = k0 + e;
+            long long v;
+            if (interior) {
+                v = g.wsum[k];
+            } else {
+                const int *pre = g.tappre + (size_t)k * per_k;
+                v = (long long)pre[r_hi * S1 + s_hi] - pre[r_lo * S1 + s_hi] - pre[r_hi * S1 + s_lo] + pre[r_lo * S1 + s_lo];
+            }
+            t += (long long)(128 - epi.zx) * v;
+            if (bias) t += (long long)bias[k];
+            out[e] = (int16_t)requant64(t, epi);
+        }
+        if constexpr (V == 4) {
+            uint2 o;
+            o.x = (unsigned)(unsigned short)out[0] | ((unsigned)(unsigned short)out[1] << 16);
+            o.y = (unsigned)(unsigned short)out[2] | ((unsigned)(unsigned short)out[3] << 16);
+            *reinterpret_cast<uint2 *>(y + i) = o;
+        } else {
+            y[i] = out[0];
+        }
+    }
+}
+
+int grid_of(size_t items) {
+    size_t b = (items + kThreads - 1) / kThreads;
+    if (b > 256 * 32) b = 256 * 32;
+    return b < 1 ? 1 : (int)b;
+}
+
+}  // namespace
+
+hipError_t launch_i16_split_w(const void *w16, void *planes, size_t count, size_t plane_stride, hipStream_t st) {
+    if (count == 0) return hipSuccess;
+    i16_split_w_kernel<<<grid_of(count), kThreads, 0, st>>>((const int16_t *)w16, (int8_t *)planes, count, plane_stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_i16_split_x(const void *x16, void *hi, void *lo, size_t count, hipStream_t st) {
+    if (count == 0) return hipSuccess;
+    i16_split_x_kernel<<<grid_of((count + 7) / 8), kThreads, 0, st>>>((const int16_t *)x16, (int8_t *)hi, (int8_t *)lo, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_i16_tappre(const void *w16, int *tappre, int K, int Cg, int R, int S, hipStream_t st) {
+    const long long items = (long long)K * (R + 1) * (S + 1);
+    if (items == 0) return hipSuccess;
+    if (items > 0x7fffffffll) return hipErrorInvalidValue;
+    i16_tappre_kernel<<<(unsigned)((items + kThreads - 1) / kThreads), kThreads, 0, st>>>((const int16_t *)w16, tappre, K, Cg, R, S);
+    return hipGetLastError();
+}
+
+hipError_t launch_i16_combine(const int *raw, size_t raw_stride, const int *bias, void *y, size_t total,
+                              const I16Combine &g, const Epi &epi, hipStream_t st) {
+    if (total == 0) return hipSuccess;
+    // (four outputs per thread need the channel count, hence every row start, to be a multiple of 4)
+    if (g.K % 4 == 0 && raw_stride % 4 == 0)
+        i16_combine_kernel<4><<<grid_of(total / 4), kThreads, 0, st>>>(raw, raw_stride, bias, (int16_t *)y, total, g, epi);
+    else
+        i16_combine_kernel<1><<<grid_of(total), kThreads, 0, st>>>(raw, raw_stride, bias, (int16_t *)y, total, g, epi);
+    return hipGetLastError();
+}
+
+}  // namespace mpq

@@ -314,18 +314,19 @@ pool_fixup_kernel(const char *__restrict__ part, char *__restrict__ y, int N, in
     }
 }
 
-// fp16, 8 channels (16 bytes) per thread, same mapping as the int8 kernel above.
+// fp16 or int16, 8 channels (16 bytes) per thread, same mapping as the int8 kernel above.
+template <typename T>
 __global__ void __launch_bounds__(kThreads)
-maxpool_f16x8_kernel(const _Float16 *__restrict__ x, _Float16 *__restrict__ y, int N, int H, int W, int C,
-                     int P, int Q, int k, int st) {
-    typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+maxpool_x8_kernel(const T *__restrict__ x, T *__restrict__ y, int N, int H, int W, int C,
+                  int P, int Q, int k, int st) {
+    typedef T v8h __attribute__((ext_vector_type(8)));
     const int np = blockIdx.x;
     const int n = np / P, p = np - n * P;
     const int c = threadIdx.x;
-    const _Float16 *row0 = x + (((size_t)n * H + (size_t)p * st) * W) * C + c * 8;
-    _Float16 *out = y + ((size_t)np * Q) * C + c * 8;
+    const T *row0 = x + (((size_t)n * H + (size_t)p * st) * W) * C + c * 8;
+    T *out = y + ((size_t)np * Q) * C + c * 8;
     for (int q = threadIdx.y; q < Q; q += blockDim.y) {
-        const _Float16 *base = row0 + (size_t)q * st * C;
+        const T *base = row0 + (size_t)q * st * C;
         v8h m = *reinterpret_cast<const v8h *>(base);
         for (int r = 0; r < k; ++r)
             for (int s = 0; s < k; ++s)
@@ -449,11 +450,15 @@ hipError_t launch_maxpool(const void *x, void *y, int N, int H, int W, int C, in
         if (k == 3) maxpool_i8x16_kernel<3><<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const int8_t *)x, (int8_t *)y, N, H, W, C, P, Q, k, s);
         else if (k == 2) maxpool_i8x16_kernel<2><<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const int8_t *)x, (int8_t *)y, N, H, W, C, P, Q, k, s);
         else maxpool_i8x16_kernel<0><<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const int8_t *)x, (int8_t *)y, N, H, W, C, P, Q, k, s);
-    } else if (dtype == MPQ_FP16 && C % 8 == 0 && C / 8 <= kThreads && aligned && (long long)N * P <= 0x7fffffffll) {
+    } else if ((dtype == MPQ_FP16 || dtype == MPQ_INT16) && C % 8 == 0 && C / 8 <= kThreads && aligned &&
+               (long long)N * P <= 0x7fffffffll) {
         const int cv = C / 8;
         int ty = kThreads / cv;
         if (ty > Q) ty = Q;
-        maxpool_f16x8_kernel<<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const _Float16 *)x, (_Float16 *)y, N, H, W, C, P, Q, k, s);
+        if (dtype == MPQ_FP16)
+            maxpool_x8_kernel<_Float16><<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const _Float16 *)x, (_Float16 *)y, N, H, W, C, P, Q, k, s);
+        else
+            maxpool_x8_kernel<short><<<(unsigned)(N * P), dim3(cv, ty), 0, st>>>((const short *)x, (short *)y, N, H, W, C, P, Q, k, s);
     } else if (dtype == MPQ_INT8) {
         maxpool_kernel<int8_t><<<grid_for(total, kThreads), kThreads, 0, st>>>((const int8_t *)x, (int8_t *)y,
                                                                              N, H, W, C, P, Q, k, s);

@@ -44,6 +44,19 @@ template <> struct Dot<int8_t> {
         return c;
     }
 };
+// int16: products reach 2^30, so every one goes straight into a 64-bit sum (exact)
+template <> struct Dot<int16_t> {
+    typedef long long Acc;
+    static __device__ __forceinline__ Acc run(v4i a, v4i b, Acc c) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ai = a[i], bi = b[i];
+            c += (long long)(short)(ai & 0xffff) * (long long)(short)(bi & 0xffff);
+            c += (long long)(ai >> 16) * (long long)(bi >> 16);
+        }
+        return c;
+    }
+};
 template <> struct Dot<_Float16> {
     typedef float Acc;
     static __device__ __forceinline__ Acc run(v4i a, v4i b, Acc c) {
@@ -111,7 +124,13 @@ __global__ void __launch_bounds__(kThreads) gemv_kernel(GemvArgs g) {
             const int row = g.swapped ? s : m;     // batch index
             const int n = g.swapped ? m : s;       // output feature
             const size_t o = (size_t)row * g.N + n;
-            if constexpr (sizeof(T) == 1) {
+            if constexpr (sizeof(Acc) == 8) {
+                long long t = v;
+                if (g.bias) t += (long long)((const int *)g.bias)[n];
+                if (g.epi.zx != 0) t -= (long long)g.epi.zx * (long long)g.wsum[n];
+                if (g.epi.kind == kEpiRawI32) ((int *)g.y)[o] = (int)t;
+                else ((int16_t *)g.y)[o] = (int16_t)requant64(t, g.epi);
+            } else if constexpr (sizeof(T) == 1) {
                 int t = v;
                 if (g.bias) t += ((const int *)g.bias)[n];
                 if (g.epi.zx != 0) t -= g.epi.zx * g.wsum[n];
@@ -153,8 +172,9 @@ hipError_t launch_nr(const GemvArgs &g, hipStream_t st) {
 
 bool gemv_eligible(const ConvArgs &a) {
     if (a.R != 1 || a.S != 1 || a.H != 1 || a.W != 1 || a.groups != 1) return false;
-    if (a.in_dtype != MPQ_INT8 && a.in_dtype != MPQ_FP16) return false;
-    if (a.in_dtype == MPQ_INT8 && a.epi.zw != 0) return false;
+    if (a.in_dtype != MPQ_INT8 && a.in_dtype != MPQ_INT16 && a.in_dtype != MPQ_FP16) return false;
+    if (a.in_dtype != MPQ_FP16 && a.epi.zw != 0) return false;
+    if (a.in_dtype == MPQ_INT16 && a.out_dtype != MPQ_INT16 && a.out_dtype != MPQ_INT32) return false;
     const int es = a.plan.esize;
     if (((size_t)a.C * es) % kChunkBytes != 0) return false;
     if ((reinterpret_cast<uintptr_t>(a.x) % 16) || (reinterpret_cast<uintptr_t>(a.w) % 16)) return false;
@@ -182,6 +202,7 @@ hipError_t launch_gemv(const ConvArgs &a, hipStream_t st) {
         g.resident = (const char *)a.w; g.nr = a.K; g.ld_r = ld_w;
     }
     if (a.in_dtype == MPQ_INT8) return launch_nr<int8_t>(g, st);
+    if (a.in_dtype == MPQ_INT16) return launch_nr<int16_t>(g, st);
     return launch_nr<_Float16>(g, st);
 }
 

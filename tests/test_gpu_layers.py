@@ -148,6 +148,9 @@ CONV_CASES = [
     (2, 32, 20, 21, 64, 3, 3, 1, 1, 1, True, (3, 2), 0, 0, 0),         # pool in the epilogue of row tiles: 2 tiles of 10 rows, 64-channel tiles
     (2, 64, 17, 30, 128, 3, 3, 1, 1, 1, True, (3, 2), 0, 0, 4),        # row tiles 6 + 6 + 5 rows, 64-byte channel blocks, z_y != 0
     (3, 48, 27, 27, 200, 5, 5, 1, 2, 1, False, (3, 2), 0, 0, 0),       # row tiles 3 x 9 rows, ragged channels, no ReLU
+    (6, 32, 16, 16, 64, 3, 3, 1, 0, 1, True, (0, 0), 9, 0, 3),         # z_x != 0 without padding (int16: digit planes + weight-sum term)
+    (4, 32, 14, 14, 128, 3, 3, 1, 1, 1, True, (0, 0), -77, 0, 11),     # z_x != 0 on a padded layer (int16: per-tap weight sums on the border)
+    (8, 32, 31, 33, 72, 3, 3, 2, 1, 1, False, (2, 2), 0, 0, -5),       # stride 2, 72 channels, 2x2 pool (int16: digit planes)
 ]
 
 
@@ -157,7 +160,12 @@ def test_int8_conv(case):
     _int_conv_case(mb.INT8, *case, seed=1000 + 17 * CONV_CASES.index(case))
 
 
-@pytest.mark.parametrize("case", [CONV_CASES[i] for i in (0, 3, 5, 8, 9)], ids=["c0", "c3", "c5", "c8", "c9"])
+# (int16 layers of at least 2^24 multiply-accumulates whose shape the int8 kernels accept run as
+# byte-digit planes on the matrix cores: c0, c1, c2, c10, c18, c22, c23, c24; the rest on the direct kernel)
+I16_CASES = (0, 1, 2, 3, 5, 8, 9, 10, 18, 22, 23, 24)
+
+
+@pytest.mark.parametrize("case", [CONV_CASES[i] for i in I16_CASES], ids=[f"c{i}" for i in I16_CASES])
 def test_int16_conv(case):
     _say("int16 conv", case)
     _int_conv_case(mb.INT16, *case, seed=2000 + 17 * CONV_CASES.index(case))
@@ -271,10 +279,12 @@ def test_int8_gemm_without_workspace(case):
     assert np.array_equal(y.cpu().numpy().astype(np.int32), o.requant(t, mult, 31, shift, 0, "int8", relu))
 
 
-def test_int16_gemm_accumulates_beyond_int32():
+@pytest.mark.parametrize("M,N", [(2, 3), (64, 96)], ids=["direct", "digit_planes"])
+def test_int16_gemm_accumulates_beyond_int32(M, N):
     K = 4096
-    x = np.full((2, K), 32767, np.int64)
-    w = np.stack([np.full(K, 32767), np.full(K, -32768), np.full(K, 11)]).astype(np.int64)
+    x = np.full((M, K), 32767, np.int64)
+    x[1::2] = -32768
+    w = np.stack([np.full(K, 32767), np.full(K, -32768), np.full(K, 11)] * (N // 3)).astype(np.int64)
     t = o.gemm_acc(x, 0, w, 0)
     assert abs(t).max() > 2 ** 31
     s = (np.float32(1e-3), np.float32(1e-3), np.float32(400.0))
