@@ -196,7 +196,9 @@ struct WsLayout {
     size_t fc_off, fc_bytes;      // fully-connected layer: x in fragment order + partial sums
     // int16 layer run as int8 digit planes: the two planes of x, six int32 partial convolutions,
     // and the workspace of one int8 convolution
-    size_t dg_off, dg_bytes, dg_x_stride, dg_raw_off, dg_raw_stride, dg_sub_off, dg_sub_bytes;
+    // (first-layer shape: dg_pad_stride > 0, the planes' channel-padded copies, made once for the three
+    // convolutions of each)
+    size_t dg_off, dg_bytes, dg_x_stride, dg_raw_off, dg_raw_stride, dg_sub_off, dg_sub_bytes, dg_pad_off, dg_pad_stride;
     size_t total;
 };
 
@@ -251,7 +253,8 @@ WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, 
         Geometry g8 = g;
         g8.Po = g.P;
         g8.Qo = g.Q;
-        const WsLayout sub = ws_layout(x8, d8, make_plan(d8, MPQ_INT8, x.w), g8, MPQ_INT32);
+        const Plan p8 = make_plan(d8, MPQ_INT8, x.w);
+        const WsLayout sub = ws_layout(x8, d8, p8, g8, MPQ_INT32);
         w.dg_off = off;
         w.dg_x_stride = round_up((size_t)x.n * x.h * x.w * x.c, 256);
         w.dg_raw_off = 2 * w.dg_x_stride;
@@ -259,6 +262,11 @@ WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, 
         w.dg_sub_off = w.dg_raw_off + 6 * w.dg_raw_stride;
         w.dg_sub_bytes = sub.total;
         w.dg_bytes = w.dg_sub_off + round_up(sub.total, 256);
+        if (p8.mode == kModeRow) {
+            w.dg_pad_off = w.dg_bytes;
+            w.dg_pad_stride = round_up((size_t)x.n * x.h * p8.Wp * p8.Cpad, 256);
+            w.dg_bytes += 2 * w.dg_pad_stride;
+        }
         off += w.dg_bytes;
     }
     w.total = off;
@@ -267,7 +275,7 @@ WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, 
 
 mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias, void *y_data,
                     int y_dtype, const mpq_conv_desc &d, const Epi &epi, const SegTable *seg,
-                    void *ws, size_t ws_bytes, hipStream_t st);
+                    void *ws, size_t ws_bytes, hipStream_t st, const void *row_padded = nullptr);
 
 // An int16 convolution as six int8 convolutions of digit planes (conv_i16.hip) plus the int64
 // recombination with the layer's epilogue; conv_out receives the unpooled int16 result.
@@ -287,10 +295,17 @@ mpq_status run_conv_digits(const mpq_tensor &x, const void *w_packed, const void
         mpq_tensor x8 = x;
         x8.data = dg + xd * wl.dg_x_stride;
         x8.dtype = MPQ_INT8;
+        const void *padded = nullptr;
+        if (wl.dg_pad_stride > 0) {
+            const Plan p8 = make_plan(d8, MPQ_INT8, x.w);
+            char *xp = dg + wl.dg_pad_off + xd * wl.dg_pad_stride;
+            if (launch_pad_channels(x8.data, xp, x.n, x.h, x.w, x.c, p8.Wp, p8.Cpad, 1, 0, st) != hipSuccess) return MPQ_ERR_DEVICE;
+            padded = xp;
+        }
         for (int wd = 0; wd < 3; ++wd) {
             void *raw = dg + wl.dg_raw_off + (size_t)(xd * 3 + wd) * wl.dg_raw_stride;
             mpq_status s = run_conv(x8, wp + pl.dg_off + wd * pl.dg_stride, nullptr, raw, MPQ_INT32, d8, e8, nullptr,
-                                    wl.dg_sub_bytes ? dg + wl.dg_sub_off : nullptr, wl.dg_sub_bytes, st);
+                                    wl.dg_sub_bytes ? dg + wl.dg_sub_off : nullptr, wl.dg_sub_bytes, st, padded);
             if (s != MPQ_OK) return s;
         }
     }
@@ -307,9 +322,11 @@ mpq_status run_conv_digits(const mpq_tensor &x, const void *w_packed, const void
 }
 
 // Everything mpq_conv2d and the MoE layer loop need to launch one convolution.
+// (row_padded: the caller's channel-padded copy of x for a first-layer shape, as launch_pad_channels
+// makes it; saves the copy when several convolutions read the same input)
 mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias, void *y_data,
                     int y_dtype, const mpq_conv_desc &d, const Epi &epi, const SegTable *seg,
-                    void *ws, size_t ws_bytes, hipStream_t st) {
+                    void *ws, size_t ws_bytes, hipStream_t st, const void *row_padded) {
     Geometry g;
     mpq_status s = geometry(x, d, &g);
     if (s != MPQ_OK) return s;
@@ -382,17 +399,20 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
         a.phased = (pl.mode == kModeTap && a.cpt % 4 == 0 && a.cpt > 4 && pl.taps > 1) ? 1 : 0;
         unsigned zb = (unsigned)(epi.zx & 0xff);
         a.fill_word = x.dtype == MPQ_INT8 ? zb * 0x01010101u : 0u;
-        if (pl.mode == kModeRow && aligned16(x.data) && aligned16(y_data)) {
+        if (pl.mode == kModeRow && !row_padded && aligned16(x.data) && aligned16(y_data)) {
             // first-layer shape: weights and an input patch resident in LDS, pool fused
             err = launch_conv_first(a, d.pool_k, d.pool_s, y_data, g.Po, g.Qo, st);
             if (err == hipSuccess) return MPQ_OK;
             if (err != hipErrorNotSupported) return MPQ_ERR_DEVICE;
         }
         if (pl.mode == kModeRow) {
-            void *xp = wsb + wl.pad_off;
-            err = launch_pad_channels(x.data, xp, x.n, x.h, x.w, x.c, pl.Wp, pl.Cpad, pl.esize,
-                                      x.dtype == MPQ_INT8 ? epi.zx : 0, st);
-            if (err != hipSuccess) return MPQ_ERR_DEVICE;
+            const void *xp = row_padded;
+            if (!xp) {
+                xp = wsb + wl.pad_off;
+                err = launch_pad_channels(x.data, wsb + wl.pad_off, x.n, x.h, x.w, x.c, pl.Wp, pl.Cpad, pl.esize,
+                                          x.dtype == MPQ_INT8 ? epi.zx : 0, st);
+                if (err != hipSuccess) return MPQ_ERR_DEVICE;
+            }
             a.x = xp;
             a.W = pl.Wp;
             a.C = pl.Cpad;
