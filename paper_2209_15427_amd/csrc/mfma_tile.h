@@ -252,6 +252,59 @@ struct Tile {
     // written with 16-byte stores in which consecutive lanes cover consecutive channels of a pixel,
     // so that every store instruction fills whole cache lines.  Raw accumulator outputs (gating
     // logits) are stored directly.  `lds` must hold kImageBytes and be idle (barrier before).
+    // Raw 32-bit results (int32 sums, fp32 sums after bias and ReLU): the tile leaves in passes of
+    // ROWB bytes per pixel, each transposed through the LDS image like the narrow outputs, so that a
+    // store instruction writes contiguous runs of a pixel's channels instead of 16 bytes per pixel.
+    static __device__ __forceinline__ void finish_raw(Acc (&acc)[TC][TP], unsigned char *lds, const ConvArgs &a,
+                                                      const TileCtx &t) {
+        const Plan &pl = a.plan;
+        const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+        const int wc = wave % WGC, wp = wave / WGC;
+        const int frow = lane & 31, fk = lane >> 5;
+        constexpr int PASSES = 4 / ES;          // 32-bit results are 4 / ES times as wide as the narrow image
+        constexpr int CPP = BC / PASSES;        // channels per pass
+#pragma unroll 1
+        for (int ps = 0; ps < PASSES; ++ps) {
+            if (ps > 0) __syncthreads();
+#pragma unroll
+            for (int i = 0; i < TC; ++i) {
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int chl = wc * WTC + i * 32 + vq * 8 + fk * 4;
+                    if (chl / CPP != ps) continue;
+                    const unsigned cb = (unsigned)((chl - ps * CPP) * 4);
+#pragma unroll
+                    for (int j = 0; j < TP; ++j) {
+                        const int row = wp * WTP + j * 32 + frow;
+                        const unsigned la = (unsigned)(row * ROWB) + (((cb >> 4) ^ (unsigned)(row & (CH16 - 1))) << 4);
+                        if constexpr (ES == 1) {
+                            *reinterpret_cast<v4i *>(lds + la) = v4i{acc[i][j][vq * 4], acc[i][j][vq * 4 + 1],
+                                                                   acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
+                        } else {
+                            float f[4];
+#pragma unroll
+                            for (int u = 0; u < 4; ++u) {
+                                f[u] = acc[i][j][vq * 4 + u];
+                                if (t.epi.relu) f[u] = f[u] > 0.f ? f[u] : 0.f;
+                            }
+                            *reinterpret_cast<float4 *>(lds + la) = make_float4(f[0], f[1], f[2], f[3]);
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+#pragma unroll 4
+            for (int idx = tid; idx < BP * CH16; idx += kThreads) {
+                const int row = idx / CH16, c16 = idx % CH16;
+                const int m = t.m0 + row;
+                const int ch = t.ch0 + ps * CPP + c16 * 4;
+                if (m >= t.m_end || ch >= pl.Kg) continue;
+                const v4i v = *reinterpret_cast<const v4i *>(lds + row * ROWB + ((c16 ^ (row & (CH16 - 1))) << 4));
+                *reinterpret_cast<v4i *>((int *)a.y + (size_t)m * a.K + (size_t)(t.g * pl.Kg + ch)) = v;
+            }
+        }
+    }
+
     // POOL (image-aligned tiles only): instead of the image, its 3x3 / stride-2 max-pool is stored
     // (the max commutes with the monotone requantization and is taken on the stored codes).
     template <bool POOL = false>
@@ -264,6 +317,10 @@ struct Tile {
         const int frow = lane & 31, fk = lane >> 5;
         const int g = t.g, m0 = t.m0, m_end = t.m_end, ch0 = t.ch0;
         const bool raw = epi.kind == kEpiRawI32 || epi.kind == kEpiRawF32;
+        if (raw) {
+            finish_raw(acc, lds, a, t);
+            return;
+        }
         auto run_epilogue = [&](auto fast_tag) {
             constexpr bool FAST = decltype(fast_tag)::value;
             const FastRequant fr = make_fast_requant(epi);
@@ -272,34 +329,25 @@ struct Tile {
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
                     const int chl = wc * WTC + i * 32 + vq * 8 + fk * 4;     // channel within the tile
-                    const int ch = ch0 + chl;
-                    const bool chv = ch < pl.Kg;
-                    const int kabs = g * pl.Kg + (chv ? ch : 0);
                     const unsigned cb = (unsigned)(chl * ES);
 #pragma unroll
                     for (int j = 0; j < TP; ++j) {
                         const int row = wp * WTP + j * 32 + frow;
-                        const int m = m0 + row;
                         const unsigned la =
                             (unsigned)(row * ROWB) + (((cb >> 4) ^ (unsigned)(row & (CH16 - 1))) << 4) + (cb & 15u);
                         if constexpr (ES == 1) {
                             int q[4];
 #pragma unroll
                             for (int u = 0; u < 4; ++u) q[u] = acc[i][j][vq * 4 + u];
-                            if (raw) {
-                                if (chv && m < m_end)
-                                    *reinterpret_cast<v4i *>((int *)a.y + (size_t)m * a.K + kabs) = v4i{q[0], q[1], q[2], q[3]};
+                            unsigned packed = 0;
+                            if constexpr (FAST) {
+                                packed = requant4_fast(q[0], q[1], q[2], q[3], fr);
                             } else {
-                                unsigned packed = 0;
-                                if constexpr (FAST) {
-                                    packed = requant4_fast(q[0], q[1], q[2], q[3], fr);
-                                } else {
 #pragma unroll
-                                    for (int u = 0; u < 4; ++u)
-                                        packed |= ((unsigned)requant32(q[u], epi) & 0xffu) << (8 * u);
-                                }
-                                *reinterpret_cast<unsigned *>(lds + la) = packed;
+                                for (int u = 0; u < 4; ++u)
+                                    packed |= ((unsigned)requant32(q[u], epi) & 0xffu) << (8 * u);
                             }
+                            *reinterpret_cast<unsigned *>(lds + la) = packed;
                         } else {
                             float f[4];
 #pragma unroll
@@ -307,15 +355,9 @@ struct Tile {
                                 f[u] = acc[i][j][vq * 4 + u];
                                 if (epi.relu) f[u] = f[u] > 0.f ? f[u] : 0.f;
                             }
-                            if (raw) {
-                                if (chv && m < m_end)
-                                    *reinterpret_cast<float4 *>((float *)a.y + (size_t)m * a.K + kabs) =
-                                        make_float4(f[0], f[1], f[2], f[3]);
-                            } else {
-                                typedef _Float16 v4h __attribute__((ext_vector_type(4)));
-                                v4h hv = {(_Float16)f[0], (_Float16)f[1], (_Float16)f[2], (_Float16)f[3]};
-                                *reinterpret_cast<v4h *>(lds + la) = hv;
-                            }
+                            typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+                            v4h hv = {(_Float16)f[0], (_Float16)f[1], (_Float16)f[2], (_Float16)f[3]};
+                            *reinterpret_cast<v4h *>(lds + la) = hv;
                         }
                     }
                 }
@@ -324,7 +366,6 @@ struct Tile {
         const bool fast = ES == 1 && fast_requant_ok(epi);
         if (fast) run_epilogue(std::true_type{});
         else run_epilogue(std::false_type{});
-        if (raw) return;
         __syncthreads();
         constexpr int CHUNK_ELEMS = 16 / ES;
         char *yb = (char *)a.y;
