@@ -141,7 +141,11 @@ mpq_status mpq_pack_weights(const void *w_kcrs, const mpq_conv_desc *d, mpq_dtyp
  *   w_packed from mpq_pack_weights with the same descriptor and dtype; w_q its parameters
  *   bias     device, k entries (int32 for integer types, fp32 for fp16), or NULL
  *   y        output view; n, h, w, c must equal the layer's output shape (after pooling)
- *   ws       device scratch of at least mpq_conv2d_workspace_bytes(), 256-byte aligned
+ *   ws       device scratch of at least mpq_conv2d_workspace_bytes(), 256-byte aligned.  For an
+ *            MPQ_INT16 layer the larger part of that size (byte planes of x and 32-bit partial
+ *            results for the int8 matrix-core kernels) is optional: with fewer bytes, but enough
+ *            for the unpooled output of a pooling layer, the layer runs on the direct kernel with
+ *            identical results; less than that is MPQ_ERR_WORKSPACE.
  * ------------------------------------------------------------------------------------------- */
 size_t mpq_conv2d_workspace_bytes(const mpq_tensor *x, const mpq_conv_desc *d);
 mpq_status mpq_conv2d(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q,
