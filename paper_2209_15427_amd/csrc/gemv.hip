@@ -95,6 +95,19 @@ __global__ void __launch_bounds__(kThreads) gemv_kernel(GemvArgs g) {
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) acc[m][r] = 0;
 
+    // the epilogue's per-feature constants are fetched now, by the threads that will use them: behind
+    // the reduction their memory latency would be the tail of every workgroup
+    unsigned bias_w = 0;
+    int wsum_n = 0;
+    if (tid < NR * ROWS) {
+        const int m = tid / ROWS, s = s0 + tid % ROWS;
+        if (m < g.nr && s < g.ns) {
+            const int n = g.swapped ? m : s;
+            if (g.bias) bias_w = ((const unsigned *)g.bias)[n];
+            if constexpr (!__is_same(Acc, float)) wsum_n = g.epi.zx != 0 ? g.wsum[n] : 0;
+        }
+    }
+
     for (int j = tid; j < g.chunks; j += kThreads) {
         v4i wv[ROWS];
 #pragma unroll
@@ -125,20 +138,17 @@ __global__ void __launch_bounds__(kThreads) gemv_kernel(GemvArgs g) {
             const int n = g.swapped ? m : s;       // output feature
             const size_t o = (size_t)row * g.N + n;
             if constexpr (sizeof(Acc) == 8) {
-                long long t = v;
-                if (g.bias) t += (long long)((const int *)g.bias)[n];
-                if (g.epi.zx != 0) t -= (long long)g.epi.zx * (long long)g.wsum[n];
+                long long t = v + (long long)(int)bias_w;
+                t -= (long long)g.epi.zx * (long long)wsum_n;
                 if (g.epi.kind == kEpiRawI32) ((int *)g.y)[o] = (int)t;
                 else ((int16_t *)g.y)[o] = (int16_t)requant64(t, g.epi);
             } else if constexpr (sizeof(T) == 1) {
-                int t = v;
-                if (g.bias) t += ((const int *)g.bias)[n];
-                if (g.epi.zx != 0) t -= g.epi.zx * g.wsum[n];
+                int t = v + (int)bias_w;
+                t -= g.epi.zx * wsum_n;
                 if (g.epi.kind == kEpiRawI32) ((int *)g.y)[o] = t;
                 else ((int8_t *)g.y)[o] = (int8_t)requant64((long long)t, g.epi);
             } else {
-                float t = v;
-                if (g.bias) t += ((const float *)g.bias)[n];
+                float t = v + __builtin_bit_cast(float, bias_w);
                 if (g.epi.relu) t = t > 0.f ? t : 0.f;
                 if (g.epi.kind == kEpiRawF32) ((float *)g.y)[o] = t;
                 else ((_Float16 *)g.y)[o] = (_Float16)t;

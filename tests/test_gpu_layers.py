@@ -279,8 +279,9 @@ def test_int8_gemm_without_workspace(case):
     assert np.array_equal(y.cpu().numpy().astype(np.int32), o.requant(t, mult, 31, shift, 0, "int8", relu))
 
 
-@pytest.mark.parametrize("M,N", [(2, 3), (64, 96)], ids=["direct", "digit_planes"])
-def test_int16_gemm_accumulates_beyond_int32(M, N):
+@pytest.mark.parametrize("M,N,ws", [(2, 3, True), (64, 96, True), (64, 96, False)],
+                         ids=["gemv", "digit_planes", "direct_without_workspace"])
+def test_int16_gemm_accumulates_beyond_int32(M, N, ws):
     K = 4096
     x = np.full((M, K), 32767, np.int64)
     x[1::2] = -32768
@@ -289,7 +290,8 @@ def test_int16_gemm_accumulates_beyond_int32(M, N):
     assert abs(t).max() > 2 ** 31
     s = (np.float32(1e-3), np.float32(1e-3), np.float32(400.0))
     y = gu.run_gemm(torch.from_numpy(x.astype(np.int16)).to("cuda"), (s[0], 0),
-                    torch.from_numpy(w.astype(np.int16)).to("cuda"), (s[1], 0), None, False, mb.INT16, (s[2], 0))
+                    torch.from_numpy(w.astype(np.int16)).to("cuda"), (s[1], 0), None, False, mb.INT16, (s[2], 0),
+                    workspace=ws)
     mult, shift = o.scale_quant_vals(*s, 15)
     ref = o.requant(t, mult, 15, shift, 0, "int16", False)
     assert np.array_equal(y.cpu().numpy().astype(np.int32), ref)
