@@ -90,6 +90,18 @@ def estimate_params(fmin, fmax, imin, imax):
     return s.value, i0.value, i1.value
 
 
+def observe_minmax(r, lo=np.inf, hi=-np.inf):
+    """Running value range of the quantizer's observe mode (section "Quantization Integration to
+    Caffe"): the smallest and largest element seen so far; NaN elements carry no value and are
+    skipped.  Returns (lo, hi) as Python floats."""
+    v = np.asarray(r, np.float32).ravel()
+    v = v[~np.isnan(v)]
+    if v.size:
+        lo = min(float(lo), float(v.min()))
+        hi = max(float(hi), float(v.max()))
+    return float(lo), float(hi)
+
+
 def quantize(r, scale, zero, dtype):
     qmin, qmax = QRANGE[dtype]
     r = _c(r, np.float32)

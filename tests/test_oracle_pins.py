@@ -45,6 +45,20 @@ def test_estimate_params_closed_forms():
     assert o.estimate_params(-0.3, 0.9, -128, 127)[1] == o.estimate_params(-0.3, 0.9, 0, 255)[1] - 128
 
 
+def test_observe_minmax_brute_force_and_special_values():
+    r = gen.normal(31, (257,), 0.5, 3.0).astype(np.float32)
+    lo, hi = np.inf, -np.inf
+    for v in r.tolist():            # element by element
+        lo, hi = (v if v < lo else lo), (v if v > hi else hi)
+    assert o.observe_minmax(r) == (lo, hi)
+    # running: a second block only widens the range; NaN is skipped; infinities count
+    assert o.observe_minmax(np.float32([0.25, np.nan]), lo, hi) == (lo, hi)
+    assert o.observe_minmax(np.float32([np.nan, np.nan])) == (np.inf, -np.inf)
+    assert o.observe_minmax(np.float32([-np.inf, 2.0]), 0.0, 1.0) == (-np.inf, 2.0)
+    assert o.observe_minmax(np.float32([]), -1.0, 1.0) == (-1.0, 1.0)
+    assert o.observe_minmax(np.float32([-3.0, -7.5, -4.0])) == (-7.5, -3.0)
+
+
 # --------------------------------------------------------------------------------------------
 # quantize / dequantize
 # --------------------------------------------------------------------------------------------
