@@ -112,6 +112,25 @@ mpq_status mpq_scale_quant_vals(float s_x, float s_w, float s_y, mpq_dtype dtype
                                 int64_t *mult /* host */, int32_t *shift /* host */);
 
 /* ---------------------------------------------------------------------------------------------
+ * Quantization parameters from an observed value range (section "Quantized Operations", the
+ * parameter estimation before the multiplication rule; the quantizer's observe mode of section
+ * "Quantization Integration to Caffe" supplies the range).
+ *   mpq_observe_minmax: folds the minimum and maximum of src[0..count) into minmax[0], minmax[1]
+ *     (device, 2 floats, read and written: a running range over several calls; start it at
+ *     +inf, -inf).  NaN elements are skipped.  Calls that share one minmax buffer may overlap.
+ *   mpq_estimate_params (host only; outputs are host pointers), in double precision, then cast:
+ *     scale = (fmax - fmin) / (imax - imin)
+ *     zero_point = clamp(round_half_even(imin - fmin / scale), imin, imax)
+ *     one_point  = 1 / scale + zero_point      (the code that represents 1.0; may be NULL)
+ *     imin / imax are the storage type's limits the caller wants used (the paper takes 0 and
+ *     255 for 8 bits).  fmax <= fmin, imax <= imin or non-finite values: MPQ_ERR_INVALID_ARG.
+ * ------------------------------------------------------------------------------------------- */
+mpq_status mpq_observe_minmax(const float *src, size_t count, float *minmax, void *stream);
+mpq_status mpq_estimate_params(float fmin, float fmax, int32_t imin, int32_t imax,
+                               float *scale /* host */, int32_t *zero_point /* host */,
+                               float *one_point /* host, optional */);
+
+/* ---------------------------------------------------------------------------------------------
  * Weight packing (one-time, outside the hot path).  Converts weights from the logical layout
  * K, C/groups, R, S (the paper's framework keeps them so) into the kernel layout used by
  * mpq_conv2d / mpq_gemm for this descriptor and dtype, and appends the per-output-channel sums

@@ -19,7 +19,8 @@ STATUS = {0: "ok", 1: "invalid argument", 2: "shape mismatch", 3: "unsupported",
           4: "workspace too small or misaligned", 5: "device error"}
 
 EXPORTS = ["mpq_status_string", "mpq_abi_version", "mpq_quantize", "mpq_dequantize", "mpq_to_fp16",
-           "mpq_from_fp16", "mpq_scale_quant_vals", "mpq_packed_weight_bytes", "mpq_pack_weights",
+           "mpq_from_fp16", "mpq_scale_quant_vals", "mpq_observe_minmax", "mpq_estimate_params",
+           "mpq_packed_weight_bytes", "mpq_pack_weights",
            "mpq_conv2d_workspace_bytes", "mpq_conv2d", "mpq_gemm_desc", "mpq_gemm_workspace_bytes",
            "mpq_gemm", "mpq_maxpool2d", "mpq_moe_workspace_bytes", "mpq_moe_forward"]
 
@@ -74,6 +75,9 @@ def lib():
         L.mpq_from_fp16.argtypes = [vp, vp, sz, vp]
         L.mpq_scale_quant_vals.argtypes = [C.c_float, C.c_float, C.c_float, C.c_int,
                                            C.POINTER(C.c_int64), C.POINTER(i32)]
+        L.mpq_observe_minmax.argtypes = [vp, sz, vp, vp]
+        L.mpq_estimate_params.argtypes = [C.c_float, C.c_float, i32, i32, C.POINTER(C.c_float), C.POINTER(i32),
+                                          C.POINTER(C.c_float)]
         L.mpq_packed_weight_bytes.restype = sz
         L.mpq_packed_weight_bytes.argtypes = [DP, C.c_int]
         L.mpq_pack_weights.argtypes = [vp, DP, C.c_int, vp, sz, vp]
@@ -151,6 +155,18 @@ def mpq_scale_quant_vals(s_x, s_w, s_y, dtype):
     m, h = C.c_int64(), C.c_int32()
     _check(lib().mpq_scale_quant_vals(s_x, s_w, s_y, dtype, C.byref(m), C.byref(h)), "mpq_scale_quant_vals")
     return m.value, h.value
+
+
+def mpq_observe_minmax(src, count, minmax, stream=None):
+    _check(lib().mpq_observe_minmax(_ptr(src), count, _ptr(minmax), _stream(stream)), "mpq_observe_minmax")
+
+
+def mpq_estimate_params(fmin, fmax, imin, imax):
+    """Returns (scale, zero_point, one_point)."""
+    s, z, one = C.c_float(), C.c_int32(), C.c_float()
+    _check(lib().mpq_estimate_params(fmin, fmax, imin, imax, C.byref(s), C.byref(z), C.byref(one)),
+           "mpq_estimate_params")
+    return s.value, z.value, one.value
 
 
 def mpq_packed_weight_bytes(desc, dtype):

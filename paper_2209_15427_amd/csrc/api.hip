@@ -542,6 +542,28 @@ mpq_status mpq_scale_quant_vals(float s_x, float s_w, float s_y, mpq_dtype dtype
     return MPQ_OK;
 }
 
+mpq_status mpq_observe_minmax(const float *src, size_t count, float *minmax, void *stream) {
+    if (!minmax) return MPQ_ERR_INVALID_ARG;
+    if (count == 0) return MPQ_OK;
+    if (!src) return MPQ_ERR_INVALID_ARG;
+    return launch_minmax(src, count, minmax, (hipStream_t)stream) == hipSuccess ? MPQ_OK : MPQ_ERR_DEVICE;
+}
+
+mpq_status mpq_estimate_params(float fmin, float fmax, int32_t imin, int32_t imax, float *scale,
+                               int32_t *zero_point, float *one_point) {
+    if (!scale || !zero_point) return MPQ_ERR_INVALID_ARG;
+    if (!std::isfinite(fmin) || !std::isfinite(fmax) || !(fmax > fmin) || imax <= imin) return MPQ_ERR_INVALID_ARG;
+    const double lo = (double)imin, hi = (double)imax;
+    const double s = ((double)fmax - (double)fmin) / (hi - lo);
+    if (!(s > 0.0) || !std::isfinite(s)) return MPQ_ERR_INVALID_ARG;
+    double z = std::nearbyint(lo - (double)fmin / s);
+    z = z < lo ? lo : (z > hi ? hi : z);
+    *scale = (float)s;
+    *zero_point = (int32_t)z;
+    if (one_point) *one_point = (float)(1.0 / s + z);
+    return MPQ_OK;
+}
+
 size_t mpq_packed_weight_bytes(const mpq_conv_desc *d, mpq_dtype dtype) {
     if (!d || !desc_ok(*d)) return 0;
     if (dtype != MPQ_INT8 && dtype != MPQ_INT16 && dtype != MPQ_FP16) return 0;

@@ -160,6 +160,7 @@ struct I16Combine {
 hipError_t launch_i16_tappre(const void *w16, int *tappre, int K, int Cg, int R, int S, hipStream_t st);
 hipError_t launch_i16_combine(const int *raw, size_t raw_stride, const int *bias, void *y, size_t total,
                               const I16Combine &g, const Epi &epi, hipStream_t st);
+hipError_t launch_minmax(const float *src, size_t n, float *minmax, hipStream_t st);
 hipError_t launch_pad_channels(const void *x, void *xp, int N, int H, int W, int C, int Wp, int Cpad,
                                int esize, int fill, hipStream_t st);
 hipError_t launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int k, int s, int dtype,

@@ -335,7 +335,84 @@ maxpool_x8_kernel(const T *__restrict__ x, T *__restrict__ y, int N, int H, int 
     }
 }
 
+// Running minimum / maximum of a float array (NaN skipped).  Floats are compared through the
+// order-preserving map to unsigned keys, so that one integer compare-and-swap loop per workgroup
+// folds the result into the caller's pair whatever the signs.
+__device__ __forceinline__ unsigned float_key(float f) {
+    const unsigned b = __builtin_bit_cast(unsigned, f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+template <bool IS_MIN>
+__device__ __forceinline__ void fold_float(float *dst, float v) {
+    unsigned *p = reinterpret_cast<unsigned *>(dst);
+    unsigned old = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned kv = float_key(v);
+    while (true) {
+        const float cur = __builtin_bit_cast(float, old);
+        // (a NaN in the caller's pair is replaced)
+        const bool better = cur != cur || (IS_MIN ? kv < float_key(cur) : kv > float_key(cur));
+        if (!better) return;
+        if (__hip_atomic_compare_exchange_strong(p, &old, __builtin_bit_cast(unsigned, v), __ATOMIC_RELAXED,
+                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+            return;
+    }
+}
+
+__global__ void __launch_bounds__(kThreads) minmax_kernel(const float *__restrict__ src, size_t n, float *minmax,
+                                                          int vec_ok) {
+    __shared__ unsigned s_lo[kThreads / 64], s_hi[kThreads / 64];
+    // keys: 0xffffffff / 0 stand for "nothing seen"
+    unsigned lo = 0xffffffffu, hi = 0u;
+    auto take = [&](float f) {
+        if (f == f) {
+            const unsigned k = float_key(f);
+            lo = k < lo ? k : lo;
+            hi = k > hi ? k : hi;
+        }
+    };
+    const size_t tid = (size_t)blockIdx.x * kThreads + threadIdx.x, nthreads = (size_t)gridDim.x * kThreads;
+    const size_t nvec = vec_ok ? n / 4 : 0;
+    for (size_t i = tid; i < nvec; i += nthreads) {
+        const float4 v = reinterpret_cast<const float4 *>(src)[i];
+        take(v.x); take(v.y); take(v.z); take(v.w);
+    }
+    for (size_t i = nvec * 4 + tid; i < n; i += nthreads) take(src[i]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const unsigned ol = __shfl_xor(lo, off, 64), oh = __shfl_xor(hi, off, 64);
+        lo = ol < lo ? ol : lo;
+        hi = oh > hi ? oh : hi;
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { s_lo[wave] = lo; s_hi[wave] = hi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kThreads / 64; ++w) {
+            lo = s_lo[w] < lo ? s_lo[w] : lo;
+            hi = s_hi[w] > hi ? s_hi[w] : hi;
+        }
+        if (hi != 0u) {   // something seen: keys back to floats
+            const unsigned bl = (lo & 0x80000000u) ? (lo & 0x7fffffffu) : ~lo;
+            const unsigned bh = (hi & 0x80000000u) ? (hi & 0x7fffffffu) : ~hi;
+            fold_float<true>(minmax, __builtin_bit_cast(float, bl));
+            fold_float<false>(minmax + 1, __builtin_bit_cast(float, bh));
+        }
+    }
+}
+
 }  // namespace
+
+hipError_t launch_minmax(const float *src, size_t n, float *minmax, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    const int vec_ok = (reinterpret_cast<uintptr_t>(src) % 16) == 0;
+    size_t blocks = (n / 4 + kThreads - 1) / kThreads;
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    minmax_kernel<<<(int)blocks, kThreads, 0, st>>>(src, n, minmax, vec_ok);
+    return hipGetLastError();
+}
 
 hipError_t launch_quantize(const float *src, void *dst, size_t n, int dtype, float scale, int zp,
                            hipStream_t st) {

@@ -71,6 +71,44 @@ def test_fp16_conversion():
     assert np.array_equal(back.cpu().numpy().astype(np.float64), ref)
 
 
+def test_observe_minmax_then_estimate_and_quantize():
+    """Observe mode -> parameter estimation -> quantize, each step against the oracle."""
+    _say("observe minmax")
+    v = np.concatenate([gen.normal(71, (100003,), -0.4, 2.0), [np.nan, -17.25, np.nan, 9.5]]).astype(np.float32)
+    src = torch.from_numpy(v).to("cuda")
+    mm = torch.tensor([np.inf, -np.inf], dtype=torch.float32, device="cuda")
+    mb.mpq_observe_minmax(src, v.size, mm)
+    torch.cuda.synchronize()
+    ref = o.observe_minmax(v)
+    assert tuple(mm.cpu().tolist()) == ref == (-17.25, 9.5)
+    # running range: a second, unaligned and ragged block; then one that changes nothing; then an empty one
+    w = (gen.normal(72, (4099,), 3.0, 4.0)).astype(np.float32)
+    wd = torch.from_numpy(w).to("cuda")
+    mb.mpq_observe_minmax(wd[1:], w.size - 1, mm)
+    mb.mpq_observe_minmax(src[:1000], 1000, mm)
+    mb.mpq_observe_minmax(src, 0, mm)
+    torch.cuda.synchronize()
+    ref = o.observe_minmax(v[:1000], *o.observe_minmax(w[1:], *ref))
+    assert tuple(mm.cpu().tolist()) == ref
+    # all-NaN input leaves the pair alone; infinities count
+    mm2 = torch.tensor([np.inf, -np.inf], dtype=torch.float32, device="cuda")
+    nan = torch.full((77,), float("nan"), device="cuda")
+    mb.mpq_observe_minmax(nan, 77, mm2)
+    torch.cuda.synchronize()
+    assert tuple(mm2.cpu().tolist()) == (np.inf, -np.inf)
+    mb.mpq_observe_minmax(torch.tensor([1.0, -np.inf, 3.0], device="cuda"), 3, mm2)
+    torch.cuda.synchronize()
+    assert tuple(mm2.cpu().tolist()) == (-np.inf, 3.0)
+    # the observed range feeds the estimation and the quantizer
+    s, z, _ = mb.mpq_estimate_params(ref[0], ref[1], -128, 127)
+    so, zo, _ = o.estimate_params(ref[0], ref[1], -128, 127)
+    assert (s, z) == (np.float32(so), zo)
+    q = torch.empty(v.size, dtype=torch.int8, device="cuda")
+    mb.mpq_quantize(src, q, v.size, mb.INT8, s, z)
+    torch.cuda.synchronize()
+    assert np.array_equal(q.cpu().numpy().astype(np.int32), o.quantize(v, s, z, "int8"))
+
+
 # ---------------------------------------------------------------------------------------------
 # integer convolution
 # ---------------------------------------------------------------------------------------------

@@ -44,6 +44,27 @@ def test_scale_quant_vals_matches_oracle():
     assert e.value.status == 3
 
 
+def test_estimate_params_matches_oracle():
+    """Host helper against the oracle's double-precision evaluation (paper values: the oracle's own pins)."""
+    lo = gen.uniform(6, (200,), -50.0, 5.0)
+    span = gen.uniform(7, (200,), 1e-3, 80.0)
+    for a, d in zip(lo, span):
+        fmin, fmax = float(np.float32(a)), float(np.float32(a + d))
+        if not fmax > fmin:
+            continue
+        for imin, imax in ((0, 255), (-128, 127), (0, 65535), (-32768, 32767)):
+            s, z, one = mb.mpq_estimate_params(fmin, fmax, imin, imax)
+            so, zo, oo = o.estimate_params(fmin, fmax, imin, imax)
+            assert s == np.float32(so) and z == zo and one == np.float32(oo)
+    s, z, one = mb.mpq_estimate_params(-394.6, 1832.0, 0, 255)     # the Celsius example's range
+    assert z == o.estimate_params(np.float32(-394.6), 1832.0, 0, 255)[1] and abs(s / 2 - 4.3658) < 2e-4
+    for bad in [(1.0, 1.0, 0, 255), (2.0, 1.0, 0, 255), (0.0, 1.0, 5, 5), (float("nan"), 1.0, 0, 255),
+                (0.0, float("inf"), 0, 255)]:
+        with pytest.raises(mb.MpqError) as e:
+            mb.mpq_estimate_params(*bad)
+        assert e.value.status == 1
+
+
 def _status(fn, *a, **k):
     try:
         fn(*a, **k)
