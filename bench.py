@@ -226,6 +226,7 @@ def main():
         out["fc_batches"] = bench_fc_batches(torch, mb, pl, cf, calib, args.dtype)
         if B == 256:
             out["moe_config5"] = bench_moe(torch, mb, pl, cf, calib, args.dtype, chain.acts[1], B)
+        out["alexnet_whole_net"] = bench_whole_net(torch, mb, pl, cf, calib, args.dtype, x_dev, B, macs_img)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cf, calib, args.dtype, args.cpu_images, macs_img)
@@ -270,6 +271,34 @@ def graph_time(torch, fn, iters=10, reps=10):
     b.record()
     torch.cuda.synchronize()
     return a.elapsed_time(b) * 1e3 / (iters * reps)
+
+
+def bench_whole_net(torch, mb, pl, cf, calib, dtype_name, x_dev, batch, conv_macs_img):
+    """Config 3's stack followed by config 4's fully-connected layers as one chain (the paper's
+    benchmark unit without its normalisation, dropout and softmax layers): input conversion, five
+    convolutions with their pools, three FC layers at the stack's batch, timed per forward pass."""
+    dt = mb.DTYPE_ID[dtype_name]
+    params = cf.alexnet_full_params()
+    if dtype_name == "fp16":
+        net = pl.Chain(cf.ALEXNET_FULL, params, dt, batch, cf.ALEXNET_INPUT)
+    else:
+        sc = calib.load()["alexnet_full"][dtype_name]
+        net = pl.Chain(cf.ALEXNET_FULL, params, dt, batch, cf.ALEXNET_INPUT, sc["x"], sc["layers"])
+    x_store = torch.empty(x_dev.shape, dtype=mb.TORCH_DTYPE[dt], device="cuda")
+    n_in = x_dev.numel()
+
+    def forward():
+        if dt == mb.FP16:
+            mb.mpq_to_fp16(x_dev, x_store, n_in)
+        else:
+            mb.mpq_quantize(x_dev, x_store, n_in, dt, net.s_in, 0)
+        return net.forward(x_store)
+
+    us = graph_time(torch, forward, 5, 5)
+    macs = conv_macs_img + sum(L.macs() for L in cf.ALEXNET_FCS)
+    return {"workload": f"conv1..conv5 + pools + fc6..fc8 chained, batch {batch}", "forward_us": round(us, 1),
+            "images_per_s": round(batch / (us * 1e-6), 1), "gop_per_image": round(2 * macs / 1e9, 4),
+            "tops": round(2.0 * macs * batch / (us * 1e-6) / 1e12, 1)}
 
 
 def bench_moe(torch, mb, pl, cf, calib, dtype_name, trunk_out, batch):

@@ -60,6 +60,14 @@ def main():
         s_in = _s(6.0, dt)
         res["alexnet"][dt] = {"x": s_in, "layers": _layer_scales(cf.ALEXNET_CONVS, params, peaks, s_in, dt)}
 
+    # the whole net (config 3's stack followed by config 4's layers), same images
+    params = cf.alexnet_full_params()
+    peaks, _ = nets.run_f64_chain_maxabs(cf.ALEXNET_FULL, x, params)
+    res["alexnet_full"] = {}
+    for dt in QSYM:
+        s_in = _s(6.0, dt)
+        res["alexnet_full"][dt] = {"x": s_in, "layers": _layer_scales(cf.ALEXNET_FULL, params, peaks, s_in, dt)}
+
     # config 4: FC layers, first 16 rows observed
     res["fc"] = {}
     for i, L in enumerate(cf.ALEXNET_FCS):

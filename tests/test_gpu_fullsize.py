@@ -28,7 +28,7 @@ def _alexnet_batch(B):
     return _ALEX[B]
 
 
-@pytest.mark.parametrize("dtype", ["int8", "fp16"])
+@pytest.mark.parametrize("dtype", ["int8", "int16", "fp16"])
 def test_alexnet_stack_batch256_sampled_images(dtype):
     """Config 3 at batch 256: every layer's output for images 0, 97 and 255 against the oracle."""
     _say("alexnet b256", dtype)
@@ -56,7 +56,7 @@ def test_alexnet_stack_batch256_sampled_images(dtype):
 
 
 def test_alexnet_stack_batch8_int16():
-    """int16 runs on the direct kernel; batch 8 keeps the oracle and the device in seconds."""
+    """int16 at a batch whose layers all take the digit-plane path (and a different workspace size)."""
     x = _alexnet_batch(256)[:8]
     params = cf.alexnet_conv_params()
     sc = calib.load()["alexnet"]["int16"]

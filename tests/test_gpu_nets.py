@@ -77,6 +77,21 @@ def test_alexnet_stack_batch2(dtype):
         _chain_parity(cf.ALEXNET_CONVS, x, params, cf.ALEXNET_INPUT, dtype, sc["x"], sc["layers"])
 
 
+@pytest.mark.parametrize("dtype", ["int8", "int16", "fp16"])
+def test_alexnet_whole_net_batch4(dtype):
+    """Config 3's stack followed by config 4's fully-connected layers, chained: conv5's pooled
+    256 x 6 x 6 output is the 9216-feature input of fc6 (C, H, W order, as the paper's framework
+    flattens it); every layer's output against the oracle."""
+    _say("alexnet whole net", dtype)
+    x = cf.alexnet_input(4)
+    params = cf.alexnet_full_params()
+    if dtype == "fp16":
+        _chain_parity(cf.ALEXNET_FULL, x, params, cf.ALEXNET_INPUT, dtype)
+    else:
+        sc = calib.load()["alexnet_full"][dtype]
+        _chain_parity(cf.ALEXNET_FULL, x, params, cf.ALEXNET_INPUT, dtype, sc["x"], sc["layers"])
+
+
 def test_alexnet_stack_batch1_int8():
     _say("alexnet batch 1 int8")
     sc = calib.load()["alexnet"]["int8"]

@@ -71,6 +71,10 @@ ALEXNET_FCS = [
 ]
 FC_BATCHES = (1, 16, 256)
 
+# ---- the whole AlexNet-shaped net: config 3's stack, then config 4's layers on its output -------
+# (256 x 6 x 6 = 9216 features; the paper's normalisation, dropout and softmax layers are left out)
+ALEXNET_FULL = ALEXNET_CONVS + ALEXNET_FCS
+
 # ---- config 2: LeNet-shaped net ---------------------------------------------------------------
 LENET_INPUT = (1, 28, 28)
 LENET_LAYERS = [
@@ -161,6 +165,16 @@ def alexnet_conv_params(layers: List[Conv] = None, base: int = 3000):
     out = []
     for i, L in enumerate(layers):
         out.append((conv_weights(base + 10 + 2 * i, L), bias(base + 11 + 2 * i, L.K, 0.1)))
+    return out
+
+
+def alexnet_full_params():
+    """Config 3's convolution parameters, then the fully-connected layers with config 4's weights
+    (He-like spread for the chained net: std = sqrt(2 / K))."""
+    out = alexnet_conv_params()
+    for i, L in enumerate(ALEXNET_FCS):
+        base = 4500 + 100 * i
+        out.append((fc_weights(base + 1, L, std=float(np.sqrt(2.0 / L.K))), bias(base + 2, L.N, 0.1)))
     return out
 
 
