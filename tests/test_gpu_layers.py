@@ -143,6 +143,52 @@ def _int_conv_case(dtype, N, C, H, W, K, R, S, stride, pad, groups, relu, pool, 
     assert len(np.unique(ref)) > 20
 
 
+def _random_geometries(seed, count, min_macs, max_macs):
+    """Seeded random convolution geometries (channels per group a multiple of 16, output channels
+    of 4) with between min_macs and max_macs multiply-accumulates."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        groups = int(rng.choice([1, 1, 2, 3]))
+        cg = 16 * int(rng.integers(1, 7))
+        kg = 4 * int(rng.integers(2, 40))
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        stride = int(rng.choice([1, 1, 2]))
+        pad = int(rng.integers(0, max(R, S)))
+        H, W = int(rng.integers(R + 4, 30)), int(rng.integers(S + 4, 30))
+        N = int(rng.integers(1, 7))
+        P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+        pool = (0, 0)
+        if rng.random() < 0.4 and min(P, Q) >= 3:
+            pool = (3, 2) if rng.random() < 0.5 else (2, 2)
+        macs = N * P * Q * kg * groups * cg * R * S
+        if min_macs <= macs <= max_macs:
+            zx = int(rng.choice([0, 0, -3, 11]))
+            out.append((N, cg * groups, H, W, kg * groups, R, S, stride, pad, groups, bool(rng.random() < 0.7), pool,
+                        zx, 0, int(rng.choice([0, 0, 5]))))
+    return out
+
+
+RANDOM_I16 = _random_geometries(20240, 14, 1 << 24, 1 << 27)
+
+
+@pytest.mark.parametrize("idx", range(len(RANDOM_I16)))
+def test_int16_conv_random_geometries(idx):
+    """int16 layers large enough for the digit-plane path, random geometry (non-square kernels,
+    padding wider than half the kernel, strides, groups, input zero-points, pools)."""
+    case = RANDOM_I16[idx]
+    _say("int16 random", case)
+    _int_conv_case(mb.INT16, *case, seed=7000 + 31 * idx)
+
+
+@pytest.mark.parametrize("idx", range(0, len(RANDOM_I16), 2))
+def test_int8_conv_random_geometries(idx):
+    case = list(RANDOM_I16[idx])
+    case[12] = 0 if case[8] > 0 else case[12]      # (int8: a padded layer with z_x != 0 is covered by c3)
+    _say("int8 random", case)
+    _int_conv_case(mb.INT8, *case, seed=7500 + 31 * idx)
+
+
 def test_config1_single_int8_conv():
     """Config 1: N=1, 3x32x32, 16 filters 3x3, stride 1, pad 1, bias + ReLU, scales 0.02/0.01/0.05."""
     _say("config 1")
