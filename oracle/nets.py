@@ -129,6 +129,35 @@ def moe_int(xq, s_x, logits, expert_layers, expert_params_q, expert_scales, dtyp
     return out, e_idx, counts
 
 
+def _expert_int(a, s, e, expert_layers, expert_params_q, expert_scales, dtype):
+    for L, (wq, bq), sc in zip(expert_layers, expert_params_q[e], expert_scales[e]):
+        if L.kind == "conv":
+            a = int_conv(a, 0, s, wq, 0, bq, L, sc, dtype)
+        else:
+            a = int_fc(a.reshape(1, -1), 0, s, wq, 0, bq, L, sc, dtype)
+        s = sc["y"]
+    return a, s
+
+
+def moe_topk_int(xq, s_x, logits, top_k, expert_layers, expert_params_q, expert_scales, dtype):
+    """K experts per sample (section "Mixture of Experts"): every selected expert's layer chain is
+    evaluated on the sample alone; the outputs, taken back to real values with the expert's output
+    scale (zero-point 0), are summed with the renormalised gating probabilities as weights.
+    Returns (y float64 [B, ...], sel, weights, counts)."""
+    sel, w, counts = o.route_topk(logits, top_k)
+    out = None
+    for b in range(xq.shape[0]):
+        acc = 0.0
+        for k in range(top_k):
+            e = int(sel[b, k])
+            a, s = _expert_int(xq[b:b + 1], s_x, e, expert_layers, expert_params_q, expert_scales, dtype)
+            acc = acc + w[b, k] * (np.float64(np.float32(s)) * a[0].astype(np.float64))
+        if out is None:
+            out = np.empty((xq.shape[0],) + acc.shape, np.float64)
+        out[b] = acc
+    return out, sel, w, counts
+
+
 def moe_fp16(x16, logits, expert_layers, expert_params16):
     e_idx, counts = o.route_top1(logits)
     out = None

@@ -251,6 +251,27 @@ def round_fp16(x):
     return y
 
 
+def route_topk(logits, top_k):
+    """Selection stage with K experts per sample (section "Mixture of Experts"): the K largest
+    gating values of a row, largest first, the lower index first among equal values; the mixing
+    weights are the gating probabilities renormalised over the selected experts, i.e. the softmax
+    of the selected logits alone (the noise terms of the paper's gating are a training aid and
+    are absent).  Returns (sel int32 [B,K], weights float64 [B,K], counts int32 [E])."""
+    lg = np.asarray(logits, np.float64)
+    B, E = lg.shape
+    sel = np.empty((B, top_k), np.int32)
+    w = np.empty((B, top_k), np.float64)
+    counts = np.zeros(E, np.int32)
+    for b in range(B):
+        order = sorted(range(E), key=lambda i: (-lg[b, i], i))[:top_k]
+        q = np.exp(lg[b, order] - lg[b, order[0]])
+        sel[b] = order
+        w[b] = q / q.sum()
+        for e in order:
+            counts[e] += 1
+    return sel, w, counts
+
+
 def route_top1(logits):
     lg = _c(logits, np.float64)
     B, E = lg.shape

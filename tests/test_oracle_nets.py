@@ -49,6 +49,50 @@ def _tiny_moe(dtype="int8"):
     return layers, params, scales, x, E
 
 
+def test_route_topk_closed_forms():
+    # two of three: ln 3 and ln 1 selected -> weights 3/4 and 1/4 (softmax over the selected pair)
+    sel, w, counts = o.route_topk(np.array([[0.0, np.log(3.0), -40.0]]), 2)
+    assert sel.tolist() == [[1, 0]] and np.allclose(w, [[0.75, 0.25]], rtol=1e-15, atol=0) and counts.tolist() == [1, 1, 0]
+    # ties: lower index first; equal logits: equal weights that sum to 1
+    sel, w, counts = o.route_topk(np.array([[2.0, 5.0, 5.0, 2.0]]), 3)
+    assert sel.tolist() == [[1, 2, 0]] and w[0, 0] == w[0, 1] and abs(w.sum() - 1) < 1e-15
+    # K = 1 is the arg-max with weight exactly 1, and the counts of the one-expert routing
+    lg = gen.normal(41, (50, 6))
+    sel, w, counts = o.route_topk(lg, 1)
+    e1, c1 = o.route_top1(lg)
+    assert np.array_equal(sel[:, 0], e1) and np.array_equal(counts, c1) and np.all(w == 1.0)
+    # K = E selects everything: the full softmax; adding a constant to a row changes nothing
+    sel, w, _ = o.route_topk(lg, 6)
+    full = np.exp(lg) / np.exp(lg).sum(1, keepdims=True)
+    assert np.allclose(np.take_along_axis(full, sel.astype(np.int64), 1), w, rtol=1e-12)
+    assert np.allclose(o.route_topk(lg + 3.5, 6)[1], w, rtol=1e-12)
+
+
+def test_moe_topk_reduces_to_one_expert_and_to_the_plain_average():
+    layers, params, scales, x, E = _tiny_moe()
+    B = x.shape[0]
+    lg = gen.normal(9, (B, E))
+    # K = 1: the one-expert result taken back to real values with that expert's output scale
+    y1, e_idx, _ = nets.moe_int(x, 0.02, lg, layers, params, scales, "int8")
+    yk, sel, w, counts = nets.moe_topk_int(x, 0.02, lg, 1, layers, params, scales, "int8")
+    s_out = np.array([np.float32(scales[int(e)][-1]["y"]) for e in e_idx], np.float64)
+    assert np.array_equal(yk, y1.astype(np.float64) * s_out[:, None])
+    # K = E with equal logits: the plain average of all experts, each evaluated on the whole batch
+    yk, sel, w, counts = nets.moe_topk_int(x, 0.02, np.zeros((B, E)), E, layers, params, scales, "int8")
+    mean = 0.0
+    for j in range(E):
+        a = nets.int_conv(x, 0, 0.02, params[j][0][0], 0, params[j][0][1], layers[0], scales[j][0], "int8")
+        a = nets.int_fc(a.reshape(B, -1), 0, scales[j][0]["y"], params[j][1][0], 0, params[j][1][1],
+                        layers[1], scales[j][1], "int8")
+        mean = mean + a.astype(np.float64) * np.float64(np.float32(scales[j][1]["y"])) / E
+    assert np.allclose(yk, mean, rtol=1e-13, atol=1e-12) and counts.tolist() == [B] * E
+    # samples are independent: a permutation of the batch permutes the result
+    yk, sel, w, _ = nets.moe_topk_int(x, 0.02, lg, 2, layers, params, scales, "int8")
+    perm = gen.permutation(3, B)
+    y2, sel2, w2, _ = nets.moe_topk_int(x[perm], 0.02, lg[perm], 2, layers, params, scales, "int8")
+    assert np.array_equal(y2, yk[perm]) and np.array_equal(sel2, sel[perm]) and np.array_equal(w2, w[perm])
+
+
 def test_moe_all_to_one_expert_and_permutation_invariance():
     layers, params, scales, x, E = _tiny_moe()
     B = x.shape[0]
