@@ -158,6 +158,30 @@ def moe_topk_int(xq, s_x, logits, top_k, expert_layers, expert_params_q, expert_
     return out, sel, w, counts
 
 
+def moe_topk_fp16(x16, logits, top_k, expert_layers, expert_params16):
+    """K experts per sample with fp16 storage: an expert's output is an fp16 tensor (its fp64
+    value rounded to fp16); the mixture is the weighted sum of those, as in moe_topk_int."""
+    sel, w, counts = o.route_topk(logits, top_k)
+    out = None
+    for b in range(x16.shape[0]):
+        acc = 0.0
+        for k in range(top_k):
+            a = x16[b:b + 1]
+            for L, (w16, b32) in zip(expert_layers, expert_params16[int(sel[b, k])]):
+                if L.kind == "conv":
+                    y = o.conv2d_f64(a, w16, b32, L.stride, L.pad, L.groups, L.relu)
+                    if L.pool_k:
+                        y = o.maxpool_f64(y, L.pool_k, L.pool_s)
+                else:
+                    y = o.gemm_f64(a.reshape(1, -1), w16, b32, L.relu)
+                a = o.round_fp16(y)
+            acc = acc + w[b, k] * a[0]
+        if out is None:
+            out = np.empty((x16.shape[0],) + acc.shape, np.float64)
+        out[b] = acc
+    return out, sel, w, counts
+
+
 def moe_fp16(x16, logits, expert_layers, expert_params16):
     e_idx, counts = o.route_top1(logits)
     out = None

@@ -93,6 +93,25 @@ def test_moe_topk_reduces_to_one_expert_and_to_the_plain_average():
     assert np.array_equal(y2, yk[perm]) and np.array_equal(sel2, sel[perm]) and np.array_equal(w2, w[perm])
 
 
+def test_moe_topk_fp16_one_expert_case():
+    """K = 1 of the fp16 mixture is the one-expert result rounded to its fp16 storage."""
+    layers = [cf.Conv("c", 6, 4, 3, 3, pad=1, groups=2, pool_k=3, pool_s=2), cf.FC("f", 5, 6 * 2 * 2)]
+    E, B = 3, 7
+    params = [[(o.round_fp16(gen.normal(500 + e, (6, 2, 3, 3), 0, 0.3)), gen.normal(510 + e, (6,), 0, 0.1)),
+               (o.round_fp16(gen.normal(520 + e, (5, 24), 0, 0.2)), gen.normal(530 + e, (5,), 0, 0.1))] for e in range(E)]
+    x = o.round_fp16(gen.normal(540, (B, 4, 5, 5)))
+    lg = gen.normal(541, (B, E))
+    y1, e_idx, _ = nets.moe_fp16(x, lg, layers, params)
+    yk, sel, w, _ = nets.moe_topk_fp16(x, lg, 1, layers, params)
+    assert np.array_equal(sel[:, 0], e_idx) and np.array_equal(yk, o.round_fp16(y1))
+    # two experts with equal logits: the mean of the two experts' fp16 outputs
+    lg2 = np.zeros((B, E)); lg2[:, 1] = -30.0
+    yk, sel, w, _ = nets.moe_topk_fp16(x, lg2, 2, layers, params)
+    ya = o.round_fp16(nets.moe_fp16(x, np.tile([1.0, 0, 0], (B, 1)), layers, params)[0])
+    yc = o.round_fp16(nets.moe_fp16(x, np.tile([0, 0, 1.0], (B, 1)), layers, params)[0])
+    assert sel.tolist() == [[0, 2]] * B and np.allclose(yk, 0.5 * (ya + yc), rtol=1e-14, atol=0)
+
+
 def test_moe_all_to_one_expert_and_permutation_invariance():
     layers, params, scales, x, E = _tiny_moe()
     B = x.shape[0]
