@@ -194,14 +194,21 @@ mpq_status mpq_gemm(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q,
 mpq_status mpq_maxpool2d(const mpq_tensor *x, mpq_tensor *y, int32_t k, int32_t s, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
- * Mixture-of-experts stage, one expert per sample (section "Mixture of Experts": the gating
- * selection picks experts per sample; outputs of the selected experts are summed weighted by
- * probabilities renormalised over the selection -- with top_k = 1 that weight is 1).
+ * Mixture-of-experts stage (section "Mixture of Experts": the gating selection picks experts
+ * per sample; outputs of the selected experts are summed weighted by probabilities renormalised
+ * over the selection -- with top_k = 1 that weight is 1).
+ * top_k = 1:
  *   expert[b] = argmax_i logits[b, i]   (lowest index on ties)
- *   y[b]      = expert_chain[expert[b]](x[b])
+ *   y[b]      = expert_chain[expert[b]](x[b])          (storage type, codes)
+ * top_k = K > 1 (fp32 logits, fp32 output):
+ *   expert[b][k], k < K: the K largest logits of row b, largest first, lower index first among equals
+ *   p[b][k]   = exp(l_k - l_0) / sum_j exp(l_j - l_0) over the K chosen logits, in fp32
+ *   y[b]      = sum_k p[b][k] * real(expert_chain[expert[b][k]](x[b])),  fp32, k ascending;
+ *               real(q) = scale_e (q - zero_e) with the expert's last-layer output parameters
+ *               (fp16 experts: the fp16 value)
  * Internally: route -> per-expert counts / exclusive offsets / stable permutation -> gather the
- * samples into expert-contiguous order -> each layer as ONE launch over all experts' segments
- * -> scatter rows back to sample order.
+ * samples (K copies of each for K > 1) into expert-contiguous order -> each layer as ONE launch
+ * over all experts' segments -> scatter rows back to sample order (K = 1) or mix (K > 1).
  *
  * All experts share layer geometry ("identical input and output tensor dimensions") and differ
  * in weights and quantization parameters.
@@ -216,17 +223,23 @@ typedef struct {
     const mpq_qparams *y_q;    /* host: [num_experts] output parameters of this layer */
 } mpq_moe_layer;
 
+/* workspace for top_k = 1, and for any top_k (x is the [B, h, w, c] trunk output in both) */
 size_t mpq_moe_workspace_bytes(const mpq_tensor *x, int32_t num_experts,
                                const mpq_moe_layer *layers /* host */, int32_t num_layers);
+size_t mpq_moe_topk_workspace_bytes(const mpq_tensor *x, int32_t num_experts, int32_t top_k,
+                                    const mpq_moe_layer *layers /* host */, int32_t num_layers);
 /*
  *   x            trunk output [B, h, w, c]
- *   logits       device [B, num_experts], logits_dtype MPQ_INT32 or MPQ_FP32
- *   top_k        must be 1
+ *   logits       device [B, num_experts], logits_dtype MPQ_INT32 or MPQ_FP32 (top_k > 1: MPQ_FP32,
+ *                real-valued logits; dequantize raw gating accumulators with mpq_dequantize first)
+ *   top_k        1 .. num_experts
  *   layers       host array of num_layers descriptors
  *   y            [B, 1, 1, n_out] (or [B, h', w', c'] if the last layer is a convolution);
- *                y->q is ignored: row b carries its expert's last-layer parameters
- *   expert_index optional device out [B]; expert_counts optional device out [num_experts]
- *                (the c_i of the paper's load-balancing term)
+ *                top_k = 1: dtype of x, y->q is ignored: row b carries its expert's last-layer
+ *                parameters; top_k > 1: MPQ_FP32
+ *   expert_index optional device out [B * top_k] (sample-major, best first); expert_counts
+ *                optional device out [num_experts] (the c_i of the paper's load-balancing term)
+ *   ws           at least mpq_moe_topk_workspace_bytes(x, num_experts, top_k, ...) bytes
  */
 mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype logits_dtype,
                            int32_t num_experts, int32_t top_k,

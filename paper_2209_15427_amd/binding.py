@@ -22,7 +22,7 @@ EXPORTS = ["mpq_status_string", "mpq_abi_version", "mpq_quantize", "mpq_dequanti
            "mpq_from_fp16", "mpq_scale_quant_vals", "mpq_observe_minmax", "mpq_estimate_params",
            "mpq_packed_weight_bytes", "mpq_pack_weights",
            "mpq_conv2d_workspace_bytes", "mpq_conv2d", "mpq_gemm_desc", "mpq_gemm_workspace_bytes",
-           "mpq_gemm", "mpq_maxpool2d", "mpq_moe_workspace_bytes", "mpq_moe_forward"]
+           "mpq_gemm", "mpq_maxpool2d", "mpq_moe_workspace_bytes", "mpq_moe_topk_workspace_bytes", "mpq_moe_forward"]
 
 
 class QParams(C.Structure):
@@ -92,6 +92,8 @@ def lib():
         L.mpq_maxpool2d.argtypes = [TP, TP, i32, i32, vp]
         L.mpq_moe_workspace_bytes.restype = sz
         L.mpq_moe_workspace_bytes.argtypes = [TP, i32, C.POINTER(MoeLayer), i32]
+        L.mpq_moe_topk_workspace_bytes.restype = sz
+        L.mpq_moe_topk_workspace_bytes.argtypes = [TP, i32, i32, C.POINTER(MoeLayer), i32]
         L.mpq_moe_forward.argtypes = [TP, vp, C.c_int, i32, i32, C.POINTER(MoeLayer), i32, TP, vp, vp,
                                       vp, sz, vp]
         for name in EXPORTS:
@@ -203,6 +205,11 @@ def mpq_maxpool2d(x, y, k, s, stream=None):
 def mpq_moe_workspace_bytes(x, num_experts, layers):
     arr = (MoeLayer * len(layers))(*layers)
     return int(lib().mpq_moe_workspace_bytes(C.byref(x), num_experts, arr, len(layers)))
+
+
+def mpq_moe_topk_workspace_bytes(x, num_experts, top_k, layers):
+    arr = (MoeLayer * len(layers))(*layers)
+    return int(lib().mpq_moe_topk_workspace_bytes(C.byref(x), num_experts, top_k, arr, len(layers)))
 
 
 def mpq_moe_forward(x, logits, logits_dtype, num_experts, top_k, layers, y, expert_index=None,

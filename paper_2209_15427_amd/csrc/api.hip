@@ -668,14 +668,20 @@ struct MoeShapes {
 
 struct MoeWs {
     size_t expert_off, counts_off, offsets_off, perm_off;   // int arrays
+    size_t inv_off, weight_off;                             // K experts per sample: entry -> row, mixing weights
     size_t buf_off[2];                                      // ping-pong activations (gathered order)
     size_t buf_bytes;
     size_t layer_ws_off, layer_ws_bytes;
     size_t total;
 };
 
-mpq_status moe_plan(const mpq_tensor &x, int E, const mpq_moe_layer *layers, int L, MoeShapes *sh, MoeWs *ws) {
+// (K experts per sample: the expert layers see rows = K * batch entries)
+mpq_status moe_plan(const mpq_tensor &x_in, int E, int K, const mpq_moe_layer *layers, int L, MoeShapes *sh, MoeWs *ws) {
     if (L < 1 || L > 16 || E < 1 || E > kMaxExperts) return MPQ_ERR_UNSUPPORTED;
+    if (K < 1 || K > E) return MPQ_ERR_INVALID_ARG;
+    if ((long long)x_in.n * K > 0x7fffffffll) return MPQ_ERR_UNSUPPORTED;
+    mpq_tensor x = x_in;
+    x.n = x_in.n * K;
     sh->h[0] = x.h; sh->w[0] = x.w; sh->c[0] = x.c;
     size_t max_act = (size_t)x.n * x.h * x.w * x.c * dtype_size(x.dtype);
     size_t max_ws = 0;
@@ -709,6 +715,8 @@ mpq_status moe_plan(const mpq_tensor &x, int E, const mpq_moe_layer *layers, int
     ws->counts_off = off;  off += round_up((size_t)E * 4, 256);
     ws->offsets_off = off; off += round_up((size_t)(E + 1) * 4, 256);
     ws->perm_off = off;    off += round_up((size_t)x.n * 4, 256);
+    ws->inv_off = off;     off += K > 1 ? round_up((size_t)x.n * 4, 256) : 0;
+    ws->weight_off = off;  off += K > 1 ? round_up((size_t)x.n * 4, 256) : 0;
     ws->buf_bytes = round_up(max_act, 256);
     ws->buf_off[0] = off;  off += ws->buf_bytes;
     ws->buf_off[1] = off;  off += ws->buf_bytes;
@@ -726,7 +734,16 @@ size_t mpq_moe_workspace_bytes(const mpq_tensor *x, int32_t num_experts, const m
     if (!x || !layers) return 0;
     MoeShapes sh;
     MoeWs ws;
-    if (moe_plan(*x, num_experts, layers, num_layers, &sh, &ws) != MPQ_OK) return 0;
+    if (moe_plan(*x, num_experts, 1, layers, num_layers, &sh, &ws) != MPQ_OK) return 0;
+    return ws.total;
+}
+
+size_t mpq_moe_topk_workspace_bytes(const mpq_tensor *x, int32_t num_experts, int32_t top_k,
+                                    const mpq_moe_layer *layers, int32_t num_layers) {
+    if (!x || !layers) return 0;
+    MoeShapes sh;
+    MoeWs ws;
+    if (moe_plan(*x, num_experts, top_k, layers, num_layers, &sh, &ws) != MPQ_OK) return 0;
     return ws.total;
 }
 
@@ -735,17 +752,19 @@ mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype lo
                            int32_t num_layers, mpq_tensor *y, int32_t *expert_index,
                            int32_t *expert_counts, void *ws, size_t ws_bytes, void *stream) {
     if (!x || !y || !layers || !logits) return MPQ_ERR_INVALID_ARG;
-    if (top_k != 1) return MPQ_ERR_UNSUPPORTED;
+    if (top_k < 1 || top_k > num_experts) return MPQ_ERR_INVALID_ARG;
     if (logits_dtype != MPQ_INT32 && logits_dtype != MPQ_FP32) return MPQ_ERR_INVALID_ARG;
     if (x->dtype != MPQ_INT8 && x->dtype != MPQ_INT16 && x->dtype != MPQ_FP16) return MPQ_ERR_INVALID_ARG;
-    if (y->dtype != x->dtype) return MPQ_ERR_UNSUPPORTED;
+    const int K = top_k;
+    // several experts per sample are mixed in real values: fp32 output, and probabilities need real logits
+    if (K == 1 ? y->dtype != x->dtype : (y->dtype != MPQ_FP32 || logits_dtype != MPQ_FP32)) return MPQ_ERR_UNSUPPORTED;
     if (x->n < 0 || x->h < 1 || x->w < 1 || x->c < 1) return MPQ_ERR_SHAPE;
     if (!qparams_ok(x->dtype, x->q)) return MPQ_ERR_INVALID_ARG;
     MoeShapes sh;
     MoeWs wl;
-    mpq_status s = moe_plan(*x, num_experts, layers, num_layers, &sh, &wl);
+    mpq_status s = moe_plan(*x, num_experts, K, layers, num_layers, &sh, &wl);
     if (s != MPQ_OK) return s;
-    const int L = num_layers, E = num_experts, B = x->n;
+    const int L = num_layers, E = num_experts, B = x->n, T = B * K;
     if (y->n != B || (size_t)y->h * y->w * y->c != (size_t)sh.h[L] * sh.w[L] * sh.c[L]) return MPQ_ERR_SHAPE;
     for (int i = 0; i < L; ++i) {
         if (!layers[i].w_packed || !layers[i].w_q || !layers[i].y_q) return MPQ_ERR_INVALID_ARG;
@@ -779,13 +798,21 @@ mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype lo
     int *d_perm = reinterpret_cast<int *>(wsb + wl.perm_off);
     const int es = dtype_size(x->dtype);
 
-    // selection stage: arg-max expert per sample, counts c_i, offsets, stable permutation
-    if (launch_route(logits, logits_dtype, B, E, expert_index ? expert_index : d_expert,
-                     expert_counts ? expert_counts : d_counts, d_offsets, d_perm, st) != hipSuccess)
+    int *d_inv = reinterpret_cast<int *>(wsb + wl.inv_off);
+    float *d_weight = reinterpret_cast<float *>(wsb + wl.weight_off);
+    int *sel = expert_index ? expert_index : d_expert;
+    // selection stage: arg-max expert (or the K best) per sample, counts c_i, offsets, stable permutation
+    if (K == 1) {
+        if (launch_route(logits, logits_dtype, B, E, sel, expert_counts ? expert_counts : d_counts, d_offsets, d_perm,
+                         st) != hipSuccess)
+            return MPQ_ERR_DEVICE;
+    } else if (launch_route_topk((const float *)logits, B, E, K, sel, d_weight, expert_counts ? expert_counts : d_counts,
+                                 d_offsets, d_perm, d_inv, st) != hipSuccess) {
         return MPQ_ERR_DEVICE;
-    // gather samples into expert-contiguous order
+    }
+    // gather samples into expert-contiguous order (entry t of a K-expert routing reads sample t / K)
     size_t row_in = (size_t)x->h * x->w * x->c * es;
-    if (launch_gather_rows(x->data, wsb + wl.buf_off[0], d_perm, B, row_in, st) != hipSuccess)
+    if (launch_gather_rows(x->data, wsb + wl.buf_off[0], d_perm, T, row_in, st, K) != hipSuccess)
         return MPQ_ERR_DEVICE;
     int cur = 0;
     bool scattered = false;
@@ -795,7 +822,7 @@ mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype lo
         std::memset(&in, 0, sizeof(in));
         in.data = wsb + wl.buf_off[cur];
         in.dtype = x->dtype;
-        in.n = B;
+        in.n = T;
         if (ly.is_fc) {
             in.h = in.w = 1;
             in.c = sh.h[i] * sh.w[i] * sh.c[i];
@@ -803,7 +830,7 @@ mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype lo
             in.h = sh.h[i]; in.w = sh.w[i]; in.c = sh.c[i];
         }
         segs[i].offsets = d_offsets;
-        if (i == L - 1) {          // the last layer may write straight into sample order
+        if (i == L - 1 && K == 1) {          // the last layer may write straight into sample order
             segs[i].out_perm = d_perm;
             segs[i].out_perm_y = y->data;
             segs[i].out_perm_done = &scattered;
@@ -812,6 +839,17 @@ mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype lo
                      &segs[i], wsb + wl.layer_ws_off, wl.layer_ws_bytes, st);
         if (s != MPQ_OK) return s;
         cur ^= 1;
+    }
+    if (K > 1) {
+        // mixing: the K rows of a sample, back in real values, weighted by the renormalised probabilities
+        MixScales ms;
+        for (int e = 0; e < kMaxExperts; ++e) {
+            ms.scale[e] = e < E && x->dtype != MPQ_FP16 ? layers[L - 1].y_q[e].scale : 1.f;
+            ms.zero[e] = e < E && x->dtype != MPQ_FP16 ? layers[L - 1].y_q[e].zero_point : 0;
+        }
+        const int n_out = sh.h[L] * sh.w[L] * sh.c[L];
+        return launch_moe_mix(wsb + wl.buf_off[cur], x->dtype, d_inv, sel, d_weight, (float *)y->data, B, K, n_out, ms,
+                              st) == hipSuccess ? MPQ_OK : MPQ_ERR_DEVICE;
     }
     // scatter rows back to sample order (unless the last layer's kernel did)
     size_t row_out = (size_t)sh.h[L] * sh.w[L] * sh.c[L] * es;

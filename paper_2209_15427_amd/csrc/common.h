@@ -196,8 +196,16 @@ hipError_t launch_fc_frag(const ConvArgs &a, void *ws_fc, hipStream_t st);
 // MoE helpers
 hipError_t launch_route(const void *logits, int logits_dtype, int B, int E, int *expert, int *counts,
                         int *offsets, int *perm, hipStream_t st);
+struct MixScales {
+    float scale[kMaxExperts];
+    int zero[kMaxExperts];
+};
+hipError_t launch_route_topk(const float *logits, int B, int E, int K, int *expert, float *weight, int *counts,
+                             int *offsets, int *perm, int *inv, hipStream_t st);
+hipError_t launch_moe_mix(const void *rows, int dtype, const int *inv, const int *expert, const float *weight,
+                          float *y, int B, int K, int N, const MixScales &sc, hipStream_t st);
 hipError_t launch_gather_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes,
-                              hipStream_t st);
+                              hipStream_t st, int div = 1);
 hipError_t launch_scatter_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes,
                                hipStream_t st);
 

@@ -85,11 +85,115 @@ route_kernel(const LT *__restrict__ logits, int B, int E, int *__restrict__ expe
     }
 }
 
-// dst row i = src row perm[i] (gather) or dst row perm[i] = src row i (scatter)
+// K experts per sample.  Entry t = b * K + k is sample b's k-th choice: the largest remaining
+// logit, the lower index among equal ones.  weight[t] is the gating probability renormalised over
+// the sample's K choices (the softmax of the chosen logits alone), in fp32.  The entries are then
+// bucketed by expert exactly as the samples are above: perm[pos] = entry, inv[entry] = pos.
+__global__ void __launch_bounds__(kThreads)
+route_topk_kernel(const float *__restrict__ logits, int B, int E, int K, int *__restrict__ expert,
+                  float *__restrict__ weight, int *__restrict__ counts, int *__restrict__ offsets,
+                  int *__restrict__ perm, int *__restrict__ inv) {
+    __shared__ int cnt[kMaxExperts];
+    __shared__ int running[kMaxExperts];
+    __shared__ int wave_cnt[kWaves][kMaxExperts];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < kMaxExperts) cnt[tid] = 0;
+    __syncthreads();
+
+    for (int b = tid; b < B; b += kThreads) {
+        const float *row = logits + (size_t)b * E;
+        unsigned taken = 0;
+        float top = 0.f, sum = 0.f;
+#pragma unroll 1
+        for (int k = 0; k < K; ++k) {
+            int best = -1;
+            float bv = 0.f;
+            for (int i = 0; i < E; ++i) {
+                if (taken & (1u << i)) continue;
+                const float v = row[i];
+                if (best < 0 || v > bv) { bv = v; best = i; }
+            }
+            taken |= 1u << best;
+            if (k == 0) top = bv;
+            const float qk = expf(bv - top);
+            weight[(size_t)b * K + k] = qk;       // (normalised below, by the same thread)
+            sum += qk;
+            expert[(size_t)b * K + k] = best;
+            atomicAdd(&cnt[best], 1);
+        }
+#pragma unroll 1
+        for (int k = 0; k < K; ++k) weight[(size_t)b * K + k] = weight[(size_t)b * K + k] / sum;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int e = 0; e < E; ++e) {
+            offsets[e] = run;
+            running[e] = run;
+            counts[e] = cnt[e];
+            run += cnt[e];
+        }
+        offsets[E] = run;
+    }
+    __syncthreads();
+
+    const int T = B * K;
+    for (int t0 = 0; t0 < T; t0 += kThreads) {
+        const int t = t0 + tid;
+        const bool valid = t < T;
+        const int mine = valid ? expert[t] : -1;
+        int rank = 0;
+        for (int e = 0; e < E; ++e) {
+            unsigned long long mask = __ballot(mine == e);
+            if (lane == 0) wave_cnt[wave][e] = __popcll(mask);
+            if (mine == e) rank = __popcll(mask & ((1ull << lane) - 1ull));
+        }
+        __syncthreads();
+        if (valid) {
+            int pos = running[mine] + rank;
+            for (int w = 0; w < wave; ++w) pos += wave_cnt[w][mine];
+            perm[pos] = t;
+            inv[t] = pos;
+        }
+        __syncthreads();
+        if (tid < E) {
+            int add = 0;
+            for (int w = 0; w < kWaves; ++w) add += wave_cnt[w][tid];
+            running[tid] += add;
+        }
+        __syncthreads();
+    }
+}
+
+// y[b][j] = sum_k weight[b K + k] * real(rows[inv[b K + k]][j]), real(v) = scale[e] (v - zero[e])
+// for codes and v itself for fp16; fp32 sums in the order of k.
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+moe_mix_kernel(const T *__restrict__ rows, const int *__restrict__ inv, const int *__restrict__ expert,
+               const float *__restrict__ weight, float *__restrict__ y, int B, int K, int N, MixScales sc) {
+    const size_t total = (size_t)B * N;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * kThreads;
+    for (; i < total; i += step) {
+        const int b = (int)(i / N), j = (int)(i % N);
+        float acc = 0.f;
+        for (int k = 0; k < K; ++k) {
+            const int t = b * K + k, e = expert[t];
+            const T v = rows[(size_t)inv[t] * N + j];
+            float r;
+            if constexpr (sizeof(T) == 2 && !__is_same(T, int16_t)) r = (float)v;
+            else r = sc.scale[e] * (float)((int)v - sc.zero[e]);
+            acc += weight[t] * r;
+        }
+        y[i] = acc;
+    }
+}
+
+// dst row i = src row perm[i] / div (gather) or dst row perm[i] = src row i (scatter)
 template <bool kScatter>
 __global__ void __launch_bounds__(kThreads)
 move_rows_kernel(const char *__restrict__ src, char *__restrict__ dst, const int *__restrict__ perm, int B,
-                 size_t row_bytes, int vec) {
+                 size_t row_bytes, int vec, int div) {
     const size_t per_row = vec ? row_bytes / 16 : row_bytes;
     const size_t total = (size_t)B * per_row;
     size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -97,7 +201,7 @@ move_rows_kernel(const char *__restrict__ src, char *__restrict__ dst, const int
     for (size_t i = tid; i < total; i += nthreads) {
         const int row = (int)(i / per_row);
         const size_t off = i % per_row;
-        const int other = perm[row];
+        const int other = kScatter ? perm[row] : perm[row] / div;
         const size_t srow = kScatter ? row : other, drow = kScatter ? other : row;
         if (vec) {
             reinterpret_cast<uint4 *>(dst + drow * row_bytes)[off] =
@@ -109,7 +213,7 @@ move_rows_kernel(const char *__restrict__ src, char *__restrict__ dst, const int
 }
 
 template <bool kScatter>
-hipError_t move_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes, hipStream_t st) {
+hipError_t move_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes, hipStream_t st, int div = 1) {
     if (B == 0 || row_bytes == 0) return hipSuccess;
     int vec = (row_bytes % 16 == 0) && (reinterpret_cast<uintptr_t>(src) % 16 == 0) &&
               (reinterpret_cast<uintptr_t>(dst) % 16 == 0);
@@ -117,7 +221,7 @@ hipError_t move_rows(const void *src, void *dst, const int *perm, int B, size_t 
     size_t blocks = (work + kThreads - 1) / kThreads;
     if (blocks > 256 * 32) blocks = 256 * 32;
     move_rows_kernel<kScatter><<<(int)blocks, kThreads, 0, st>>>((const char *)src, (char *)dst, perm, B,
-                                                                row_bytes, vec);
+                                                                row_bytes, vec, div);
     return hipGetLastError();
 }
 
@@ -132,9 +236,31 @@ hipError_t launch_route(const void *logits, int logits_dtype, int B, int E, int 
     return hipGetLastError();
 }
 
+hipError_t launch_route_topk(const float *logits, int B, int E, int K, int *expert, float *weight, int *counts,
+                             int *offsets, int *perm, int *inv, hipStream_t st) {
+    route_topk_kernel<<<1, kThreads, 0, st>>>(logits, B, E, K, expert, weight, counts, offsets, perm, inv);
+    return hipGetLastError();
+}
+
+hipError_t launch_moe_mix(const void *rows, int dtype, const int *inv, const int *expert, const float *weight,
+                          float *y, int B, int K, int N, const MixScales &sc, hipStream_t st) {
+    const size_t total = (size_t)B * N;
+    if (total == 0) return hipSuccess;
+    size_t blocks = (total + kThreads - 1) / kThreads;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (dtype == MPQ_INT8)
+        moe_mix_kernel<int8_t><<<(int)blocks, kThreads, 0, st>>>((const int8_t *)rows, inv, expert, weight, y, B, K, N, sc);
+    else if (dtype == MPQ_INT16)
+        moe_mix_kernel<int16_t><<<(int)blocks, kThreads, 0, st>>>((const int16_t *)rows, inv, expert, weight, y, B, K, N, sc);
+    else
+        moe_mix_kernel<_Float16><<<(int)blocks, kThreads, 0, st>>>((const _Float16 *)rows, inv, expert, weight, y, B, K, N, sc);
+    return hipGetLastError();
+}
+
+// (div > 1: entry perm[i] of a K-experts-per-sample routing reads sample perm[i] / K)
 hipError_t launch_gather_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes,
-                              hipStream_t st) {
-    return move_rows<false>(src, dst, perm, B, row_bytes, st);
+                              hipStream_t st, int div) {
+    return move_rows<false>(src, dst, perm, B, row_bytes, st, div);
 }
 
 hipError_t launch_scatter_rows(const void *src, void *dst, const int *perm, int B, size_t row_bytes,

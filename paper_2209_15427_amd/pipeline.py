@@ -156,9 +156,9 @@ class MoE:
     enqueues mpq_moe_forward.  params[e][i] = (w, b) real-valued (converted by the library) or,
     with codes=True, already storage codes / int32 bias codes."""
 
-    def __init__(self, specs, params, dtype, batch, in_hwc, s_in=1.0, scales=None, codes=False):
+    def __init__(self, specs, params, dtype, batch, in_hwc, s_in=1.0, scales=None, codes=False, top_k=1):
         import ctypes as C
-        self.dtype, self.batch, self.E = dtype, batch, len(params)
+        self.dtype, self.batch, self.E, self.top_k = dtype, batch, len(params), top_k
         E = self.E
         h, w, c = in_hwc
         self.in_shape = (batch, h, w, c)
@@ -211,17 +211,19 @@ class MoE:
                     P, Q = (P - L.pool_k) // L.pool_s + 1, (Q - L.pool_k) // L.pool_s + 1
                 shape = (P, Q, L.K)
         self.out_shape = (batch,) + shape
-        self.y = torch.empty(self.out_shape, dtype=mb.TORCH_DTYPE[dtype], device=DEV)
-        self.expert_index = torch.empty((batch,), dtype=torch.int32, device=DEV)
+        # (several experts per sample are mixed in real values: fp32 output)
+        self.y_dtype = dtype if top_k == 1 else mb.FP32
+        self.y = torch.empty(self.out_shape, dtype=mb.TORCH_DTYPE[self.y_dtype], device=DEV)
+        self.expert_index = torch.empty((batch * top_k,), dtype=torch.int32, device=DEV)
         self.expert_counts = torch.empty((E,), dtype=torch.int32, device=DEV)
         xv = mb.tensor(None, dtype, *self.in_shape, scale=s_in)
-        self.ws_bytes = mb.mpq_moe_workspace_bytes(xv, E, self.layers)
+        self.ws_bytes = mb.mpq_moe_topk_workspace_bytes(xv, E, top_k, self.layers)
         self.ws = alloc_bytes(self.ws_bytes)
         torch.cuda.synchronize()
 
     def forward(self, x_storage, logits, logits_dtype):
         xv = mb.tensor(x_storage, self.dtype, *self.in_shape, scale=self.s_in)
-        yv = mb.tensor(self.y, self.dtype, *self.out_shape)
-        mb.mpq_moe_forward(xv, logits, logits_dtype, self.E, 1, self.layers, yv, self.expert_index,
+        yv = mb.tensor(self.y, self.y_dtype, *self.out_shape)
+        mb.mpq_moe_forward(xv, logits, logits_dtype, self.E, self.top_k, self.layers, yv, self.expert_index,
                            self.expert_counts, self.ws, self.ws_bytes)
         return self.y

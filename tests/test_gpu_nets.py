@@ -116,7 +116,7 @@ def test_fc_layers(layer, batch, dtype):
 # ---------------------------------------------------------------------------------------------
 # mixture of experts
 # ---------------------------------------------------------------------------------------------
-def _moe_device(x_codes_nchw, s_x, logits, layers, params_q, scales, dtype, logits_dtype):
+def _moe_device(x_codes_nchw, s_x, logits, layers, params_q, scales, dtype, logits_dtype, top_k=1):
     """params_q[e][i] = (w codes logical layout, bias codes); everything uploaded and packed per
     expert into one buffer per layer with a uniform stride."""
     E = len(params_q)
@@ -162,13 +162,14 @@ def _moe_device(x_codes_nchw, s_x, logits, layers, params_q, scales, dtype, logi
             shape = (P, Q, L.K)
     lg = torch.from_numpy(np.ascontiguousarray(logits)).to(torch.int32 if logits_dtype == mb.INT32 else torch.float32).to("cuda")
     xv = mb.tensor(xd, dtype, B, H, W, Cc, s_x)
-    y = torch.full((B,) + shape, 55, dtype=mb.TORCH_DTYPE[dtype], device="cuda")
-    yv = mb.tensor(y, dtype, B, *shape)
-    nws = mb.mpq_moe_workspace_bytes(xv, E, mls)
+    y_dtype = dtype if top_k == 1 else mb.FP32
+    y = torch.full((B,) + shape, 55, dtype=mb.TORCH_DTYPE[y_dtype], device="cuda")
+    yv = mb.tensor(y, y_dtype, B, *shape)
+    nws = mb.mpq_moe_workspace_bytes(xv, E, mls) if top_k == 1 else mb.mpq_moe_topk_workspace_bytes(xv, E, top_k, mls)
     ws = pl.alloc_bytes(nws)
-    idx = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    idx = torch.full((B * top_k,), -1, dtype=torch.int32, device="cuda")
     cnt = torch.full((E,), -1, dtype=torch.int32, device="cuda")
-    mb.mpq_moe_forward(xv, lg, logits_dtype, E, 1, mls, yv, idx, cnt, ws, nws)
+    mb.mpq_moe_forward(xv, lg, logits_dtype, E, top_k, mls, yv, idx, cnt, ws, nws)
     torch.cuda.synchronize()
     return y, idx.cpu().numpy(), cnt.cpu().numpy()
 
@@ -207,6 +208,46 @@ def test_moe_small_int(dtype, B):
     assert len(np.unique(ref)) > 8
 
 
+@pytest.mark.parametrize("dtype", ["int8", "int16"])
+@pytest.mark.parametrize("B,K", [(1, 2), (37, 2), (300, 3), (64, 1)])
+def test_moe_topk_mixing(dtype, B, K):
+    """K experts per sample: the selection is exact; the mixed fp32 output is the oracle's fp64 sum
+    within fp32 arithmetic (weights from fp32 exp and one division, K products and sums:
+    a few 1e-7 relative to the largest term)."""
+    _say("moe top-k", dtype, B, K)
+    layers, params, scales, x, E = _tiny_moe_case(dtype, B, 900)
+    s_x = 0.02 * 127.0 / (127 if dtype == "int8" else 32767)
+    logits = gen.normal(15, (B, E), 0.0, 1.5).astype(np.float32)
+    if B >= 4:
+        logits[1] = logits[1, 0]          # a three-way tie
+        logits[2, 1:] = logits[2, 2]      # tie between experts 1 and 2
+    if K == 1:
+        # one expert per sample through the same entry point keeps its storage-type output
+        y, idx, cnt = _moe_device(x, s_x, logits, layers, params, scales, DT[dtype], mb.FP32)
+        ref, e_ref, c_ref = nets.moe_int(x, s_x, logits.astype(np.float64), layers, params, scales, dtype)
+        assert np.array_equal(idx, e_ref) and np.array_equal(y.cpu().numpy().reshape(ref.shape).astype(np.int32), ref)
+        return
+    y, idx, cnt = _moe_device(x, s_x, logits, layers, params, scales, DT[dtype], mb.FP32, top_k=K)
+    ref, sel, w, c_ref = nets.moe_topk_int(x, s_x, logits, K, layers, params, scales, dtype)
+    assert np.array_equal(idx.reshape(B, K), sel) and np.array_equal(cnt, c_ref) and cnt.sum() == B * K
+    got = y.cpu().numpy().reshape(ref.shape).astype(np.float64)
+    bound = 2e-6 * np.max(np.abs(ref), axis=tuple(range(1, ref.ndim)), keepdims=True) * K
+    assert np.all(np.abs(got - ref) <= bound + 1e-30), float(np.max(np.abs(got - ref) / (bound + 1e-30)))
+    assert np.std(ref) > 0
+
+
+def test_moe_topk_argument_errors():
+    layers, params, scales, x, E = _tiny_moe_case("int8", 4, 950)
+    lg = gen.normal(16, (4, E)).astype(np.float32)
+    for bad_k in (0, E + 1):
+        with pytest.raises(mb.MpqError) as e:
+            _moe_device(x, 0.02, lg, layers, params, scales, mb.INT8, mb.FP32, top_k=bad_k)
+        assert e.value.status in (1, 4)
+    with pytest.raises(mb.MpqError) as e:      # probabilities need real-valued logits
+        _moe_device(x, 0.02, lg, layers, params, scales, mb.INT8, mb.INT32, top_k=2)
+    assert e.value.status == 3
+
+
 def test_moe_all_to_one_expert_and_empty_experts():
     layers, params, scales, x, E = _tiny_moe_case("int8", 20, 800)
     logits = gen.integers(6, (20, E), -50, 50)
@@ -215,6 +256,24 @@ def test_moe_all_to_one_expert_and_empty_experts():
     assert list(cnt) == [0, 0, 20] and (idx == 2).all()
     ref, _, _ = nets.moe_int(x, 0.02, logits.astype(np.float64), layers, params, scales, "int8")
     assert np.array_equal(y.cpu().numpy().reshape(ref.shape).astype(np.int32), ref)
+
+
+def test_moe_topk_fp16():
+    layers = [cf.Conv("c", 64, 32, 3, 3, pad=1, groups=2, pool_k=3, pool_s=2), cf.FC("f", 40, 64 * 3 * 3)]
+    E, B, K = 4, 50, 2
+    params = []
+    for e in range(E):
+        params.append([(o.round_fp16(gen.normal(900 + e, (64, 16, 3, 3), 0, 0.1)), gen.normal(910 + e, (64,), 0, 0.1).astype(np.float32)),
+                       (o.round_fp16(gen.normal(920 + e, (40, 576), 0, 0.05)), gen.normal(930 + e, (40,), 0, 0.1).astype(np.float32))])
+    x = o.round_fp16(gen.normal(940, (B, 32, 7, 7)))
+    logits = gen.normal(941, (B, E)).astype(np.float32)
+    scales = [[{"w": 1.0, "y": 1.0}] * 2] * E
+    y, idx, cnt = _moe_device(x, 1.0, logits, layers, params, scales, mb.FP16, mb.FP32, top_k=K)
+    p64 = [[(w, b.astype(np.float64)) for (w, b) in ps] for ps in params]
+    ref, sel, w, c_ref = nets.moe_topk_fp16(x, logits, K, layers, p64)
+    assert np.array_equal(idx.reshape(B, K), sel) and np.array_equal(cnt, c_ref)
+    # each expert output is within the fp16 layer tolerance; the mixture is a convex combination of them
+    gu.check_fp16(y.cpu().numpy().reshape(ref.shape), ref, "moe top-2 fp16", 0.1)
 
 
 def test_moe_small_fp16():
