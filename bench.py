@@ -227,6 +227,7 @@ def main():
         if B == 256:
             out["moe_config5"] = bench_moe(torch, mb, pl, cf, calib, args.dtype, chain.acts[1], B)
         out["alexnet_whole_net"] = bench_whole_net(torch, mb, pl, cf, calib, args.dtype, x_dev, B, macs_img)
+        out["moe16_top4"] = bench_moe16(torch, mb, pl, cf, calib, args.dtype, x_store, B)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cf, calib, args.dtype, args.cpu_images, macs_img)
@@ -299,6 +300,49 @@ def bench_whole_net(torch, mb, pl, cf, calib, dtype_name, x_dev, batch, conv_mac
     return {"workload": f"conv1..conv5 + pools + fc6..fc8 chained, batch {batch}", "forward_us": round(us, 1),
             "images_per_s": round(batch / (us * 1e-6), 1), "gop_per_image": round(2 * macs / 1e9, 4),
             "tops": round(2.0 * macs * batch / (us * 1e-6) / 1e12, 1)}
+
+
+def bench_moe16(torch, mb, pl, cf, calib, dtype_name, x_store, batch):
+    """The paper's mixture geometry (section "ImageNet-MOE Configuration"): 16 quarter-width experts,
+    4 per sample, outputs mixed in fp32 with the renormalised gating probabilities; synthetic logits.
+    Timed: mpq_moe_forward on the trunk's output, and, as the comparison the paper ran, one expert's
+    layer chain on the whole batch (x 16 = every expert on every sample)."""
+    if dtype_name == "int16":
+        return None         # (expert-grouped int16 layers run on the direct kernel; not a bench line)
+    dt = mb.DTYPE_ID[dtype_name]
+    K, E = cf.MOE16_TOPK, cf.MOE16_EXPERTS
+    trunk_p, experts_p = cf.moe16_params()
+    if dtype_name == "fp16":
+        trunk = pl.Chain(cf.MOE16_TRUNK, trunk_p, dt, batch, cf.ALEXNET_INPUT)
+        moe = pl.MoE(cf.MOE16_EXPERT_LAYERS, experts_p, dt, batch, (27, 27, 48), top_k=K)
+        dense = pl.Chain(cf.MOE16_EXPERT_LAYERS, experts_p[0], dt, batch, (48, 27, 27))
+    else:
+        sm = calib.load()["moe16"][dtype_name]
+        s_trunk = sm["trunk"][-1]["y"]
+        trunk = pl.Chain(cf.MOE16_TRUNK, trunk_p, dt, batch, cf.ALEXNET_INPUT, sm["x"], sm["trunk"])
+        moe = pl.MoE(cf.MOE16_EXPERT_LAYERS, experts_p, dt, batch, (27, 27, 48), s_trunk, sm["experts"], top_k=K)
+        dense = pl.Chain(cf.MOE16_EXPERT_LAYERS, experts_p[0], dt, batch, (48, 27, 27), s_trunk, sm["experts"][0])
+    t = trunk.forward(x_store)
+    lg = torch.from_numpy(cf.moe16_logits(batch)).to("cuda")
+    moe_us = graph_time(torch, lambda: moe.forward(t, lg, mb.FP32), 5, 5)
+    one_us = graph_time(torch, lambda: dense.forward(t), 5, 5)
+    counts = [int(v) for v in moe.expert_counts.cpu().numpy()]
+    hw, macs = (27, 27), 0
+    for L in cf.MOE16_EXPERT_LAYERS:
+        if L.kind == "fc":
+            macs += L.N * L.K
+        else:
+            macs += L.macs(*hw)
+            P, Q = L.out_hw(*hw)
+            if L.pool_k:
+                P, Q = (P - L.pool_k) // L.pool_s + 1, (Q - L.pool_k) // L.pool_s + 1
+            hw = (P, Q)
+    return {"workload": f"16 quarter-width experts, {K} per sample, batch {batch}, fp32 mixing; entries per expert {min(counts)}..{max(counts)}",
+            "moe_forward_us": round(moe_us, 1), "samples_per_s": round(batch / (moe_us * 1e-6), 1),
+            "expert_gmac_per_sample": round(K * macs / 1e9, 4),
+            "expert_tops": round(2.0 * K * macs * batch / (moe_us * 1e-6) / 1e12, 1),
+            "all_experts_on_whole_batch_us": round(E * one_us, 1),
+            "one_expert_on_whole_batch_us": round(one_us, 1)}
 
 
 def bench_moe(torch, mb, pl, cf, calib, dtype_name, trunk_out, batch):

@@ -93,6 +93,19 @@ def main():
                         for ps, pk in zip(experts_p, epeaks)],
         }
 
+    # the paper's mixture geometry: one trunk convolution, 16 experts, every expert observed on the
+    # same calibration images
+    trunk_p, experts_p = cf.moe16_params()
+    tpk, trunk_out = nets.run_f64_chain_maxabs(cf.MOE16_TRUNK, x, trunk_p)
+    epeaks = [nets.run_f64_chain_maxabs(cf.MOE16_EXPERT_LAYERS, trunk_out, ps)[0] for ps in experts_p]
+    res["moe16"] = {}
+    for dt in QSYM:
+        s_in = _s(6.0, dt)
+        tsc = _layer_scales(cf.MOE16_TRUNK, trunk_p, tpk, s_in, dt)
+        res["moe16"][dt] = {"x": s_in, "trunk": tsc,
+                            "experts": [_layer_scales(cf.MOE16_EXPERT_LAYERS, ps, pk, tsc[-1]["y"], dt)
+                                        for ps, pk in zip(experts_p, epeaks)]}
+
     path = os.path.join(os.path.dirname(os.path.abspath(cf.__file__)), "calib.json")
     with open(path, "w") as f:
         json.dump(res, f, indent=1)

@@ -177,3 +177,51 @@ def test_moe_config5_parity_routing_batch16_int8():
     assert np.array_equal(moe.expert_index.cpu().numpy(), e_ref)
     assert np.array_equal(moe.expert_counts.cpu().numpy(), c_ref)
     assert np.array_equal(y.cpu().numpy().reshape(ref.shape).astype(np.int32), ref)
+
+
+# ---------------------------------------------------------------------------------------------
+# the paper's mixture geometry: 16 quarter-width experts, 4 per sample, mixed in fp32
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["int8", "int16", "fp16"])
+def test_moe16_top4_paper_geometry(dtype):
+    """Trunk (48-filter first convolution + pool), then 4 of 16 experts per sample (section
+    "ImageNet-MOE Configuration"), batch 64: the selection for every sample, the mixed output for
+    five samples against the oracle."""
+    _say("moe16 top-4", dtype)
+    B, K = 64, cf.MOE16_TOPK
+    x = _alexnet_batch(256)[:B]
+    trunk_p, experts_p = cf.moe16_params()
+    logits = cf.moe16_logits(B)
+    lg = torch.from_numpy(logits).to("cuda")
+    if dtype == "fp16":
+        trunk = pl.Chain(cf.MOE16_TRUNK, trunk_p, mb.FP16, B, cf.ALEXNET_INPUT)
+        moe = pl.MoE(cf.MOE16_EXPERT_LAYERS, experts_p, mb.FP16, B, (27, 27, 48), top_k=K)
+    else:
+        sm = calib.load()["moe16"][dtype]
+        s_trunk = sm["trunk"][-1]["y"]
+        trunk = pl.Chain(cf.MOE16_TRUNK, trunk_p, DT[dtype], B, cf.ALEXNET_INPUT, sm["x"], sm["trunk"])
+        moe = pl.MoE(cf.MOE16_EXPERT_LAYERS, experts_p, DT[dtype], B, (27, 27, 48), s_trunk, sm["experts"], top_k=K)
+    t = trunk.forward(trunk.input_storage(x))
+    y = moe.forward(t, lg, mb.FP32)
+    torch.cuda.synchronize()
+    sel, w, counts = o.route_topk(logits, K)
+    assert np.array_equal(moe.expert_index.cpu().numpy().reshape(B, K), sel)
+    assert np.array_equal(moe.expert_counts.cpu().numpy(), counts) and counts.sum() == B * K
+    sample = [0, 1, 17, 40, 63]
+    got = y[sample].cpu().numpy().reshape(len(sample), -1).astype(np.float64)
+    if dtype == "fp16":
+        t64 = nets.run_fp16_chain(cf.MOE16_TRUNK, x[sample], trunk_p)
+        e16 = [[nets.fp16_params(wt, b) for (wt, b) in ps] for ps in experts_p]
+        ref, sel_s, _, _ = nets.moe_topk_fp16(o.round_fp16(t64), logits[sample], K, cf.MOE16_EXPERT_LAYERS, e16)
+        assert np.array_equal(sel_s, sel[sample])
+        gu.check_fp16(got, ref.reshape(len(sample), -1), "moe16 fp16", 0.1 * 6)      # 1 trunk + 6 expert layers deep
+    else:
+        tq = nets.run_int_chain(cf.MOE16_TRUNK, x[sample], trunk_p, sm["x"], sm["trunk"], dtype)
+        eq = [[nets.quantize_params(wt, b, sc, dtype) for (wt, b), sc in zip(ps, scs)]
+              for ps, scs in zip(experts_p, sm["experts"])]
+        ref, sel_s, _, _ = nets.moe_topk_int(tq, s_trunk, logits[sample], K, cf.MOE16_EXPERT_LAYERS, eq, sm["experts"], dtype)
+        assert np.array_equal(sel_s, sel[sample])
+        ref = ref.reshape(len(sample), -1)
+        bound = 2e-6 * K * np.max(np.abs(ref), axis=1, keepdims=True)
+        assert np.all(np.abs(got - ref) <= bound), float(np.max(np.abs(got - ref) / bound))
+        assert np.std(ref) > 0

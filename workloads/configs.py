@@ -96,6 +96,23 @@ MOE_EXPERT_LAYERS = [                        # half the channel width of config 
     FC("fc", 2048, 128 * 6 * 6, relu=True),
 ]
 
+# ---- the paper's own mixture geometry (section "ImageNet-MOE Configuration"): a trunk of a
+# 48-filter first convolution, 16 experts of which 4 run per sample, each expert the later
+# convolutions at a quarter of the width followed by fully-connected layers of 1024 and 2048
+# outputs.  (The normalisation layers are left out as in the other configurations; the expert
+# convolutions are not grouped here, so that a quarter-width layer still has whole 16-channel
+# blocks; logits are synthetic.)
+MOE16_EXPERTS, MOE16_TOPK = 16, 4
+MOE16_TRUNK = [Conv("conv1q", 48, 3, 11, 11, stride=4, pad=0, groups=1, pool_k=3, pool_s=2)]   # -> 48 x 27 x 27
+MOE16_EXPERT_LAYERS = [
+    Conv("conv2q", 64, 48, 5, 5, pad=2, pool_k=3, pool_s=2),
+    Conv("conv3q", 96, 64, 3, 3, pad=1),
+    Conv("conv4q", 96, 96, 3, 3, pad=1),
+    Conv("conv5q", 64, 96, 3, 3, pad=1, pool_k=3, pool_s=2),
+    FC("fc1q", 1024, 64 * 6 * 6, relu=True),
+    FC("fc2q", 2048, 1024, relu=True),
+]
+
 
 def _he_std(layer: Conv) -> float:
     return float(np.sqrt(2.0 / ((layer.C // layer.groups) * layer.R * layer.S)))
@@ -204,6 +221,27 @@ def moe_params():
                 ps.append((fc_weights(seed, L, std=float(np.sqrt(2.0 / L.K))), bias(seed + 1, L.N, 0.1)))
         experts.append(ps)
     return trunk, gate_w, experts
+
+
+def moe16_params():
+    """Trunk and the 16 experts of the paper-geometry mixture, each with its own seeds."""
+    trunk = alexnet_conv_params(MOE16_TRUNK, base=6000)
+    experts = []
+    for e in range(MOE16_EXPERTS):
+        ps = []
+        for i, L in enumerate(MOE16_EXPERT_LAYERS):
+            seed = 6100 + 100 * e + 2 * i
+            if L.kind == "conv":
+                ps.append((conv_weights(seed, L), bias(seed + 1, L.K, 0.1)))
+            else:
+                ps.append((fc_weights(seed, L, std=float(np.sqrt(2.0 / L.K))), bias(seed + 1, L.N, 0.1)))
+        experts.append(ps)
+    return trunk, experts
+
+
+def moe16_logits(batch: int, seed: int = 6002) -> np.ndarray:
+    """Gating values of the paper-geometry mixture: N(0,1), seeded, rows independent of the batch size."""
+    return gen.normal(seed, (256, MOE16_EXPERTS), 0.0, 1.0)[:batch].astype(np.float32)
 
 
 def moe_benchmark_logits(batch: int = 256, counts=MOE_COUNTS_256, seed: int = 5002) -> np.ndarray:
