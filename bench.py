@@ -307,8 +307,6 @@ def bench_moe16(torch, mb, pl, cf, calib, dtype_name, x_store, batch):
     4 per sample, outputs mixed in fp32 with the renormalised gating probabilities; synthetic logits.
     Timed: mpq_moe_forward on the trunk's output, and, as the comparison the paper ran, one expert's
     layer chain on the whole batch (x 16 = every expert on every sample)."""
-    if dtype_name == "int16":
-        return None         # (expert-grouped int16 layers run on the direct kernel; not a bench line)
     dt = mb.DTYPE_ID[dtype_name]
     K, E = cf.MOE16_TOPK, cf.MOE16_EXPERTS
     trunk_p, experts_p = cf.moe16_params()
@@ -350,8 +348,6 @@ def bench_moe(torch, mb, pl, cf, calib, dtype_name, trunk_out, batch):
     (raw logits) and mpq_moe_forward (route + gather + grouped experts + scatter), timed per call.
     `trunk_out` is the device activation after conv2 + pool of the main chain."""
     import numpy as np
-    if dtype_name == "int16":
-        return None
     dt = mb.DTYPE_ID[dtype_name]
     _, gate_w, experts_p = cf.moe_params()
     cal = calib.load()

@@ -246,7 +246,7 @@ WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, 
         off += w.fc_bytes;
     }
     const long long macs = (long long)x.n * g.P * g.Q * d.k * pl.Kdim;
-    if (pl.dg_stride > 0 && out_dtype == MPQ_INT16 && num_experts == 0 && macs >= kDigitMinMacs) {
+    if (pl.dg_stride > 0 && out_dtype == MPQ_INT16 && macs >= kDigitMinMacs) {
         mpq_tensor x8 = x;
         x8.dtype = MPQ_INT8;
         const mpq_conv_desc d8 = digit_desc(d);
@@ -254,7 +254,7 @@ WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, 
         g8.Po = g.P;
         g8.Qo = g.Q;
         const Plan p8 = make_plan(d8, MPQ_INT8, x.w);
-        const WsLayout sub = ws_layout(x8, d8, p8, g8, MPQ_INT32);
+        const WsLayout sub = ws_layout(x8, d8, p8, g8, MPQ_INT32, num_experts);
         w.dg_off = off;
         w.dg_x_stride = round_up((size_t)x.n * x.h * x.w * x.c, 256);
         w.dg_raw_off = 2 * w.dg_x_stride;
@@ -279,9 +279,10 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
 
 // An int16 convolution as six int8 convolutions of digit planes (conv_i16.hip) plus the int64
 // recombination with the layer's epilogue; conv_out receives the unpooled int16 result.
+// (seg: expert-grouped launch; the experts' digit planes lie at the same offsets of their packed blobs)
 mpq_status run_conv_digits(const mpq_tensor &x, const void *w_packed, const void *bias, void *conv_out,
-                           const mpq_conv_desc &d, const Epi &epi, const Plan &pl, const Geometry &g,
-                           const WsLayout &wl, char *wsb, hipStream_t st) {
+                           const mpq_conv_desc &d, const Epi &epi, const SegTable *seg, const Plan &pl,
+                           const Geometry &g, const WsLayout &wl, char *wsb, hipStream_t st) {
     char *dg = wsb + wl.dg_off;
     const size_t count = (size_t)x.n * x.h * x.w * x.c;
     if (launch_i16_split_x(x.data, dg, dg + wl.dg_x_stride, count, st) != hipSuccess) return MPQ_ERR_DEVICE;
@@ -290,6 +291,15 @@ mpq_status run_conv_digits(const mpq_tensor &x, const void *w_packed, const void
     std::memset(&e8, 0, sizeof(e8));
     e8.kind = kEpiRawI32;
     e8.sb = 31;
+    SegTable seg8;
+    if (seg) {
+        std::memset(&seg8, 0, sizeof(seg8));
+        seg8.offsets = seg->offsets;
+        seg8.num_experts = seg->num_experts;
+        seg8.bias_stride = 0;
+        seg8.w_stride = seg->w_stride;
+        for (int e = 0; e < seg->num_experts; ++e) seg8.epi[e] = e8;
+    }
     const char *wp = reinterpret_cast<const char *>(w_packed);
     for (int xd = 0; xd < 2; ++xd) {
         mpq_tensor x8 = x;
@@ -304,8 +314,9 @@ mpq_status run_conv_digits(const mpq_tensor &x, const void *w_packed, const void
         }
         for (int wd = 0; wd < 3; ++wd) {
             void *raw = dg + wl.dg_raw_off + (size_t)(xd * 3 + wd) * wl.dg_raw_stride;
-            mpq_status s = run_conv(x8, wp + pl.dg_off + wd * pl.dg_stride, nullptr, raw, MPQ_INT32, d8, e8, nullptr,
-                                    wl.dg_sub_bytes ? dg + wl.dg_sub_off : nullptr, wl.dg_sub_bytes, st, padded);
+            mpq_status s = run_conv(x8, wp + pl.dg_off + wd * pl.dg_stride, nullptr, raw, MPQ_INT32, d8, e8,
+                                    seg ? &seg8 : nullptr, wl.dg_sub_bytes ? dg + wl.dg_sub_off : nullptr,
+                                    wl.dg_sub_bytes, st, padded);
             if (s != MPQ_OK) return s;
         }
     }
@@ -315,8 +326,16 @@ mpq_status run_conv_digits(const mpq_tensor &x, const void *w_packed, const void
     cb.K = d.k; cb.P = g.P; cb.Q = g.Q; cb.H = x.h; cb.W = x.w; cb.R = d.r; cb.S = d.s;
     cb.stride_h = d.stride_h; cb.stride_w = d.stride_w; cb.pad_h = d.pad_h; cb.pad_w = d.pad_w;
     const size_t total = (size_t)x.n * g.P * g.Q * d.k;
+    I16Seg cs;
+    if (seg) {
+        cs.offsets = seg->offsets;
+        cs.num_experts = seg->num_experts;
+        cs.bias_stride = seg->bias_stride;
+        cs.w_stride = seg->w_stride;
+        for (int e = 0; e < kMaxExperts; ++e) cs.epi[e] = seg->epi[e];
+    }
     if (launch_i16_combine(reinterpret_cast<const int *>(dg + wl.dg_raw_off), wl.dg_raw_stride / 4, (const int *)bias,
-                           conv_out, total, cb, epi, st) != hipSuccess)
+                           conv_out, total, cb, epi, seg ? &cs : nullptr, st) != hipSuccess)
         return MPQ_ERR_DEVICE;
     return MPQ_OK;
 }
@@ -371,14 +390,20 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     hipError_t err = hipSuccess;
     // int16 on the matrix cores: byte-digit planes through the int8 kernels.  Needs the optional part
     // of the workspace and no weight zero-point.
-    const bool digits = wl.dg_bytes > 0 && !seg && fc_ws_ok(ws, ws_bytes, wl.total) && epi.kind == kEpiRequant &&
+    bool seg_plain = true;      // (an expert-grouped layer: no weight zero-points, blobs at aligned strides)
+    if (seg) {
+        seg_plain = seg->w_stride % 256 == 0;
+        for (int e = 0; e < seg->num_experts; ++e)
+            seg_plain = seg_plain && seg->epi[e].zw == 0 && seg->epi[e].kind == kEpiRequant;
+    }
+    const bool digits = wl.dg_bytes > 0 && seg_plain && fc_ws_ok(ws, ws_bytes, wl.total) && epi.kind == kEpiRequant &&
                         epi.zw == 0 && aligned16(x.data) &&
                         aligned16(w_packed) && aligned16(conv_out) && (bias == nullptr || aligned16(bias));
     if (!seg && gemv_eligible(a) && (a.N < 4 || a.K <= 16)) {
         // batch < 4 (or <= 16 outputs): memory-bound, one pass over the larger matrix on the dot units
         err = launch_gemv(a, st);
     } else if (digits) {
-        s = run_conv_digits(x, w_packed, bias, conv_out, d, epi, pl, g, wl, wsb, st);
+        s = run_conv_digits(x, w_packed, bias, conv_out, d, epi, seg, pl, g, wl, wsb, st);
         if (s != MPQ_OK) return s;
     } else if (fc_ws && d.pool_k == 0 && fc_frag_eligible(a)) {
         // a matrix product on 4..512 rows (or an expert's rows): fragment-ordered operands, the

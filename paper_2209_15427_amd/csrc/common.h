@@ -158,8 +158,17 @@ struct I16Combine {
     int K, P, Q, H, W, R, S, stride_h, stride_w, pad_h, pad_w;
 };
 hipError_t launch_i16_tappre(const void *w16, int *tappre, int K, int Cg, int R, int S, hipStream_t st);
+// expert-grouped launch of the recombination: sample ranges, strides between the experts' packed
+// blobs (bytes) and bias vectors (elements), per-expert rescale
+struct I16Seg {
+    const int *offsets;
+    int num_experts;
+    int bias_stride;
+    size_t w_stride;
+    Epi epi[kMaxExperts];
+};
 hipError_t launch_i16_combine(const int *raw, size_t raw_stride, const int *bias, void *y, size_t total,
-                              const I16Combine &g, const Epi &epi, hipStream_t st);
+                              const I16Combine &g, const Epi &epi, const I16Seg *seg, hipStream_t st);
 hipError_t launch_minmax(const float *src, size_t n, float *minmax, hipStream_t st);
 hipError_t launch_pad_channels(const void *x, void *xp, int N, int H, int W, int C, int Wp, int Cpad,
                                int esize, int fill, hipStream_t st);

@@ -82,10 +82,11 @@ __global__ void __launch_bounds__(kThreads) i16_tappre_kernel(const int16_t *__r
 
 // t = the formula above + bias, then the layer's rescale; raw[j] is the j-th partial convolution
 // in the formula's order (hh, hm, hb, lh, lm, lb)
-template <int V>
+// (expert-grouped launch: the row's sample picks the expert, whose tables, bias and rescale apply)
+template <int V, bool SEG>
 __global__ void __launch_bounds__(kThreads) i16_combine_kernel(const int *__restrict__ raw, size_t raw_stride,
                                                                const int *__restrict__ bias, int16_t *__restrict__ y,
-                                                               size_t total, I16Combine g, Epi epi) {
+                                                               size_t total, I16Combine g, Epi epi0, I16Seg seg) {
     const int K = g.K;
     const int S1 = g.S + 1, per_k = (g.R + 1) * S1;
     size_t i = ((size_t)blockIdx.x * kThreads + threadIdx.x) * V;
@@ -99,6 +100,17 @@ __global__ void __launch_bounds__(kThreads) i16_combine_kernel(const int *__rest
         const int r_lo = min(max(-h0, 0), g.R), r_hi = min(max(g.H - h0, r_lo), g.R);
         const int s_lo = min(max(-w0, 0), g.S), s_hi = min(max(g.W - w0, s_lo), g.S);
         const bool interior = r_lo == 0 && s_lo == 0 && r_hi == g.R && s_hi == g.S;
+        Epi epi = epi0;
+        const int *wsum = g.wsum, *tappre = g.tappre, *bias_e = bias;
+        if constexpr (SEG) {
+            const int n = (int)(m / ((size_t)g.P * g.Q));
+            int e = 0;
+            while (e + 1 < seg.num_experts && n >= seg.offsets[e + 1]) ++e;
+            epi = seg.epi[e];
+            wsum = reinterpret_cast<const int *>(reinterpret_cast<const char *>(g.wsum) + (size_t)e * seg.w_stride);
+            tappre = reinterpret_cast<const int *>(reinterpret_cast<const char *>(g.tappre) + (size_t)e * seg.w_stride);
+            if (bias) bias_e = bias + (size_t)e * seg.bias_stride;
+        }
         int c[6][V];
 #pragma unroll
         for (int j = 0; j < 6; ++j) {
@@ -118,13 +130,13 @@ __global__ void __launch_bounds__(kThreads) i16_combine_kernel(const int *__rest
             const int k = k0 + e;
             long long v;
             if (interior) {
-                v = g.wsum[k];
+                v = wsum[k];
             } else {
-                const int *pre = g.tappre + (size_t)k * per_k;
+                const int *pre = tappre + (size_t)k * per_k;
                 v = (long long)pre[r_hi * S1 + s_hi] - pre[r_lo * S1 + s_hi] - pre[r_hi * S1 + s_lo] + pre[r_lo * S1 + s_lo];
             }
             t += (long long)(128 - epi.zx) * v;
-            if (bias) t += (long long)bias[k];
+            if (bias) t += (long long)bias_e[k];
             out[e] = (int16_t)requant64(t, epi);
         }
         if constexpr (V == 4) {
@@ -167,13 +179,21 @@ hipError_t launch_i16_tappre(const void *w16, int *tappre, int K, int Cg, int R,
 }
 
 hipError_t launch_i16_combine(const int *raw, size_t raw_stride, const int *bias, void *y, size_t total,
-                              const I16Combine &g, const Epi &epi, hipStream_t st) {
+                              const I16Combine &g, const Epi &epi, const I16Seg *seg, hipStream_t st) {
     if (total == 0) return hipSuccess;
     // (four outputs per thread need the channel count, hence every row start, to be a multiple of 4)
-    if (g.K % 4 == 0 && raw_stride % 4 == 0)
-        i16_combine_kernel<4><<<grid_of(total / 4), kThreads, 0, st>>>(raw, raw_stride, bias, (int16_t *)y, total, g, epi);
-    else
-        i16_combine_kernel<1><<<grid_of(total), kThreads, 0, st>>>(raw, raw_stride, bias, (int16_t *)y, total, g, epi);
+    const bool v4 = g.K % 4 == 0 && raw_stride % 4 == 0;
+    const int grid = grid_of(v4 ? total / 4 : total);
+    I16Seg none;
+    none.offsets = nullptr;
+    none.num_experts = 0;
+    if (seg) {
+        if (v4) i16_combine_kernel<4, true><<<grid, kThreads, 0, st>>>(raw, raw_stride, bias, (int16_t *)y, total, g, epi, *seg);
+        else i16_combine_kernel<1, true><<<grid, kThreads, 0, st>>>(raw, raw_stride, bias, (int16_t *)y, total, g, epi, *seg);
+    } else {
+        if (v4) i16_combine_kernel<4, false><<<grid, kThreads, 0, st>>>(raw, raw_stride, bias, (int16_t *)y, total, g, epi, none);
+        else i16_combine_kernel<1, false><<<grid, kThreads, 0, st>>>(raw, raw_stride, bias, (int16_t *)y, total, g, epi, none);
+    }
     return hipGetLastError();
 }
 
