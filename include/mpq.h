@@ -160,7 +160,9 @@ mpq_status mpq_pack_weights(const void *w_kcrs, const mpq_conv_desc *d, mpq_dtyp
  *   w_packed from mpq_pack_weights with the same descriptor and dtype; w_q its parameters
  *   bias     device, k entries (int32 for integer types, fp32 for fp16), or NULL
  *   y        output view; n, h, w, c must equal the layer's output shape (after pooling)
- *   ws       device scratch of at least mpq_conv2d_workspace_bytes(), 256-byte aligned.  For an
+ *   ws       device scratch of at least mpq_conv2d_workspace_bytes(), 256-byte aligned.  An
+ *            MPQ_INT8 layer with a weight zero-point uses a small part of it (per-pixel input
+ *            sums) to stay on the matrix-core kernels; without it the direct kernel runs.  For an
  *            MPQ_INT16 layer the larger part of that size (byte planes of x and 32-bit partial
  *            results for the int8 matrix-core kernels) is optional: with fewer bytes, but enough
  *            for the unpooled output of a pooling layer, the layer runs on the direct kernel with

@@ -193,6 +193,8 @@ struct WsLayout {
     size_t pad_off, pad_bytes;    // channel-padded copy of the input (row mode)
     size_t mid_off, mid_bytes;    // unpooled convolution output
     size_t pp_off, pp_bytes;      // row-tiled convolution with the pool in its epilogue: windows that straddle two tiles
+    size_t opt_off;               // everything from here on is optional (a layer runs without it on a slower kernel)
+    size_t xs_off, xs_bytes;      // int8 layer with a weight zero-point: per-pixel window sums of the input
     size_t fc_off, fc_bytes;      // fully-connected layer: x in fragment order + partial sums
     // int16 layer run as int8 digit planes: the two planes of x, six int32 partial convolutions,
     // and the workspace of one int8 convolution
@@ -237,6 +239,12 @@ WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, 
             w.pp_bytes = round_up((size_t)x.n * (ti - 1) * 2 * g.Qo * d.k * dtype_size(out_dtype), 256);
             off += w.pp_bytes;
         }
+    }
+    w.opt_off = off;
+    if (x.dtype == MPQ_INT8 && num_experts == 0 && pl.mode != kModeGeneric) {
+        w.xs_off = off;
+        w.xs_bytes = round_up((size_t)x.n * g.P * g.Q * d.groups * 4, 256);
+        off += w.xs_bytes;
     }
     if (x.h == 1 && x.w == 1 && d.r == 1 && d.s == 1 && d.groups == 1 && pl.frag_bytes > 0 && pl.f_ksp == 1 &&
         ((size_t)x.c * pl.esize) % 64 == 0 && x.n >= 1) {
@@ -352,7 +360,7 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     Plan pl = make_plan(d, x.dtype, x.w);
     WsLayout wl = ws_layout(x, d, pl, g, y_dtype, seg ? seg->num_experts : 0);
     // (the fully-connected scratch is optional: without it the layer runs on the kernels that need none)
-    const size_t ws_required = wl.dg_bytes > 0 ? wl.dg_off : wl.fc_bytes > 0 ? wl.fc_off : wl.total;
+    const size_t ws_required = wl.opt_off;
     if (ws_required > 0 && (ws == nullptr || ws_bytes < ws_required || !aligned16(ws))) return MPQ_ERR_WORKSPACE;
     const bool fc_ws = wl.fc_bytes > 0 && fc_ws_ok(ws, ws_bytes, wl.total);
     if ((long long)x.n * g.P * g.Q > 0x7ffffc00ll) return MPQ_ERR_UNSUPPORTED;
@@ -378,7 +386,9 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
 
     // kernel choice
     const bool mfma_type = x.dtype == MPQ_INT8 || x.dtype == MPQ_FP16;
-    bool zw_ok = (x.dtype == MPQ_FP16) || epi.zw == 0;
+    // (a weight zero-point on the matrix-core kernels needs the window sums' part of the workspace)
+    const bool xs_ok = wl.xs_bytes > 0 && !seg && fc_ws_ok(ws, ws_bytes, wl.xs_off + wl.xs_bytes);
+    bool zw_ok = (x.dtype == MPQ_FP16) || epi.zw == 0 || xs_ok;
     if (seg)
         for (int e = 0; e < seg->num_experts; ++e) zw_ok = zw_ok && (x.dtype == MPQ_FP16 || seg->epi[e].zw == 0);
     bool use_mfma = mfma_type && zw_ok && pl.mode != kModeGeneric && (pl.Kg % 4 == 0) && aligned16(x.data) &&
@@ -424,6 +434,12 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
         a.phased = (pl.mode == kModeTap && a.cpt % 4 == 0 && a.cpt > 4 && pl.taps > 1) ? 1 : 0;
         unsigned zb = (unsigned)(epi.zx & 0xff);
         a.fill_word = x.dtype == MPQ_INT8 ? zb * 0x01010101u : 0u;
+        if (x.dtype == MPQ_INT8 && epi.zw != 0) {
+            int *xs = reinterpret_cast<int *>(wsb + wl.xs_off);
+            if (launch_window_sums(a, x.data, x.w, x.c, xs, st) != hipSuccess) return MPQ_ERR_DEVICE;
+            a.xsum = xs;
+            a.zw_corr = epi.zw;
+        }
         if (pl.mode == kModeRow && !row_padded && aligned16(x.data) && aligned16(y_data)) {
             // first-layer shape: weights and an input patch resident in LDS, pool fused
             err = launch_conv_first(a, d.pool_k, d.pool_s, y_data, g.Po, g.Qo, st);

@@ -131,6 +131,10 @@ struct ConvArgs {
     int cbc, nphase, ksp;
     unsigned magic_wv, magic_hw, magic_cbc, magic_s, magic_pq, magic_q;
     unsigned magic_qo;     // ceil(2^32 / Qo) for the pooled epilogue
+    // non-zero weight zero-point on the MFMA kernels (int8): xsum[m][group] = sum over the window's
+    // taps inside the image of (x - z_x); the epilogue subtracts zw_corr * xsum from the row's sums
+    const int *xsum;
+    int zw_corr;
     unsigned fill_word;    // the input zero-point replicated over 32 bits (out-of-image taps)
     unsigned long long x_bytes;   // size of the input tensor the kernel sees
     Plan plan;
@@ -169,6 +173,7 @@ struct I16Seg {
 };
 hipError_t launch_i16_combine(const int *raw, size_t raw_stride, const int *bias, void *y, size_t total,
                               const I16Combine &g, const Epi &epi, const I16Seg *seg, hipStream_t st);
+hipError_t launch_window_sums(const ConvArgs &a, const void *x, int W, int C, int *xsum, hipStream_t st);
 hipError_t launch_minmax(const float *src, size_t n, float *minmax, hipStream_t st);
 hipError_t launch_pad_channels(const void *x, void *xp, int N, int H, int W, int C, int Wp, int Cpad,
                                int esize, int fill, hipStream_t st);

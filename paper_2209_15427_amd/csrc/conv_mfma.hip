@@ -226,6 +226,8 @@ __global__ void __launch_bounds__(kThreads) conv_mfma_kernel(ConvArgs a) {
     for (int j = 0; j < TP; ++j) {
         const int m = m0 + wp * WTP + j * 32 + frow;
         if (m >= m_end) continue;
+        // (weight zero-point: z_w times the pixel's window sum of (x - z_x), made by a kernel before this one)
+        const int zw_term = (ES == 1 && a.xsum) ? a.zw_corr * a.xsum[(size_t)m * a.groups + g] : 0;
 #pragma unroll
         for (int i = 0; i < TC; ++i) {
 #pragma unroll
@@ -243,7 +245,7 @@ __global__ void __launch_bounds__(kThreads) conv_mfma_kernel(ConvArgs a) {
                     }
                     int t[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u] + b4[u];
+                    for (int u = 0; u < 4; ++u) t[u] = acc[i][j][vq * 4 + u] + b4[u] - zw_term;
                     if (epi.kind == kEpiRawI32) {
                         *reinterpret_cast<v4i *>((int *)a.y + o) = v4i{t[0], t[1], t[2], t[3]};
                     } else {

@@ -463,7 +463,60 @@ __global__ void __launch_bounds__(kThreads) minmax_kernel(const float *__restric
     }
 }
 
+// xsum[m][g] = sum over the taps of output pixel m that lie inside the image, and over the group's
+// channels, of (x - z_x): the per-pixel factor of the weight zero-point term (section "Quantized
+// Operations", expanded product).  One thread per (pixel, group).
+__global__ void __launch_bounds__(kThreads)
+window_sums_kernel(const int8_t *__restrict__ x, int *__restrict__ xsum, int N, int H, int W, int C, int P, int Q, int R,
+                   int S, int stride_h, int stride_w, int pad_h, int pad_w, int groups, int zx, int vec) {
+    const int Cg = C / groups;
+    const size_t total = (size_t)N * P * Q * groups;
+    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t step = (size_t)gridDim.x * kThreads;
+    for (; i < total; i += step) {
+        const int g = (int)(i % groups);
+        const size_t m = i / groups;
+        const int q = (int)(m % Q), p = (int)((m / Q) % P), n = (int)(m / ((size_t)P * Q));
+        const int h0 = p * stride_h - pad_h, w0 = q * stride_w - pad_w;
+        int sum = 0, taps = 0;
+        for (int r = 0; r < R; ++r) {
+            const int h = h0 + r;
+            if (h < 0 || h >= H) continue;
+            for (int sx = 0; sx < S; ++sx) {
+                const int w = w0 + sx;
+                if (w < 0 || w >= W) continue;
+                const int8_t *px = x + (((size_t)n * H + h) * W + w) * C + (size_t)g * Cg;
+                ++taps;
+                if (vec) {
+                    for (int c = 0; c < Cg; c += 16) {
+                        const int4 v = *reinterpret_cast<const int4 *>(px + c);
+                        sum = __builtin_amdgcn_sdot4(v.x, 0x01010101, sum, false);
+                        sum = __builtin_amdgcn_sdot4(v.y, 0x01010101, sum, false);
+                        sum = __builtin_amdgcn_sdot4(v.z, 0x01010101, sum, false);
+                        sum = __builtin_amdgcn_sdot4(v.w, 0x01010101, sum, false);
+                    }
+                } else {
+                    for (int c = 0; c < Cg; ++c) sum += px[c];
+                }
+            }
+        }
+        xsum[i] = sum - zx * taps * Cg;
+    }
+}
+
 }  // namespace
+
+// (x, W, C: the layer's input as the caller passed it, not a channel-padded copy)
+hipError_t launch_window_sums(const ConvArgs &a, const void *x, int W, int C, int *xsum, hipStream_t st) {
+    const size_t total = (size_t)a.N * a.P * a.Q * a.groups;
+    if (total == 0) return hipSuccess;
+    const int Cg = C / a.groups;
+    const int vec = (Cg % 16 == 0) && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
+    window_sums_kernel<<<grid_for(total, kThreads), kThreads, 0, st>>>((const int8_t *)x, xsum, a.N, a.H, W, C, a.P, a.Q, a.R,
+                                                                     a.S, a.stride_h, a.stride_w, a.pad_h, a.pad_w, a.groups,
+                                                                     a.epi.zx, vec);
+    return hipGetLastError();
+}
 
 hipError_t launch_minmax(const float *src, size_t n, float *minmax, hipStream_t st) {
     if (n == 0) return hipSuccess;

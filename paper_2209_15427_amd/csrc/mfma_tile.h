@@ -317,6 +317,21 @@ struct Tile {
         const int frow = lane & 31, fk = lane >> 5;
         const int g = t.g, m0 = t.m0, m_end = t.m_end, ch0 = t.ch0;
         const bool raw = epi.kind == kEpiRawI32 || epi.kind == kEpiRawF32;
+        if constexpr (ES == 1) {
+            // weight zero-point: sum (x - z_x)(w - z_w) = sum (x - z_x) w - z_w sum (x - z_x); the second
+            // sum belongs to the pixel (and group) and was made by a kernel before this one
+            if (a.xsum) {
+#pragma unroll
+                for (int j = 0; j < TP; ++j) {
+                    const int m = t.m0 + wp * WTP + j * 32 + frow;
+                    const int corr = m < t.m_end ? a.zw_corr * a.xsum[(size_t)m * a.groups + t.g] : 0;
+#pragma unroll
+                    for (int i = 0; i < TC; ++i)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[i][j][v] -= corr;
+                }
+            }
+        }
         if (raw) {
             finish_raw(acc, lds, a, t);
             return;

@@ -234,7 +234,11 @@ CONV_CASES = [
     (3, 48, 27, 27, 200, 5, 5, 1, 2, 1, False, (3, 2), 0, 0, 0),       # row tiles 3 x 9 rows, ragged channels, no ReLU
     (6, 32, 16, 16, 64, 3, 3, 1, 0, 1, True, (0, 0), 9, 0, 3),         # z_x != 0 without padding (int16: digit planes + weight-sum term)
     (4, 32, 14, 14, 128, 3, 3, 1, 1, 1, True, (0, 0), -77, 0, 11),     # z_x != 0 on a padded layer (int16: per-tap weight sums on the border)
-    (8, 32, 31, 33, 72, 3, 3, 2, 1, 1, False, (2, 2), 0, 0, -5),       # stride 2, 72 channels, 2x2 pool (int16: digit planes)
+    (8, 32, 31, 33, 72, 3, 3, 2, 1, 1, False, (2, 2), 0, 0, -5),
+    (3, 64, 13, 13, 128, 3, 3, 1, 1, 1, True, (3, 2), 0, 9, 0),        # z_w != 0 on the patch kernel (window sums), pool in the epilogue
+    (2, 96, 27, 27, 256, 5, 5, 1, 2, 2, True, (3, 2), 0, -6, 3),       # z_w != 0, conv2 shape: row tiles + fix-up, two groups
+    (2, 48, 17, 19, 72, 3, 3, 2, 1, 1, False, (0, 0), -5, 11, 0),      # z_w != 0 and z_x != 0, strided, padded
+    (2, 3, 43, 43, 96, 11, 11, 4, 0, 1, True, (3, 2), 4, -3, 0),       # z_w != 0 on a first-layer shape       # stride 2, 72 channels, 2x2 pool (int16: digit planes)
 ]
 
 
@@ -361,6 +365,26 @@ def test_int8_gemm_without_workspace(case):
                     (s_w, 0), torch.from_numpy(b.astype(np.int32)).to("cuda"), relu, mb.INT8, (s_y, 0), workspace=False)
     mult, shift = o.scale_quant_vals(s_x, s_w, s_y, 31)
     assert np.array_equal(y.cpu().numpy().astype(np.int32), o.requant(t, mult, 31, shift, 0, "int8", relu))
+
+
+@pytest.mark.parametrize("M,K,N,zx,zw,ws", [(40, 512, 96, 0, 5, True), (130, 1088, 100, -7, -128, True), (40, 512, 96, 3, 5, False),
+                                            (2, 512, 96, 0, 5, True)],
+                         ids=["mfma", "mfma_extreme_zw", "direct_without_workspace", "batch2"])
+def test_int8_gemm_weight_zero_point(M, K, N, zx, zw, ws):
+    """z_w != 0: the matrix-core kernels subtract z_w times the row's input sum in their epilogue
+    (needs the optional workspace); without it, and at batch < 4, the direct kernel runs."""
+    seed = 4800 + M + K
+    x = gen.integers(seed, (M, K), -128, 127)
+    w = gen.integers(seed + 1, (N, K), -128, 127)
+    b = gen.integers(seed + 2, (N,), -9000, 9000)
+    t = o.gemm_acc(x, zx, w, zw, b)
+    s_x, s_w = np.float32(0.02), np.float32(0.004)
+    s_y = np.float32(float(s_x) * float(s_w) * float(np.std(t)) * 3.0 / 127)
+    y = gu.run_gemm(torch.from_numpy(x.astype(np.int8)).to("cuda"), (s_x, zx), torch.from_numpy(w.astype(np.int8)).to("cuda"),
+                    (s_w, zw), torch.from_numpy(b.astype(np.int32)).to("cuda"), True, mb.INT8, (s_y, 2), workspace=ws)
+    mult, shift = o.scale_quant_vals(s_x, s_w, s_y, 31)
+    ref = o.requant(t, mult, 31, shift, 2, "int8", True)
+    assert np.array_equal(y.cpu().numpy().astype(np.int32), ref) and len(np.unique(ref)) > 20
 
 
 @pytest.mark.parametrize("M,N,ws", [(2, 3, True), (64, 96, True), (64, 96, False)],
