@@ -153,6 +153,40 @@ int64_t orc_requant_one(int64_t t, int64_t mult, int sb, int shift,
     return y;
 }
 
+/* Round-to-nearest variant of the rescale (the paper leaves the rounding of the rescale to the
+ * operator, section "Quantized Operations"; this is the single-rounding alternative to the
+ * listing's truncate-then-floor): with s = sb + shift,
+ *   y = floor((t * mult + 2^(s-1)) / 2^s)     (nearest integer to t * mult / 2^s, halves upward)
+ *   y = t * mult * 2^(-s)                     for s <= 0 (exact)
+ * then + z_out and the clamp as above. */
+int64_t orc_requant_nearest_one(int64_t t, int64_t mult, int sb, int shift,
+                                int64_t z_out, int64_t lo, int64_t hi) {
+    __int128 p = (__int128)t * (__int128)mult;
+    int s = sb + shift;
+    __int128 y;
+    if (s <= 0) {
+        y = p * ((__int128)1 << (-s));
+    } else {
+        __int128 d = (__int128)1 << s;
+        __int128 v = p + (d >> 1);
+        y = v / d;
+        if ((v % d) != 0 && v < 0) y -= 1;
+    }
+    y += z_out;
+    if (y < lo) y = lo;
+    if (y > hi) y = hi;
+    return (int64_t)y;
+}
+
+void orc_requant_nearest(const int64_t *t, size_t count, int64_t mult, int sb, int shift,
+                         int32_t z_out, int32_t qmin, int32_t qmax, int relu, int32_t *q) {
+    int64_t lo = qmin;
+    if (relu && z_out > qmin) lo = z_out;
+    for (size_t i = 0; i < count; ++i) {
+        q[i] = (int32_t)orc_requant_nearest_one(t[i], mult, sb, shift, z_out, lo, qmax);
+    }
+}
+
 void orc_requant(const int64_t *t, size_t count, int64_t mult, int sb, int shift,
                  int32_t z_out, int32_t qmin, int32_t qmax, int relu, int32_t *q) {
     int64_t lo = qmin;

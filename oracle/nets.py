@@ -25,23 +25,23 @@ def quantize_params(w_real, b_real, sc, dtype, z_w=0):
     return wq, bq
 
 
-def int_conv(xq, z_x, s_x, wq, z_w, bq, L, sc, dtype, z_y=0):
+def int_conv(xq, z_x, s_x, wq, z_w, bq, L, sc, dtype, z_y=0, nearest=False):
     """conv accumulate -> requantize (ReLU as raised clamp) -> optional max-pool."""
     t = o.conv2d_acc(xq, z_x, wq, z_w, bq, L.stride, L.pad, L.groups)
     mult, shift = o.scale_quant_vals(s_x, sc["w"], sc["y"], o.SHIFT_BITS[dtype])
-    y = o.requant(t, mult, o.SHIFT_BITS[dtype], shift, z_y, dtype, L.relu)
+    y = o.requant(t, mult, o.SHIFT_BITS[dtype], shift, z_y, dtype, L.relu, nearest)
     if L.pool_k:
         y = o.maxpool_i32(y, L.pool_k, L.pool_s)
     return y
 
 
-def int_fc(xq, z_x, s_x, wq, z_w, bq, L, sc, dtype, z_y=0):
+def int_fc(xq, z_x, s_x, wq, z_w, bq, L, sc, dtype, z_y=0, nearest=False):
     t = o.gemm_acc(xq, z_x, wq, z_w, bq)
     mult, shift = o.scale_quant_vals(s_x, sc["w"], sc["y"], o.SHIFT_BITS[dtype])
-    return o.requant(t, mult, o.SHIFT_BITS[dtype], shift, z_y, dtype, L.relu)
+    return o.requant(t, mult, o.SHIFT_BITS[dtype], shift, z_y, dtype, L.relu, nearest)
 
 
-def run_int_chain(layers, x_real, params_real, s_in, scales, dtype, collect=False):
+def run_int_chain(layers, x_real, params_real, s_in, scales, dtype, collect=False, nearest=False):
     """Quantize the real input at scale s_in, then run conv / FC layers in order.  An FC layer
     after a conv layer sees the activation flattened in (C,H,W) order, as the paper's framework
     does.  Returns the final codes (and every layer's output if collect)."""
@@ -51,9 +51,9 @@ def run_int_chain(layers, x_real, params_real, s_in, scales, dtype, collect=Fals
     for L, (w, b), sc in zip(layers, params_real, scales):
         wq, bq = quantize_params(w, b, sc, dtype)
         if L.kind == "conv":
-            xq = int_conv(xq, 0, s_x, wq, 0, bq, L, sc, dtype)
+            xq = int_conv(xq, 0, s_x, wq, 0, bq, L, sc, dtype, nearest=nearest)
         else:
-            xq = int_fc(xq.reshape(xq.shape[0], -1), 0, s_x, wq, 0, bq, L, sc, dtype)
+            xq = int_fc(xq.reshape(xq.shape[0], -1), 0, s_x, wq, 0, bq, L, sc, dtype, nearest=nearest)
         s_x = sc["y"]
         outs.append(xq)
     return (xq, outs) if collect else xq

@@ -42,8 +42,11 @@ def _declare(L):
     L.orc_requant_one.argtypes = [C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int64, C.c_int64,
                                   C.c_int64]
     L.orc_requant_one.restype = C.c_int64
+    L.orc_requant_nearest_one.argtypes = L.orc_requant_one.argtypes
+    L.orc_requant_nearest_one.restype = C.c_int64
     L.orc_requant.argtypes = [i64p, C.c_size_t, C.c_int64, C.c_int, C.c_int, C.c_int32,
                               C.c_int32, C.c_int32, C.c_int, i32p]
+    L.orc_requant_nearest.argtypes = L.orc_requant.argtypes
     conv_args = [i32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int32,
                  i32p, C.c_int, C.c_int, C.c_int, C.c_int32, i64p,
                  C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i64p]
@@ -141,12 +144,19 @@ def requant_one(t, mult, sb, shift, z_out, lo, hi):
                                      int(hi)))
 
 
-def requant(t, mult, sb, shift, z_out, dtype, relu):
+def requant_nearest_one(t, mult, sb, shift, z_out, lo, hi):
+    return int(lib().orc_requant_nearest_one(int(t), int(mult), int(sb), int(shift), int(z_out), int(lo),
+                                             int(hi)))
+
+
+def requant(t, mult, sb, shift, z_out, dtype, relu, nearest=False):
+    """nearest=False: the listing's truncate-then-floor rule; True: one rounding to nearest."""
     qmin, qmax = QRANGE[dtype]
     t = _c(t, np.int64)
     q = np.empty(t.shape, np.int32)
-    lib().orc_requant(_p(t, C.c_int64), t.size, int(mult), int(sb), int(shift), int(z_out), qmin,
-                      qmax, int(bool(relu)), _p(q, C.c_int32))
+    fn = lib().orc_requant_nearest if nearest else lib().orc_requant
+    fn(_p(t, C.c_int64), t.size, int(mult), int(sb), int(shift), int(z_out), qmin,
+       qmax, int(bool(relu)), _p(q, C.c_int32))
     return q
 
 

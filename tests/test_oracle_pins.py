@@ -167,6 +167,36 @@ def test_requant_bigint_and_real_bracket(dtype):
                         assert (g - z) <= exact + slack
 
 
+@pytest.mark.parametrize("dtype", ["int8", "int16"])
+def test_requant_nearest_is_the_nearest_integer_of_the_exact_product(dtype):
+    """Round-to-nearest variant against exact rational arithmetic: floor(t mult / 2^(sb + shift) + 1/2)."""
+    import math
+    qmin, qmax = o.QRANGE[dtype]
+    sb = o.SHIFT_BITS[dtype]
+    big = 2 ** 31 - 1 if dtype == "int8" else 2 ** 44
+    ts = np.concatenate([gen.integers(5, (400,), -5000, 5000), gen.integers(6, (200,), -big, big), np.arange(-40, 41)])
+    for sa, sw, sy in [(0.02, 0.01, 0.05), (0.5, 0.5, 0.01), (1.0, 1.0, 1.0), (3e-3, 7e-3, 0.9), (2.0, 3.0, 0.5), (1e-4, 1e-4, 30.0)]:
+        mult, shift = o.scale_quant_vals(sa, sw, sy, sb)
+        for z in (0, -7):
+            got = o.requant(ts, mult, sb, shift, z, dtype, relu=False, nearest=True)
+            for t, g in zip(ts.tolist(), got.tolist()):
+                exact = Fraction(t * mult, 1) / (Fraction(2) ** (sb + shift))
+                assert g == min(max(math.floor(exact + Fraction(1, 2)) + z, qmin), qmax)
+    # closed forms, M = 1/4 (mult = 2^30, sb = 31, shift = 1): halves go upward, also below zero
+    expect = {0: 0, 1: 0, 2: 1, 3: 1, 5: 1, 6: 2, -1: 0, -2: 0, -3: -1, -6: -1, -7: -2}
+    for t, y in expect.items():
+        assert o.requant_nearest_one(t, 1 << 30, 31, 1, 0, -128, 127) == y
+    # ReLU as the raised clamp, and saturation
+    assert o.requant(np.array([-9, 1000]), 1 << 30, 31, 1, 3, "int8", relu=True, nearest=True).tolist() == [3, 127]
+    # never further than half a step from the exact product, where the truncating rule may be a whole step off
+    t = gen.integers(8, (2000,), -100000, 100000)
+    mult, shift = o.scale_quant_vals(0.02, 0.01, 0.05, 31)
+    near = o.requant(t, mult, 31, shift, 0, "int16", relu=False, nearest=True).astype(np.float64)
+    trunc = o.requant(t, mult, 31, shift, 0, "int16", relu=False).astype(np.float64)
+    exact = t * (mult / 2.0 ** (31 + shift))
+    assert np.max(np.abs(near - exact)) <= 0.5 + 1e-9 and np.max(np.abs(trunc - exact)) > 0.9
+
+
 def test_requant_negative_truncates_then_floors():
     # mult = 2^30 (M0 = 0.5), sb = 31, shift = 1: y = trunc(t / 2) then floor(y / 2)
     mult, sb, shift = 1 << 30, 31, 1
