@@ -76,6 +76,8 @@ typedef struct {
     int32_t groups;
     int32_t relu;
     int32_t pool_k, pool_s;       /* 0, 0 = no pooling */
+    int32_t rounding;             /* integer rescale: 0 = truncate, then floor (the paper's listing);
+                                     1 = one rounding to the nearest integer, halves upward */
 } mpq_conv_desc;
 
 const char *mpq_status_string(mpq_status s);
@@ -152,6 +154,9 @@ mpq_status mpq_pack_weights(const void *w_kcrs, const mpq_conv_desc *d, mpq_dtyp
  *   y   = (t * mult) / 2^sb   truncating toward zero, then  >> shift  (arithmetic; a negative
  *         shift multiplies by 2^-shift)                      (integer branch of the quantized
  *         ReLU listing in section "Emitted OpenCL Runtime Code", applied to every operator)
+ *         with d->rounding = 1 instead: y = floor((t * mult + 2^(sb+shift-1)) / 2^(sb+shift)), the
+ *         nearest integer to t * mult / 2^(sb+shift) (the paper leaves the rounding of the rescale
+ *         to the operator; the fast ReLU path of the 8-bit kernels serves rounding 0 only)
  *   out = min(max(y + z_y, lo), type_max), lo = relu ? max(type_min, z_y) : type_min
  * y.dtype may instead be MPQ_INT32: then out = t (raw accumulator, no rescale; used for gating).
  * MPQ_FP16: out = fp16(relu(sum in fp32 of x w + bias[k])), bias fp32; y.dtype MPQ_FP16 or

@@ -38,7 +38,7 @@ class ConvDesc(C.Structure):
     _fields_ = [("c", C.c_int32), ("k", C.c_int32), ("r", C.c_int32), ("s", C.c_int32),
                 ("stride_h", C.c_int32), ("stride_w", C.c_int32), ("pad_h", C.c_int32),
                 ("pad_w", C.c_int32), ("groups", C.c_int32), ("relu", C.c_int32),
-                ("pool_k", C.c_int32), ("pool_s", C.c_int32)]
+                ("pool_k", C.c_int32), ("pool_s", C.c_int32), ("rounding", C.c_int32)]
 
 
 class MoeLayer(C.Structure):
@@ -126,8 +126,8 @@ def tensor(t, dtype, n, h, w, c, scale=1.0, zero_point=0):
     return Tensor(_ptr(t), dtype, n, h, w, c, QParams(float(scale), int(zero_point)))
 
 
-def conv_desc(c, k, r, s, stride=1, pad=0, groups=1, relu=False, pool_k=0, pool_s=0):
-    return ConvDesc(c, k, r, s, stride, stride, pad, pad, groups, int(bool(relu)), pool_k, pool_s)
+def conv_desc(c, k, r, s, stride=1, pad=0, groups=1, relu=False, pool_k=0, pool_s=0, rounding=0):
+    return ConvDesc(c, k, r, s, stride, stride, pad, pad, groups, int(bool(relu)), pool_k, pool_s, rounding)
 
 
 def gemm_desc(k_in, n_out, relu=False):

@@ -113,6 +113,7 @@ bool desc_ok(const mpq_conv_desc &d) {
     if (d.stride_h < 1 || d.stride_w < 1 || d.pad_h < 0 || d.pad_w < 0) return false;
     if (d.groups < 1 || d.c % d.groups != 0 || d.k % d.groups != 0) return false;
     if (d.pool_k < 0 || (d.pool_k > 0 && d.pool_s < 1)) return false;
+    if (d.rounding != 0 && d.rounding != 1) return false;
     if ((long long)d.r * d.s * (d.c / d.groups) > (1ll << 28)) return false;
     return true;
 }
@@ -138,9 +139,10 @@ mpq_status rescale_constants(float s_x, float s_w, float s_y, int dtype, long lo
 }
 
 mpq_status build_epi(int in_dtype, int out_dtype, const mpq_qparams &xq, const mpq_qparams &wq,
-                     const mpq_qparams &yq, int relu, Epi *e) {
+                     const mpq_qparams &yq, int relu, int rounding, Epi *e) {
     std::memset(e, 0, sizeof(*e));
     e->relu = relu ? 1 : 0;
+    e->rnd = rounding ? 1 : 0;
     if (in_dtype == MPQ_FP16) {
         e->kind = out_dtype == MPQ_FP32 ? kEpiRawF32 : kEpiHalf;
         return MPQ_OK;
@@ -535,7 +537,7 @@ const char *mpq_status_string(mpq_status s) {
     }
 }
 
-int32_t mpq_abi_version(void) { return 1; }
+int32_t mpq_abi_version(void) { return 2; }
 
 mpq_status mpq_quantize(const float *src, void *dst, size_t count, mpq_dtype dtype, mpq_qparams q,
                         void *stream) {
@@ -650,7 +652,7 @@ mpq_status mpq_conv2d(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q
     mpq_status s = check_conv_args(x, w_packed, w_q, y, d, &g);
     if (s != MPQ_OK) return s;
     Epi epi;
-    s = build_epi(x->dtype, y->dtype, x->q, w_q, y->q, d->relu, &epi);
+    s = build_epi(x->dtype, y->dtype, x->q, w_q, y->q, d->relu, d->rounding, &epi);
     if (s != MPQ_OK) return s;
     if (x->n == 0) return MPQ_OK;
     return run_conv(*x, w_packed, bias, y->data, y->dtype, *d, epi, nullptr, ws, ws_bytes, (hipStream_t)stream);
@@ -822,7 +824,7 @@ mpq_status mpq_moe_forward(const mpq_tensor *x, const void *logits, mpq_dtype lo
         segs[i].w_stride = layers[i].w_stride;
         for (int e = 0; e < E; ++e) {
             mpq_qparams xq = i == 0 ? x->q : layers[i - 1].y_q[e];
-            s = build_epi(x->dtype, x->dtype, xq, layers[i].w_q[e], layers[i].y_q[e], layers[i].desc.relu,
+            s = build_epi(x->dtype, x->dtype, xq, layers[i].w_q[e], layers[i].y_q[e], layers[i].desc.relu, layers[i].desc.rounding,
                           &segs[i].epi[e]);
             if (s != MPQ_OK) return s;
         }

@@ -76,7 +76,7 @@ struct Epi {
     int lo, hi;
     int zx, zw;
     int relu;
-    int pad_;
+    int rnd;       // 1: one rounding to nearest instead of truncate-then-floor
 };
 
 constexpr int kMaxExperts = 16;

@@ -11,12 +11,20 @@
 
 namespace mpq {
 
+// (rnd: the round-to-nearest variant, y = floor((p + 2^(s-1)) / 2^s) with s = sb + shift >= 0;
+// |p| < 2^62, so for s >= 63 the result is 0)
 __device__ __forceinline__ int requant64(long long t, const Epi &e) {
     long long p = t * e.mult;
-    // truncating division by 2^sb: bias negatives by 2^sb - 1, then shift
-    long long y = (p + ((p >> 63) & ((1ll << e.sb) - 1))) >> e.sb;
-    if (e.shift >= 0) y >>= e.shift;
-    else y *= (1ll << (-e.shift));
+    long long y;
+    if (e.rnd) {
+        const int s = e.sb + e.shift;
+        y = s <= 0 ? p * (1ll << (-s)) : (s >= 63 ? 0ll : (p + (1ll << (s - 1))) >> s);
+    } else {
+        // truncating division by 2^sb: bias negatives by 2^sb - 1, then shift
+        y = (p + ((p >> 63) & ((1ll << e.sb) - 1))) >> e.sb;
+        if (e.shift >= 0) y >>= e.shift;
+        else y *= (1ll << (-e.shift));
+    }
     y += e.zy;
     y = y < e.lo ? e.lo : y;
     y = y > e.hi ? e.hi : y;
@@ -27,7 +35,7 @@ __device__ __forceinline__ int requant64(long long t, const Epi &e) {
 // t * mult is formed as a (high, low) pair; floor(p / 2^31) = (high << 1) | (low >> 31), and the
 // truncation adds one back when p is negative with a non-zero remainder.  |y| <= |t| fits int32.
 __device__ __forceinline__ int requant32(int t, const Epi &e) {
-    if (e.shift < 0 || e.sb != 31) return requant64((long long)t, e);
+    if (e.shift < 0 || e.sb != 31 || e.rnd) return requant64((long long)t, e);
     const int mult = (int)e.mult;
     const int hi = __mulhi(t, mult);
     const unsigned lo = (unsigned)t * (unsigned)mult;
@@ -65,7 +73,7 @@ __device__ __forceinline__ FastRequant make_fast_requant(const Epi &e) {
 }
 
 __device__ __forceinline__ bool fast_requant_ok(const Epi &e) {
-    return e.kind == kEpiRequant && e.relu && e.shift >= 1 && e.sb == 31;
+    return e.kind == kEpiRequant && e.relu && e.shift >= 1 && e.sb == 31 && !e.rnd;
 }
 
 __device__ __forceinline__ unsigned requant4_fast(int t0, int t1, int t2, int t3, const FastRequant &f) {

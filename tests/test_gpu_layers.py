@@ -112,7 +112,7 @@ def test_observe_minmax_then_estimate_and_quantize():
 # ---------------------------------------------------------------------------------------------
 # integer convolution
 # ---------------------------------------------------------------------------------------------
-def _int_conv_case(dtype, N, C, H, W, K, R, S, stride, pad, groups, relu, pool, zx, zw, zy, seed, raw=False):
+def _int_conv_case(dtype, N, C, H, W, K, R, S, stride, pad, groups, relu, pool, zx, zw, zy, seed, raw=False, nearest=False):
     name = gu.NAME[dtype]
     qmin, qmax = o.QRANGE[name]
     x = gen.integers(seed, (N, C, H, W), qmin, qmax)
@@ -122,7 +122,7 @@ def _int_conv_case(dtype, N, C, H, W, K, R, S, stride, pad, groups, relu, pool, 
     # output scale from the accumulator spread so that codes fill the range without all saturating
     s_x, s_w = np.float32(0.021), np.float32(0.013)
     s_y = np.float32(float(s_x) * float(s_w) * float(np.std(t)) * 3.0 / qmax + 1e-12)
-    desc = mb.conv_desc(C, K, R, S, stride, pad, groups, relu, pool[0], pool[1])
+    desc = mb.conv_desc(C, K, R, S, stride, pad, groups, relu, pool[0], pool[1], rounding=int(nearest))
     xd = gu.codes_to_dev(x, dtype)
     wd = torch.from_numpy(np.ascontiguousarray(w.astype(gu.NP_STORE[dtype]))).to("cuda")
     bd = torch.from_numpy(b.astype(np.int32)).to("cuda")
@@ -132,7 +132,10 @@ def _int_conv_case(dtype, N, C, H, W, K, R, S, stride, pad, groups, relu, pool, 
         return
     y = gu.run_conv(xd, (s_x, zx), wd, (s_w, zw), bd, desc, dtype, (s_y, zy))
     mult, shift = o.scale_quant_vals(s_x, s_w, s_y, o.SHIFT_BITS[name])
-    ref = o.requant(t, mult, o.SHIFT_BITS[name], shift, zy, name, relu)
+    ref = o.requant(t, mult, o.SHIFT_BITS[name], shift, zy, name, relu, nearest)
+    if nearest:
+        # the option matters here: the truncating rule gives a different tensor
+        assert not np.array_equal(ref, o.requant(t, mult, o.SHIFT_BITS[name], shift, zy, name, relu))
     if pool[0]:
         ref = o.maxpool_i32(ref, pool[0], pool[1])
     got = gu.to_nchw(y).astype(np.int32)
@@ -246,6 +249,29 @@ CONV_CASES = [
 def test_int8_conv(case):
     _say("int8 conv", case)
     _int_conv_case(mb.INT8, *case, seed=1000 + 17 * CONV_CASES.index(case))
+
+
+@pytest.mark.parametrize("idx", [0, 2, 3, 4, 5, 8, 19, 25])
+def test_int8_conv_round_to_nearest(idx):
+    """The rescale's round-to-nearest option on every int8 kernel family (patch, fused pools, strided,
+    1x1, first-layer, direct, row tiles, weight zero-point)."""
+    _say("int8 nearest", CONV_CASES[idx])
+    _int_conv_case(mb.INT8, *CONV_CASES[idx], seed=8000 + idx, nearest=True)
+
+
+@pytest.mark.parametrize("idx", [0, 3, 5, 8, 18])
+def test_int16_conv_round_to_nearest(idx):
+    _say("int16 nearest", CONV_CASES[idx])
+    _int_conv_case(mb.INT16, *CONV_CASES[idx], seed=8100 + idx, nearest=True)
+
+
+@pytest.mark.parametrize("M", [1, 3, 40, 300])
+@pytest.mark.parametrize("dtype", [mb.INT8, mb.INT16])
+def test_fc_round_to_nearest(M, dtype):
+    """FC layers (a 1x1 convolution on a 1x1 image through mpq_conv2d, which carries the option):
+    batch 1..3 on the streaming kernel, 40 and 300 on the matrix-core FC kernels."""
+    _say("fc nearest", M, dtype)
+    _int_conv_case(dtype, M, 1024, 1, 1, 260, 1, 1, 1, 0, 1, True, (0, 0), 0, 0, 3, seed=8200 + M, nearest=True)
 
 
 # (int16 layers of at least 2^24 multiply-accumulates whose shape the int8 kernels accept run as
