@@ -204,10 +204,24 @@ struct Tile {
     static_assert(WGC * WGP == 4, "four wavefronts per workgroup");
     static_assert((CH16 & (CH16 - 1)) == 0, "chunks per output row must be a power of two");
 
-    // Accumulators start at the epilogue's per-channel constant: the bias, minus z_x * sum(w) for int8.
+    // Accumulators start at the epilogue's per-channel constant: the bias, minus z_x * sum(w) for int8;
+    // with a weight zero-point also minus z_w times the pixel's window sum of (x - z_x), which a
+    // kernel before this one left in a.xsum (sum (x - z_x)(w - z_w) = sum (x - z_x) w - z_w sum (x - z_x)).
     static __device__ __forceinline__ void init_acc(Acc (&acc)[TC][TP], const ConvArgs &a, const TileCtx &t) {
         const Plan &pl = a.plan;
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wc = wave % WGC;
+        int corr[TP];
+#pragma unroll
+        for (int j = 0; j < TP; ++j) corr[j] = 0;
+        if constexpr (ES == 1) {
+            if (a.xsum) {
+#pragma unroll
+                for (int j = 0; j < TP; ++j) {
+                    const int m = t.m0 + (wave / WGC) * WTP + j * 32 + (lane & 31);
+                    corr[j] = m < t.m_end ? a.zw_corr * a.xsum[(size_t)m * a.groups + t.g] : 0;
+                }
+            }
+        }
         const int *wsum = reinterpret_cast<const int *>(t.wbase + pl.wsum_off);
         // all loads first, unconditionally (a missing bias reads the always-present sums and is
         // masked afterwards): with the loads under branches each one was waited for in turn
@@ -233,7 +247,7 @@ struct Tile {
 #pragma unroll
                     for (int j = 0; j < TP; ++j)
 #pragma unroll
-                        for (int u = 0; u < 4; ++u) acc[i][j][vq * 4 + u] = b4[u];
+                        for (int u = 0; u < 4; ++u) acc[i][j][vq * 4 + u] = b4[u] - corr[j];
                 } else {
                     typedef float v4f __attribute__((ext_vector_type(4)));
                     const v4f bb = has_bias ? __builtin_bit_cast(v4f, braw[i][vq]) : v4f{0.f, 0.f, 0.f, 0.f};
@@ -252,55 +266,72 @@ struct Tile {
     // written with 16-byte stores in which consecutive lanes cover consecutive channels of a pixel,
     // so that every store instruction fills whole cache lines.  Raw accumulator outputs (gating
     // logits) are stored directly.  `lds` must hold kImageBytes and be idle (barrier before).
-    // Raw 32-bit results (int32 sums, fp32 sums after bias and ReLU): the tile leaves in passes of
-    // ROWB bytes per pixel, each transposed through the LDS image like the narrow outputs, so that a
-    // store instruction writes contiguous runs of a pixel's channels instead of 16 bytes per pixel.
+    // Raw 32-bit results.  int32 sums (the digit-plane convolutions of int16 layers write six of
+    // them per layer): the tile leaves in passes of ROWB bytes per pixel, each transposed through the
+    // LDS image like the narrow outputs, so that a store instruction writes contiguous runs of a
+    // pixel's channels instead of 16 bytes per pixel.
     static __device__ __forceinline__ void finish_raw(Acc (&acc)[TC][TP], unsigned char *lds, const ConvArgs &a,
                                                       const TileCtx &t) {
         const Plan &pl = a.plan;
         const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
         const int wc = wave % WGC, wp = wave / WGC;
         const int frow = lane & 31, fk = lane >> 5;
-        constexpr int PASSES = 4 / ES;          // 32-bit results are 4 / ES times as wide as the narrow image
-        constexpr int CPP = BC / PASSES;        // channels per pass
-#pragma unroll 1
-        for (int ps = 0; ps < PASSES; ++ps) {
-            if (ps > 0) __syncthreads();
+        if constexpr (ES == 2) {
+            // fp32 sums (gating logits): straight from the accumulators, 16 bytes per pixel and lane.
+            // (The LDS passes below cost this instance registers it does not have.)
 #pragma unroll
             for (int i = 0; i < TC; ++i) {
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {
-                    const int chl = wc * WTC + i * 32 + vq * 8 + fk * 4;
-                    if (chl / CPP != ps) continue;
-                    const unsigned cb = (unsigned)((chl - ps * CPP) * 4);
+                    const int ch = t.ch0 + wc * WTC + i * 32 + vq * 8 + fk * 4;
+                    if (ch >= pl.Kg) continue;
 #pragma unroll
                     for (int j = 0; j < TP; ++j) {
-                        const int row = wp * WTP + j * 32 + frow;
-                        const unsigned la = (unsigned)(row * ROWB) + (((cb >> 4) ^ (unsigned)(row & (CH16 - 1))) << 4);
-                        if constexpr (ES == 1) {
-                            *reinterpret_cast<v4i *>(lds + la) = v4i{acc[i][j][vq * 4], acc[i][j][vq * 4 + 1],
-                                                                   acc[i][j][vq * 4 + 2], acc[i][j][vq * 4 + 3]};
-                        } else {
-                            float f[4];
+                        const int m = t.m0 + wp * WTP + j * 32 + frow;
+                        if (m >= t.m_end) continue;
+                        float f[4];
 #pragma unroll
-                            for (int u = 0; u < 4; ++u) {
-                                f[u] = acc[i][j][vq * 4 + u];
-                                if (t.epi.relu) f[u] = f[u] > 0.f ? f[u] : 0.f;
-                            }
-                            *reinterpret_cast<float4 *>(lds + la) = make_float4(f[0], f[1], f[2], f[3]);
+                        for (int u = 0; u < 4; ++u) {
+                            f[u] = acc[i][j][vq * 4 + u];
+                            if (t.epi.relu) f[u] = f[u] > 0.f ? f[u] : 0.f;
                         }
+                        *reinterpret_cast<float4 *>((float *)a.y + (size_t)m * a.K + (size_t)(t.g * pl.Kg + ch)) =
+                            make_float4(f[0], f[1], f[2], f[3]);
                     }
                 }
             }
-            __syncthreads();
+        } else {
+            constexpr int PASSES = 4;               // int32 results are four times as wide as the int8 image
+            constexpr int CPP = BC / PASSES;        // channels per pass
+#pragma unroll 1
+            for (int ps = 0; ps < PASSES; ++ps) {
+                if (ps > 0) __syncthreads();
+#pragma unroll
+                for (int i = 0; i < TC; ++i) {
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const int chl = wc * WTC + i * 32 + vq * 8 + fk * 4;
+                        if (chl / CPP != ps) continue;
+                        const unsigned cb = (unsigned)((chl - ps * CPP) * 4);
+#pragma unroll
+                        for (int j = 0; j < TP; ++j) {
+                            const int row = wp * WTP + j * 32 + frow;
+                            const unsigned la = (unsigned)(row * ROWB) + (((cb >> 4) ^ (unsigned)(row & (CH16 - 1))) << 4);
+                            *reinterpret_cast<v4i *>(lds + la) = v4i{(int)acc[i][j][vq * 4], (int)acc[i][j][vq * 4 + 1],
+                                                                   (int)acc[i][j][vq * 4 + 2], (int)acc[i][j][vq * 4 + 3]};
+                        }
+                    }
+                }
+                __syncthreads();
 #pragma unroll 4
-            for (int idx = tid; idx < BP * CH16; idx += kThreads) {
-                const int row = idx / CH16, c16 = idx % CH16;
-                const int m = t.m0 + row;
-                const int ch = t.ch0 + ps * CPP + c16 * 4;
-                if (m >= t.m_end || ch >= pl.Kg) continue;
-                const v4i v = *reinterpret_cast<const v4i *>(lds + row * ROWB + ((c16 ^ (row & (CH16 - 1))) << 4));
-                *reinterpret_cast<v4i *>((int *)a.y + (size_t)m * a.K + (size_t)(t.g * pl.Kg + ch)) = v;
+                for (int idx = tid; idx < BP * CH16; idx += kThreads) {
+                    const int row = idx / CH16, c16 = idx % CH16;
+                    const int m = t.m0 + row;
+                    const int ch = t.ch0 + ps * CPP + c16 * 4;
+                    if (m >= t.m_end || ch >= pl.Kg) continue;
+                    const v4i v = *reinterpret_cast<const v4i *>(lds + row * ROWB + ((c16 ^ (row & (CH16 - 1))) << 4));
+                    *reinterpret_cast<v4i *>((int *)a.y + (size_t)m * a.K + (size_t)(t.g * pl.Kg + ch)) = v;
+                }
             }
         }
     }
@@ -317,21 +348,6 @@ struct Tile {
         const int frow = lane & 31, fk = lane >> 5;
         const int g = t.g, m0 = t.m0, m_end = t.m_end, ch0 = t.ch0;
         const bool raw = epi.kind == kEpiRawI32 || epi.kind == kEpiRawF32;
-        if constexpr (ES == 1) {
-            // weight zero-point: sum (x - z_x)(w - z_w) = sum (x - z_x) w - z_w sum (x - z_x); the second
-            // sum belongs to the pixel (and group) and was made by a kernel before this one
-            if (a.xsum) {
-#pragma unroll
-                for (int j = 0; j < TP; ++j) {
-                    const int m = t.m0 + wp * WTP + j * 32 + frow;
-                    const int corr = m < t.m_end ? a.zw_corr * a.xsum[(size_t)m * a.groups + t.g] : 0;
-#pragma unroll
-                    for (int i = 0; i < TC; ++i)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) acc[i][j][v] -= corr;
-                }
-            }
-        }
         if (raw) {
             finish_raw(acc, lds, a, t);
             return;
