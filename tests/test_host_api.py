@@ -152,3 +152,19 @@ def test_moe_argument_errors():
     assert _status(mb.mpq_moe_forward, x, FAKE, mb.INT32, 2, 1, [layer], ybad, ws=FAKE + (1 << 20), ws_bytes=1 << 20) == 2
     small = mb.MoeLayer(d, 1, FAKE, 256, None, q, q)                                      # expert stride too small
     assert _status(mb.mpq_moe_forward, x, FAKE, mb.INT32, 2, 1, [small], y) == 4
+
+
+def test_no_kernel_spills_registers():
+    """Every kernel of the last build keeps its registers: no scratch memory per lane (a change in
+    a shared epilogue once cost the 128-channel convolution instances 320 bytes of it and a third
+    of their speed), and the matrix-core kernels leave room for two workgroups per CU."""
+    from paper_2209_15427_amd import build as b
+    rows = b.kernel_resources()
+    if not rows:
+        pytest.skip("no build record (the library was not built in this tree)")
+    assert len(rows) > 50
+    spilled = [(r["file"], r["kernel"], r["scratch"]) for r in rows if r["scratch"] > 0]
+    assert not spilled, spilled
+    for r in rows:
+        if r["file"] in ("conv_patch.hip", "conv_mfma_dma.hip", "conv_first.hip", "fc_frag.hip"):
+            assert r["VGPRs"] + r["AGPRs"] <= 512 and r["occupancy"] >= 1, r
