@@ -1,5 +1,6 @@
 // Direct convolution for every geometry, dtype and zero-point combination the MFMA kernels do
-// not cover (small or odd channel counts, non-zero weight zero-point, int16).  One thread per
+// not cover (small or odd channel counts; int16 layers that are small, carry a weight zero-point
+// or come without the optional workspace; weight zero-points in expert-grouped launches).  One thread per
 // (output pixel, 4 output channels); differences-first accumulation
 //   acc = sum (x - z_x)(w - z_w)      (first quantized-multiply equation, section
 //                                      "Quantized Operations")
