@@ -258,6 +258,27 @@ def test_moe_all_to_one_expert_and_empty_experts():
     assert np.array_equal(y.cpu().numpy().reshape(ref.shape).astype(np.int32), ref)
 
 
+def test_moe_int16_digit_planes_with_empty_and_single_experts():
+    """int16 expert convolution large enough for the digit-plane path: everything routed to one
+    expert (two empty segments), then one sample each for two experts and the rest to the third."""
+    B = 160
+    layers, params, scales, x, E = _tiny_moe_case("int16", B, 860)
+    s_x = 0.02 * 127.0 / 32767
+    for variant in range(2):
+        logits = gen.integers(7 + variant, (B, E), -50, 50)
+        if variant == 0:
+            logits[:, 1] += 1000
+        else:
+            logits[:, 2] += 1000
+            logits[0, 0] += 5000
+            logits[B - 1, 1] += 5000
+        y, idx, cnt = _moe_device(x, s_x, logits, layers, params, scales, mb.INT16, mb.INT32)
+        ref, e_ref, c_ref = nets.moe_int(x, s_x, logits.astype(np.float64), layers, params, scales, "int16")
+        assert np.array_equal(idx, e_ref) and np.array_equal(cnt, c_ref)
+        assert list(cnt) == ([0, B, 0] if variant == 0 else [1, 1, B - 2])
+        assert np.array_equal(y.cpu().numpy().reshape(ref.shape).astype(np.int32), ref)
+
+
 def test_moe_topk_fp16():
     layers = [cf.Conv("c", 64, 32, 3, 3, pad=1, groups=2, pool_k=3, pool_s=2), cf.FC("f", 40, 64 * 3 * 3)]
     E, B, K = 4, 50, 2
