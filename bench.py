@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the FC / MoE side measurements")
     ap.add_argument("--cpu-images", type=int, default=256, help="images the oracle is timed on")
+    ap.add_argument("--no-two-stream", action="store_true",
+                    help="skip the extra two-batches-in-flight figure (kernel traces: its kernels overlap)")
     ap.add_argument("--profile-layer", default=None,
                     help="for counter collection: run only this layer's kernels as the step runs them (conv1..conv5; a "
                          "layer whose pool is a separate kernel: without the pool), or 'copy' (a 256 MiB device "
@@ -166,7 +168,7 @@ def main():
     # (quantize, the pool fix-up) beside batch i's matrix-core kernels: two chains with their own
     # activations and workspace, steps alternating between two branches of one graph.
     pipelined = None
-    if not args.eager and not args.no_extras:
+    if not args.eager and not args.no_extras and not args.no_two_stream:
         if args.dtype == "fp16":
             chain_b = pl.Chain(cf.ALEXNET_CONVS, params, dt, B, cf.ALEXNET_INPUT)
         else:
