@@ -34,7 +34,8 @@ def parse():
     ap.add_argument("--no-two-stream", action="store_true",
                     help="skip the extra two-batches-in-flight figure (kernel traces: its kernels overlap)")
     ap.add_argument("--profile-layer", default=None,
-                    help="for counter collection: run only this layer's kernels as the step runs them (conv1..conv5; a "
+                    help="for counter collection: fc6 / fc7 / fc8 = that FC layer at batch 1 with cold weights; otherwise "
+                         "run only this layer's kernels as the step runs them (conv1..conv5; a "
                          "layer whose pool is a separate kernel: without the pool), or 'copy' (a 256 MiB device "
                          "copy), --steps times, print nothing else")
     return ap.parse_args()
@@ -97,6 +98,11 @@ def main():
             mb.mpq_quantize(x_dev, x_store, n_in, dt, chain.s_in, 0)
         return chain.forward(x_store)
 
+    if args.profile_layer and args.profile_layer.startswith("fc"):
+        # batch-1 FC layer, cold weights: --steps passes over > 320 MB of weight copies, eager launches
+        bench_fc(torch, mb, pl, cf, calib, args.dtype, only=args.profile_layer, eager_passes=args.steps)
+        print(json.dumps({"profile_layer": args.profile_layer, "passes": args.steps}))
+        return
     if args.profile_layer:
         step()
         torch.cuda.synchronize()
@@ -438,12 +444,15 @@ def bench_moe(torch, mb, pl, cf, calib, dtype_name, trunk_out, batch):
             "expert_tops": round(2.0 * macs * batch / (moe_us * 1e-6) / 1e12, 1)}
 
 
-def bench_fc(torch, mb, pl, cf, calib, dtype_name):
+def bench_fc(torch, mb, pl, cf, calib, dtype_name, only=None, eager_passes=0):
     """Batch-1 FC layers, cold weights: every launch reads a different copy of the packed
-    weights, the copies together exceeding the 256 MB Infinity Cache."""
+    weights, the copies together exceeding the 256 MB Infinity Cache.
+    (only / eager_passes: counter collection — that layer alone, launched one by one.)"""
     dt = mb.DTYPE_ID[dtype_name]
     res = {}
     for li, L in enumerate(cf.ALEXNET_FCS):
+        if only and L.name != only:
+            continue
         _, x, w, b = cf.fc_case(li, 1)
         if dtype_name == "fp16":
             lay = pl.Layer(L, w, b, dt)
@@ -469,6 +478,12 @@ def bench_fc(torch, mb, pl, cf, calib, dtype_name):
         def run(c):
             mb.mpq_gemm(xv, ptrs[c], lay.w_scale, 0, lay.bias, yv, L.relu, None, 0)
 
+        if eager_passes:
+            for _ in range(eager_passes):
+                for c in range(copies):
+                    run(c)
+            torch.cuda.synchronize()
+            continue
         # cold: one graph walks all copies once (> 256 MB of distinct weights per replay)
         state = {"c": 0}
 
