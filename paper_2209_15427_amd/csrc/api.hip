@@ -167,8 +167,8 @@ mpq_status build_epi(int in_dtype, int out_dtype, const mpq_qparams &xq, const m
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) % 16) == 0; }
 
-// (the optional tail of a workspace is used when the caller passed the full size)
-bool fc_ws_ok(const void *ws, size_t ws_bytes, size_t total) { return ws != nullptr && ws_bytes >= total && aligned16(ws); }
+// (an optional part of a workspace is used when the caller's buffer reaches its end)
+bool ws_holds(const void *ws, size_t ws_bytes, size_t total) { return ws != nullptr && ws_bytes >= total && aligned16(ws); }
 
 struct Geometry {
     int P, Q;      // convolution output
@@ -337,6 +337,7 @@ mpq_status run_conv_digits(const mpq_tensor &x, const void *w_packed, const void
     cb.stride_h = d.stride_h; cb.stride_w = d.stride_w; cb.pad_h = d.pad_h; cb.pad_w = d.pad_w;
     const size_t total = (size_t)x.n * g.P * g.Q * d.k;
     I16Seg cs;
+    std::memset(&cs, 0, sizeof(cs));
     if (seg) {
         cs.offsets = seg->offsets;
         cs.num_experts = seg->num_experts;
@@ -364,7 +365,7 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     // (the fully-connected scratch is optional: without it the layer runs on the kernels that need none)
     const size_t ws_required = wl.opt_off;
     if (ws_required > 0 && (ws == nullptr || ws_bytes < ws_required || !aligned16(ws))) return MPQ_ERR_WORKSPACE;
-    const bool fc_ws = wl.fc_bytes > 0 && fc_ws_ok(ws, ws_bytes, wl.total);
+    const bool fc_ws = wl.fc_bytes > 0 && ws_holds(ws, ws_bytes, wl.total);
     if ((long long)x.n * g.P * g.Q > 0x7ffffc00ll) return MPQ_ERR_UNSUPPORTED;
 
     ConvArgs a;
@@ -389,7 +390,7 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     // kernel choice
     const bool mfma_type = x.dtype == MPQ_INT8 || x.dtype == MPQ_FP16;
     // (a weight zero-point on the matrix-core kernels needs the window sums' part of the workspace)
-    const bool xs_ok = wl.xs_bytes > 0 && !seg && fc_ws_ok(ws, ws_bytes, wl.xs_off + wl.xs_bytes);
+    const bool xs_ok = wl.xs_bytes > 0 && !seg && ws_holds(ws, ws_bytes, wl.xs_off + wl.xs_bytes);
     bool zw_ok = (x.dtype == MPQ_FP16) || epi.zw == 0 || xs_ok;
     if (seg)
         for (int e = 0; e < seg->num_experts; ++e) zw_ok = zw_ok && (x.dtype == MPQ_FP16 || seg->epi[e].zw == 0);
@@ -408,7 +409,7 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
         for (int e = 0; e < seg->num_experts; ++e)
             seg_plain = seg_plain && seg->epi[e].zw == 0 && seg->epi[e].kind == kEpiRequant;
     }
-    const bool digits = wl.dg_bytes > 0 && seg_plain && fc_ws_ok(ws, ws_bytes, wl.total) && epi.kind == kEpiRequant &&
+    const bool digits = wl.dg_bytes > 0 && seg_plain && ws_holds(ws, ws_bytes, wl.total) && epi.kind == kEpiRequant &&
                         epi.zw == 0 && aligned16(x.data) &&
                         aligned16(w_packed) && aligned16(conv_out) && (bias == nullptr || aligned16(bias));
     if (!seg && gemv_eligible(a) && (a.N < 4 || a.K <= 16)) {

@@ -13,6 +13,8 @@
 //                     + C(xl',wb) + (128 - z_x) V
 // This file holds the digit splits, the weight-sum table and the recombination with the layer's
 // epilogue; the convolutions themselves are the int8 kernels.
+#include <cstring>
+
 #include "common.h"
 #include "epilogue.h"
 
@@ -185,8 +187,7 @@ hipError_t launch_i16_combine(const int *raw, size_t raw_stride, const int *bias
     const bool v4 = g.K % 4 == 0 && raw_stride % 4 == 0;
     const int grid = grid_of(v4 ? total / 4 : total);
     I16Seg none;
-    none.offsets = nullptr;
-    none.num_experts = 0;
+    std::memset(&none, 0, sizeof(none));
     if (seg) {
         if (v4) i16_combine_kernel<4, true><<<grid, kThreads, 0, st>>>(raw, raw_stride, bias, (int16_t *)y, total, g, epi, *seg);
         else i16_combine_kernel<1, true><<<grid, kThreads, 0, st>>>(raw, raw_stride, bias, (int16_t *)y, total, g, epi, *seg);
