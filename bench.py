@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the FC / MoE side measurements")
     ap.add_argument("--cpu-images", type=int, default=256, help="images the oracle is timed on")
+    ap.add_argument("--separate-convert", action="store_true",
+                    help="fp16: convert the input with mpq_to_fp16 before the first layer instead of inside it")
     ap.add_argument("--no-two-stream", action="store_true",
                     help="skip the extra two-batches-in-flight figure (kernel traces: its kernels overlap)")
     ap.add_argument("--profile-layer", default=None,
@@ -83,8 +85,11 @@ def main():
     x_real = cf.alexnet_input(B)                                     # N,C,H,W fp64
     x_dev = torch.from_numpy(np.ascontiguousarray(x_real.transpose(0, 2, 3, 1).astype(np.float32))).to("cuda")
     params = cf.alexnet_conv_params()
+    # fp16: the first layer takes the fp32 input itself (its conversion rides on the layer's channel
+    # padding pass); --separate-convert runs mpq_to_fp16 as a pass of its own instead
+    fused_in = args.dtype == "fp16" and not args.separate_convert
     if args.dtype == "fp16":
-        chain = pl.Chain(cf.ALEXNET_CONVS, params, dt, B, cf.ALEXNET_INPUT)
+        chain = pl.Chain(cf.ALEXNET_CONVS, params, dt, B, cf.ALEXNET_INPUT, in_f32=fused_in)
     else:
         sc = calib.load()["alexnet"][args.dtype]
         chain = pl.Chain(cf.ALEXNET_CONVS, params, dt, B, cf.ALEXNET_INPUT, sc["x"], sc["layers"])
@@ -92,6 +97,8 @@ def main():
     n_in = x_dev.numel()
 
     def step():
+        if fused_in:
+            return chain.forward(x_dev)
         if dt == mb.FP16:
             mb.mpq_to_fp16(x_dev, x_store, n_in)
         else:
@@ -112,7 +119,7 @@ def main():
             call = lambda: dst.copy_(src)
         else:
             i = [L.name for L in cf.ALEXNET_CONVS].index(args.profile_layer)
-            ins = [x_store] + chain.acts[:-1]
+            ins = [x_dev if fused_in else x_store] + chain.acts[:-1]
             call = (lambda: chain.run_layer(i, ins[i])) if cf.ALEXNET_CONVS[i].name in FUSED_POOL else conv_only_call(mb, pl, chain, ins, i, dt)
         for _ in range(args.steps):
             call()
@@ -176,12 +183,14 @@ def main():
     pipelined = None
     if not args.eager and not args.no_extras and not args.no_two_stream:
         if args.dtype == "fp16":
-            chain_b = pl.Chain(cf.ALEXNET_CONVS, params, dt, B, cf.ALEXNET_INPUT)
+            chain_b = pl.Chain(cf.ALEXNET_CONVS, params, dt, B, cf.ALEXNET_INPUT, in_f32=fused_in)
         else:
             chain_b = pl.Chain(cf.ALEXNET_CONVS, params, dt, B, cf.ALEXNET_INPUT, sc["x"], sc["layers"])
         x_store_b = torch.empty_like(x_store)
 
         def step_b():
+            if fused_in:
+                return chain_b.forward(x_dev)
             if dt == mb.FP16:
                 mb.mpq_to_fp16(x_dev, x_store_b, n_in)
             else:
@@ -226,11 +235,13 @@ def main():
         return graph_time(torch, fn, iters, reps)
 
     layer_us = {}
-    if dt == mb.FP16:
+    if fused_in:
+        mb.mpq_to_fp16(x_dev, x_store, n_in)       # (the side measurements below start from the fp16 input)
+    elif dt == mb.FP16:
         layer_us["convert_in"] = time_call(lambda: mb.mpq_to_fp16(x_dev, x_store, n_in))
     else:
         layer_us["quantize_in"] = time_call(lambda: mb.mpq_quantize(x_dev, x_store, n_in, dt, chain.s_in, 0))
-    ins = [x_store] + chain.acts[:-1]
+    ins = [x_dev if fused_in else x_store] + chain.acts[:-1]
     for i, L in enumerate(cf.ALEXNET_CONVS):
         layer_us[L.name] = time_call(lambda i=i: chain.run_layer(i, ins[i]))
 
@@ -273,7 +284,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"int8": "int8 (int32 acc)", "fp16": "fp16 (fp32 acc)", "int16": "int16 (int64 acc)"}[args.dtype],
         "data": "synthetic",
-        "config": {"workload": f"alexnet_conv_stack_b{B}_{args.dtype}: quantize + conv1..conv5 + 3 max-pools, NHWC",
+        "config": {"workload": f"alexnet_conv_stack_b{B}_{args.dtype}: " +
+                               ("fp32 input converted inside conv1, " if fused_in else "quantize + ") +
+                               "conv1..conv5 + 3 max-pools, NHWC",
                    "batch": B, "input": "3x227x227 N(0,1), seeded", "gop_per_image": round(2 * macs_img / 1e9, 4)},
         "frac_of_mfma_peak": round(tops / PEAK[args.dtype], 4),
         "layer_us": {k: round(v, 1) for k, v in layer_us.items()},
@@ -308,7 +321,8 @@ def conv_only_call(mb, pl, chain, ins, i, dt):
     P, Q = L.out_hw(h, w_)
     tmp = torch.empty((n, P, Q, L.K), dtype=mb.TORCH_DTYPE[dt], device="cuda")
     s_x = chain.s_in if i == 0 else chain.layers[i - 1].y_scale
-    xv = mb.tensor(ins[i], dt, n, h, w_, c, s_x)
+    x_dt = mb.FP32 if ins[i].dtype == torch.float32 else dt     # (fp16: the first layer may take the fp32 input itself)
+    xv = mb.tensor(ins[i], x_dt, n, h, w_, c, s_x)
     yv = mb.tensor(tmp, dt, n, P, Q, L.K, lay.y_scale)
     nws = mb.mpq_conv2d_workspace_bytes(xv, d)       # (first-layer plans keep a channel-padded copy of the input there)
     ws = pl.alloc_bytes(nws) if nws else None

@@ -161,6 +161,9 @@ mpq_status mpq_pack_weights(const void *w_kcrs, const mpq_conv_desc *d, mpq_dtyp
  * y.dtype may instead be MPQ_INT32: then out = t (raw accumulator, no rescale; used for gating).
  * MPQ_FP16: out = fp16(relu(sum in fp32 of x w + bias[k])), bias fp32; y.dtype MPQ_FP16 or
  * MPQ_FP32 (raw).  The paper accumulates floats in the storage type; fp32 is used here.
+ * x->dtype may be MPQ_FP32 for an fp16 layer of first-layer shape (at most 4 input channels, no
+ * padding, see mpq_pack_weights): the quantizer's fp32 -> fp16 conversion (round to nearest even,
+ * as mpq_to_fp16) is then part of the layer; other shapes return MPQ_ERR_UNSUPPORTED.
  *   x        input view; x->c == d->c
  *   w_packed from mpq_pack_weights with the same descriptor and dtype; w_q its parameters
  *   bias     device, k entries (int32 for integer types, fp32 for fp16), or NULL

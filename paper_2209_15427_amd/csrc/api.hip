@@ -285,7 +285,7 @@ WsLayout ws_layout(const mpq_tensor &x, const mpq_conv_desc &d, const Plan &pl, 
 
 mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias, void *y_data,
                     int y_dtype, const mpq_conv_desc &d, const Epi &epi, const SegTable *seg,
-                    void *ws, size_t ws_bytes, hipStream_t st, const void *row_padded = nullptr);
+                    void *ws, size_t ws_bytes, hipStream_t st, const void *row_padded = nullptr, bool x_f32 = false);
 
 // An int16 convolution as six int8 convolutions of digit planes (conv_i16.hip) plus the int64
 // recombination with the layer's epilogue; conv_out receives the unpooled int16 result.
@@ -353,10 +353,12 @@ mpq_status run_conv_digits(const mpq_tensor &x, const void *w_packed, const void
 
 // Everything mpq_conv2d and the MoE layer loop need to launch one convolution.
 // (row_padded: the caller's channel-padded copy of x for a first-layer shape, as launch_pad_channels
-// makes it; saves the copy when several convolutions read the same input)
+// makes it; saves the copy when several convolutions read the same input.
+// x_f32: x.data holds fp32 values although x.dtype says fp16 — a first-layer shape whose input
+// conversion is folded into the channel padding; any other kernel choice is refused.)
 mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias, void *y_data,
                     int y_dtype, const mpq_conv_desc &d, const Epi &epi, const SegTable *seg,
-                    void *ws, size_t ws_bytes, hipStream_t st, const void *row_padded) {
+                    void *ws, size_t ws_bytes, hipStream_t st, const void *row_padded, bool x_f32) {
     Geometry g;
     mpq_status s = geometry(x, d, &g);
     if (s != MPQ_OK) return s;
@@ -400,6 +402,7 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
     if (pl.mode == kModeTap) use_mfma = use_mfma && ((size_t)x.c * pl.esize) % kChunkBytes == 0;
     if (seg && seg->w_stride % 256 != 0) use_mfma = false;
 
+    if (x_f32 && !(use_mfma && pl.mode == kModeRow && !seg && x.dtype == MPQ_FP16)) return MPQ_ERR_UNSUPPORTED;
     hipError_t err = hipSuccess;
     // int16 on the matrix cores: byte-digit planes through the int8 kernels.  Needs the optional part
     // of the workspace and no weight zero-point.
@@ -453,8 +456,9 @@ mpq_status run_conv(const mpq_tensor &x, const void *w_packed, const void *bias,
             const void *xp = row_padded;
             if (!xp) {
                 xp = wsb + wl.pad_off;
-                err = launch_pad_channels(x.data, wsb + wl.pad_off, x.n, x.h, x.w, x.c, pl.Wp, pl.Cpad, pl.esize,
-                                          x.dtype == MPQ_INT8 ? epi.zx : 0, st);
+                err = x_f32 ? launch_pad_channels_f32(x.data, wsb + wl.pad_off, x.n, x.h, x.w, x.c, pl.Wp, pl.Cpad, st)
+                            : launch_pad_channels(x.data, wsb + wl.pad_off, x.n, x.h, x.w, x.c, pl.Wp, pl.Cpad, pl.esize,
+                                                  x.dtype == MPQ_INT8 ? epi.zx : 0, st);
                 if (err != hipSuccess) return MPQ_ERR_DEVICE;
             }
             a.x = xp;
@@ -639,8 +643,11 @@ mpq_status mpq_pack_weights(const void *w_kcrs, const mpq_conv_desc *d, mpq_dtyp
     return MPQ_OK;
 }
 
-size_t mpq_conv2d_workspace_bytes(const mpq_tensor *x, const mpq_conv_desc *d) {
-    if (!x || !d || !desc_ok(*d) || x->c != d->c || x->n < 0 || x->h < 1 || x->w < 1) return 0;
+size_t mpq_conv2d_workspace_bytes(const mpq_tensor *x_in, const mpq_conv_desc *d) {
+    if (!x_in || !d || !desc_ok(*d) || x_in->c != d->c || x_in->n < 0 || x_in->h < 1 || x_in->w < 1) return 0;
+    mpq_tensor xv = *x_in;
+    if (xv.dtype == MPQ_FP32) xv.dtype = MPQ_FP16;      // (fp32 input of an fp16 first layer)
+    const mpq_tensor *x = &xv;
     Geometry g;
     if (geometry(*x, *d, &g) != MPQ_OK) return 0;
     Plan pl = make_plan(*d, x->dtype, x->w);
@@ -649,6 +656,16 @@ size_t mpq_conv2d_workspace_bytes(const mpq_tensor *x, const mpq_conv_desc *d) {
 
 mpq_status mpq_conv2d(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q, const void *bias,
                       mpq_tensor *y, const mpq_conv_desc *d, void *ws, size_t ws_bytes, void *stream) {
+    // fp32 input of an fp16 layer: first-layer shapes only, the conversion rides on the channel padding
+    mpq_tensor xh;
+    bool x_f32 = false;
+    if (x && x->dtype == MPQ_FP32) {
+        if (!d || !desc_ok(*d) || make_plan(*d, MPQ_FP16, x->w).mode != kModeRow) return MPQ_ERR_UNSUPPORTED;
+        xh = *x;
+        xh.dtype = MPQ_FP16;
+        x = &xh;
+        x_f32 = true;
+    }
     Geometry g;
     mpq_status s = check_conv_args(x, w_packed, w_q, y, d, &g);
     if (s != MPQ_OK) return s;
@@ -656,7 +673,7 @@ mpq_status mpq_conv2d(const mpq_tensor *x, const void *w_packed, mpq_qparams w_q
     s = build_epi(x->dtype, y->dtype, x->q, w_q, y->q, d->relu, d->rounding, &epi);
     if (s != MPQ_OK) return s;
     if (x->n == 0) return MPQ_OK;
-    return run_conv(*x, w_packed, bias, y->data, y->dtype, *d, epi, nullptr, ws, ws_bytes, (hipStream_t)stream);
+    return run_conv(*x, w_packed, bias, y->data, y->dtype, *d, epi, nullptr, ws, ws_bytes, (hipStream_t)stream, nullptr, x_f32);
 }
 
 mpq_conv_desc mpq_gemm_desc(int32_t k_in, int32_t n_out, int32_t relu) {

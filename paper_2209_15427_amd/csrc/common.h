@@ -175,6 +175,7 @@ hipError_t launch_i16_combine(const int *raw, size_t raw_stride, const int *bias
                               const I16Combine &g, const Epi &epi, const I16Seg *seg, hipStream_t st);
 hipError_t launch_window_sums(const ConvArgs &a, const void *x, int W, int C, int *xsum, hipStream_t st);
 hipError_t launch_minmax(const float *src, size_t n, float *minmax, hipStream_t st);
+hipError_t launch_pad_channels_f32(const void *x, void *xp, int N, int H, int W, int C, int Wp, int Cpad, hipStream_t st);
 hipError_t launch_pad_channels(const void *x, void *xp, int N, int H, int W, int C, int Wp, int Cpad,
                                int esize, int fill, hipStream_t st);
 hipError_t launch_maxpool(const void *x, void *y, int N, int H, int W, int C, int k, int s, int dtype,

@@ -174,6 +174,26 @@ pad_channels_kernel(const T *__restrict__ x, T *__restrict__ xp, int N, int H, i
     }
 }
 
+// fp32 source, fp16 copy: the input conversion of an fp16 first layer folded into its channel padding
+// (one pass over the input instead of a conversion pass and a padding pass).
+__global__ void __launch_bounds__(kThreads)
+pad_channels_f32_kernel(const float *__restrict__ x, _Float16 *__restrict__ xp, int N, int H, int W, int C, int Wp) {
+    typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+    size_t total = (size_t)N * H * Wp;
+    size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t nthreads = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = tid; i < total; i += nthreads) {
+        int wp = (int)(i % Wp);
+        size_t nh = i / Wp;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        if (wp < W) {
+            const float *src = x + (nh * W + wp) * C;
+            for (int c = 0; c < C; ++c) v[c] = src[c];
+        }
+        *reinterpret_cast<v4h *>(xp + i * 4) = v4h{(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
+    }
+}
+
 // The same for C = 3 (the first-layer case), 12 source bytes = 4 (int8) or 2 (16-bit) pixels per
 // thread as three dword loads: element-sized loads at a 3-element stride were the slow part.
 template <typename T>
@@ -621,6 +641,14 @@ hipError_t launch_pad_channels(const void *x, void *xp, int N, int H, int W, int
     else
         pad_channels_kernel<int16_t><<<grid, kThreads, 0, st>>>((const int16_t *)x, (int16_t *)xp, N, H, W,
                                                                 C, Wp, Cpad, (int16_t)fill);
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_channels_f32(const void *x, void *xp, int N, int H, int W, int C, int Wp, int Cpad, hipStream_t st) {
+    if (Cpad != 4 || C > 4 || (reinterpret_cast<uintptr_t>(xp) % 8) != 0) return hipErrorInvalidValue;
+    size_t total = (size_t)N * H * Wp;
+    if (total == 0) return hipSuccess;
+    pad_channels_f32_kernel<<<grid_for(total, kThreads), kThreads, 0, st>>>((const float *)x, (_Float16 *)xp, N, H, W, C, Wp);
     return hipGetLastError();
 }
 

@@ -86,7 +86,8 @@ class Layer:
 class Chain:
     """A stack of layers with pre-allocated activations; forward() only enqueues kernels."""
 
-    def __init__(self, specs, params_real, dtype, batch, in_chw, s_in=1.0, scales=None, raw_last=False):
+    def __init__(self, specs, params_real, dtype, batch, in_chw, s_in=1.0, scales=None, raw_last=False, in_f32=False):
+        """in_f32: the first layer (fp16, first-layer shape) takes the fp32 NHWC input itself."""
         self.dtype, self.batch = dtype, batch
         c, h, w = in_chw
         self.in_shape = (batch, h, w, c)
@@ -113,7 +114,8 @@ class Chain:
                 xin = (shape[0], 1, 1, shape[1] * shape[2] * shape[3])
             else:
                 xin = shape
-            xv = lambda data, xin=xin, s_x=s_x: mb.tensor(data, dtype, *xin, scale=s_x)
+            x_dt = mb.FP32 if (in_f32 and i == 0) else dtype
+            xv = lambda data, xin=xin, s_x=s_x, x_dt=x_dt: mb.tensor(data, x_dt, *xin, scale=s_x)
             yv = mb.tensor(y, out_dt, *oshape, scale=L.y_scale)
             self.views.append((xv, yv))
             if spec.kind != "fc":

@@ -32,8 +32,9 @@ def pack(w_dev_kcrs, desc, dtype):
     return packed
 
 
-def run_conv(x_dev, xq, w_dev_kcrs, wq, bias_dev, desc, dtype, yq=(1.0, 0), out_dtype=None):
-    """x_dev: NHWC device tensor.  Returns the NHWC output tensor (host sync included)."""
+def run_conv(x_dev, xq, w_dev_kcrs, wq, bias_dev, desc, dtype, yq=(1.0, 0), out_dtype=None, in_dtype=None):
+    """x_dev: NHWC device tensor.  Returns the NHWC output tensor (host sync included).
+    in_dtype: the dtype announced for x when it differs from the layer's (fp32 input of an fp16 first layer)."""
     out_dtype = dtype if out_dtype is None else out_dtype
     n, h, w, c = x_dev.shape
     packed = pack(w_dev_kcrs, desc, dtype)
@@ -42,7 +43,7 @@ def run_conv(x_dev, xq, w_dev_kcrs, wq, bias_dev, desc, dtype, yq=(1.0, 0), out_
     if desc.pool_k:
         P, Q = (P - desc.pool_k) // desc.pool_s + 1, (Q - desc.pool_k) // desc.pool_s + 1
     y = torch.full((n, P, Q, desc.k), 77, dtype=mb.TORCH_DTYPE[out_dtype], device="cuda")
-    xv = mb.tensor(x_dev, dtype, n, h, w, c, xq[0], xq[1])
+    xv = mb.tensor(x_dev, dtype if in_dtype is None else in_dtype, n, h, w, c, xq[0], xq[1])
     yv = mb.tensor(y, out_dtype, n, P, Q, desc.k, yq[0], yq[1])
     nws = mb.mpq_conv2d_workspace_bytes(xv, desc)
     ws = pl.alloc_bytes(nws)

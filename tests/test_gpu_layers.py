@@ -324,6 +324,41 @@ def test_fp16_conv(case):
     gu.check_fp16(gu.to_nchw(y), ref, "fp16 conv")
 
 
+@pytest.mark.parametrize("idx", [5, 14, 15, 18])
+def test_fp16_first_layer_takes_fp32_input(idx):
+    """A first-layer shape with x->dtype = FP32: the fp32 -> fp16 conversion is part of the layer;
+    the result equals the layer on the separately converted input (same kernel, same fp16 values)
+    and meets the fp16 bar against the oracle on the rounded input."""
+    case = CONV_CASES[idx]
+    _say("fp16 conv, fp32 input", case)
+    N, C, H, W, K, R, S, stride, pad, groups, relu, pool = case[:12]
+    seed = 3300 + idx
+    x32 = gen.normal(seed, (N, C, H, W)).astype(np.float32)
+    x = o.round_fp16(x32.astype(np.float64))
+    w = o.round_fp16(gen.normal(seed + 1, (K, C // groups, R, S), 0, float(np.sqrt(2.0 / (C // groups * R * S)))))
+    b = gen.normal(seed + 2, (K,), 0, 0.1).astype(np.float32)
+    desc = mb.conv_desc(C, K, R, S, stride, pad, groups, relu, pool[0], pool[1])
+    wd = torch.from_numpy(w.astype(np.float16)).to("cuda")
+    bd = torch.from_numpy(b).to("cuda")
+    y16 = gu.run_conv(gu.half_to_dev(x), (1.0, 0), wd, (1.0, 0), bd, desc, mb.FP16)
+    xd32 = torch.from_numpy(np.ascontiguousarray(x32.transpose(0, 2, 3, 1))).to("cuda")
+    y32 = gu.run_conv(xd32, (1.0, 0), wd, (1.0, 0), bd, desc, mb.FP16, in_dtype=mb.FP32)
+    assert torch.equal(y16, y32)
+    ref = o.conv2d_f64(x, w, b.astype(np.float64), stride, pad, groups, relu)
+    if pool[0]:
+        ref = o.maxpool_f64(ref, pool[0], pool[1])
+    gu.check_fp16(gu.to_nchw(y32), ref, "fp16 conv, fp32 input")
+
+
+def test_fp32_input_is_refused_elsewhere():
+    desc = mb.conv_desc(32, 64, 3, 3, 1, 1, 1, True)
+    x = torch.zeros((1, 8, 8, 32), dtype=torch.float32, device="cuda")
+    w = torch.zeros((64, 32, 3, 3), dtype=torch.float16, device="cuda")
+    with pytest.raises(mb.MpqError) as e:
+        gu.run_conv(x, (1.0, 0), w, (1.0, 0), None, desc, mb.FP16, in_dtype=mb.FP32)
+    assert e.value.status == 3
+
+
 def test_fp16_conv_power_of_two_data_is_exact():
     # sums of a few powers of two are exact in fp32 and representable in fp16: bit-exact result
     N, C, H, W, K = 2, 16, 8, 8, 64
