@@ -99,7 +99,7 @@ def test_conv_argument_errors():
     assert call(wsc=0.0) == 1
     assert call(d=mb.conv_desc(16, 32, 3, 3, 1, 1, 3, True)) == 1                    # c % groups
     assert call(d=mb.conv_desc(16, 32, 3, 3, 0, 1, 1, True)) == 1                    # stride 0
-    assert call(x=mb.tensor(FAKE, mb.FP32, 2, 8, 8, 16)) == 1                        # unsupported input type
+    assert call(x=mb.tensor(FAKE, mb.FP32, 2, 8, 8, 16)) == 3                        # fp32 input: fp16 first-layer shapes only
     # kernel larger than the padded image
     assert _status(mb.mpq_conv2d, mb.tensor(FAKE, mb.INT8, 1, 2, 2, 16, 0.1), FAKE, 0.1, 0, None,
                    mb.tensor(FAKE + 4096, mb.INT8, 1, 1, 1, 32, 0.1), mb.conv_desc(16, 32, 7, 7), None, 0) == 2
