@@ -302,6 +302,7 @@ def main():
         if B == 256:
             out["moe_config5"] = bench_moe(torch, mb, pl, cf, calib, args.dtype, chain.acts[1], B)
         out["alexnet_whole_net"] = bench_whole_net(torch, mb, pl, cf, calib, args.dtype, x_dev, B, macs_img)
+        out["latency_bound"] = bench_small(torch, mb, pl, cf, calib, args.dtype)
         out["moe16_top4"] = bench_moe16(torch, mb, pl, cf, calib, args.dtype, x_store, B)
 
     if not args.no_cpu_baseline:
@@ -376,6 +377,44 @@ def bench_whole_net(torch, mb, pl, cf, calib, dtype_name, x_dev, batch, conv_mac
     return {"workload": f"conv1..conv5 + pools + fc6..fc8 chained, batch {batch}", "forward_us": round(us, 1),
             "images_per_s": round(batch / (us * 1e-6), 1), "gop_per_image": round(2 * macs / 1e9, 4),
             "tops": round(2.0 * macs * batch / (us * 1e-6) / 1e12, 1)}
+
+
+def bench_small(torch, mb, pl, cf, calib, dtype_name):
+    """The latency-bound configurations: config 2 (LeNet shape, batch 64) and config 3 at batch 1,
+    input conversion included; microseconds per forward pass and images per second, no roofline claim."""
+    import numpy as np
+    dt = mb.DTYPE_ID[dtype_name]
+    res = {}
+    x, params = cf.lenet_tensors(64)
+    if dtype_name == "fp16":
+        net = pl.Chain(cf.LENET_LAYERS, params, dt, 64, cf.LENET_INPUT)
+    else:
+        sc = calib.load()["lenet"][dtype_name]
+        net = pl.Chain(cf.LENET_LAYERS, params, dt, 64, cf.LENET_INPUT, sc["x"], sc["layers"])
+    cases = [("lenet_b64", net, x, 64)]
+    x1 = cf.alexnet_input(1)
+    p3 = cf.alexnet_conv_params()
+    if dtype_name == "fp16":
+        net1 = pl.Chain(cf.ALEXNET_CONVS, p3, dt, 1, cf.ALEXNET_INPUT)
+    else:
+        sc = calib.load()["alexnet"][dtype_name]
+        net1 = pl.Chain(cf.ALEXNET_CONVS, p3, dt, 1, cf.ALEXNET_INPUT, sc["x"], sc["layers"])
+    cases.append(("alexnet_conv_stack_b1", net1, x1, 1))
+    for name, chain, xr, b in cases:
+        xd = torch.from_numpy(np.ascontiguousarray(xr.transpose(0, 2, 3, 1).astype(np.float32))).to("cuda")
+        store = torch.empty(xd.shape, dtype=mb.TORCH_DTYPE[dt], device="cuda")
+        n = xd.numel()
+
+        def forward(chain=chain, xd=xd, store=store, n=n):
+            if dt == mb.FP16:
+                mb.mpq_to_fp16(xd, store, n)
+            else:
+                mb.mpq_quantize(xd, store, n, dt, chain.s_in, 0)
+            return chain.forward(store)
+
+        us = graph_time(torch, forward, 10, 10)
+        res[name] = {"forward_us": round(us, 1), "images_per_s": round(b / (us * 1e-6), 1), "launches": len(chain.layers) + 1}
+    return res
 
 
 def bench_moe16(torch, mb, pl, cf, calib, dtype_name, x_store, batch):

@@ -135,6 +135,7 @@ struct ConvArgs {
     // taps inside the image of (x - z_x); the epilogue subtracts zw_corr * xsum from the row's sums
     const int *xsum;
     int zw_corr;
+    int vec4;              // direct kernel, int8: channels per tap are whole, aligned dwords
     unsigned fill_word;    // the input zero-point replicated over 32 bits (out-of-image taps)
     unsigned long long x_bytes;   // size of the input tensor the kernel sees
     Plan plan;

@@ -13,25 +13,37 @@ namespace mpq {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kCh = 4;   // output channels per thread
+// output channels per thread: 4 (an input value is loaded once for four channels), or 1 where the
+// layer is too small to fill the chip with a quarter of the threads
 
-template <typename T, typename AccT>
+template <typename T, typename AccT, int kCh>
 __global__ void __launch_bounds__(kThreads) conv_generic_kernel(ConvArgs a) {
     const Plan &pl = a.plan;
     const int PQ = a.P * a.Q;
     const size_t M = (size_t)a.N * PQ;
     const int kq = (a.K + kCh - 1) / kCh;
-    const size_t total = M * kq;
     size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t nthreads = (size_t)gridDim.x * blockDim.x;
     const T *x = (const T *)a.x;
-    for (size_t i = tid; i < total; i += nthreads) {
-        int k0 = (int)(i % kq) * kCh;
-        size_t m = i / kq;
-        int q = (int)(m % a.Q);
-        size_t np = m / a.Q;
-        int p = (int)(np % a.P);
-        int n = (int)(np / a.P);
+    // blockIdx.y = the channel group: a workgroup's threads are consecutive pixels of the same output
+    // channels, so the weight addresses are uniform over a wavefront (one cache line per load
+    // instead of one per lane) and the input loads of neighbouring lanes are neighbours
+    for (int kb = blockIdx.y; kb < kq; kb += gridDim.y) {
+    const int k0 = kb * kCh;
+    for (size_t m = tid; m < M; m += nthreads) {
+        // (32-bit divisions where the index fits)
+        int q, p, n;
+        if (M <= 0xffffffffull) {
+            const unsigned mu = (unsigned)m, npu = mu / (unsigned)a.Q, nu = npu / (unsigned)a.P;
+            q = (int)(mu - npu * (unsigned)a.Q);
+            p = (int)(npu - nu * (unsigned)a.P);
+            n = (int)nu;
+        } else {
+            q = (int)(m % a.Q);
+            const size_t np = m / a.Q;
+            p = (int)(np % a.P);
+            n = (int)(np / a.P);
+        }
 
         // grouped (MoE) launch: sample n belongs to the expert whose offset range holds it
         const char *wbase = (const char *)a.w;
@@ -53,7 +65,93 @@ __global__ void __launch_bounds__(kThreads) conv_generic_kernel(ConvArgs a) {
         // all kCh channels of a thread lie in one group when Kg % kCh == 0; otherwise handle each
         // channel's group separately (rare, tiny layers)
         const int h0 = p * a.stride_h - a.pad_h, w0 = q * a.stride_w - a.pad_w;
-        for (int j = 0; j < kCh; ++j) {
+        bool done = false;
+        if constexpr (sizeof(T) == 1) {
+            // int8 with whole dwords of channels per tap (LeNet's second convolution: 20 channels):
+            // every input dword is loaded once for the thread's four output channels and multiplied
+            // with v_dot4; the zero-point terms come from dot products against ones (expanded form).
+            if (a.vec4) {
+                const int g = k0 / pl.Kg;
+                int xw[kCh], sw[kCh], sx = 0, cnt = 0;
+#pragma unroll
+                for (int j = 0; j < kCh; ++j) xw[j] = sw[j] = 0;
+                const T *wk[kCh];
+#pragma unroll
+                for (int j = 0; j < kCh; ++j) wk[j] = w + (size_t)(k0 + j < a.K ? k0 + j : k0) * pl.Kp;
+                const int c4n = pl.Cg / 4;
+                // (taps outside the image are read at a clamped position and masked to zero: no branch
+                // between the loads, so that several taps' loads are in flight per thread)
+                for (int r = 0; r < a.R; ++r) {
+                    const int h = h0 + r;
+                    const bool hv = h >= 0 && h < a.H;
+                    const int hc = h < 0 ? 0 : (h >= a.H ? a.H - 1 : h);
+#pragma unroll 4
+                    for (int sxp = 0; sxp < a.S; ++sxp) {
+                        const int ww = w0 + sxp;
+                        const bool v = hv && ww >= 0 && ww < a.W;
+                        const int wc = ww < 0 ? 0 : (ww >= a.W ? a.W - 1 : ww);
+                        const int *xp = reinterpret_cast<const int *>(x + (((size_t)n * a.H + hc) * a.W + wc) * a.C + (size_t)g * pl.Cg);
+                        const int wo = r * pl.row_pitch + sxp * pl.s_pitch;
+                        cnt += v ? pl.Cg : 0;
+#pragma unroll 2
+                        for (int c = 0; c < c4n; ++c) {
+                            const int xl = xp[c];
+                            const int xv = v ? xl : 0;
+                            sx = __builtin_amdgcn_sdot4(xv, 0x01010101, sx, false);
+#pragma unroll
+                            for (int j = 0; j < kCh; ++j) {
+                                const int wl = reinterpret_cast<const int *>(wk[j] + wo)[c];
+                                const int wv = v ? wl : 0;
+                                xw[j] = __builtin_amdgcn_sdot4(xv, wv, xw[j], false);
+                                sw[j] = __builtin_amdgcn_sdot4(wv, 0x01010101, sw[j], false);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < kCh; ++j)
+                    acc[j] = (AccT)xw[j] - (AccT)epi.zx * sw[j] - (AccT)epi.zw * sx + (AccT)cnt * epi.zx * epi.zw;
+                done = true;
+            }
+        }
+        if (!done && (a.groups == 1 || pl.Kg % kCh == 0)) {
+            // the thread's channels share a group: every input value is loaded once and multiplied
+            // with each channel's weight (per channel the same (r, s, c) order as below)
+            const int g = k0 / pl.Kg;
+            const T *wk[kCh];
+#pragma unroll
+            for (int j = 0; j < kCh; ++j) wk[j] = w + (size_t)(k0 + j < a.K ? k0 + j : k0) * pl.Kp;
+            for (int r = 0; r < a.R; ++r) {
+                const int h = h0 + r;
+                const bool hv = h >= 0 && h < a.H;
+                const int hc = h < 0 ? 0 : (h >= a.H ? a.H - 1 : h);
+#pragma unroll 4
+                for (int sx = 0; sx < a.S; ++sx) {
+                    const int ww = w0 + sx;
+                    const bool v = hv && ww >= 0 && ww < a.W;
+                    const int wc = ww < 0 ? 0 : (ww >= a.W ? a.W - 1 : ww);
+                    const T *xp = x + (((size_t)n * a.H + hc) * a.W + wc) * a.C + (size_t)g * pl.Cg;
+                    const int wo = r * pl.row_pitch + sx * pl.s_pitch;
+#pragma unroll 4
+                    for (int c = 0; c < pl.Cg; ++c) {
+                        if constexpr (sizeof(AccT) == 8) {
+                            const int xl = (int)xp[c];
+                            const AccT xv = v ? (AccT)(xl - epi.zx) : (AccT)0;
+#pragma unroll
+                            for (int j = 0; j < kCh; ++j) acc[j] += xv * (AccT)((int)wk[j][wo + c] - epi.zw);
+                        } else {
+                            // (a masked tap adds +0 products: the sums are those of the taps inside the image)
+                            const float xl = (float)xp[c];
+                            const float xv = v ? xl : 0.f;
+#pragma unroll
+                            for (int j = 0; j < kCh; ++j) acc[j] += xv * (float)wk[j][wo + c];
+                        }
+                    }
+                }
+            }
+            done = true;
+        }
+        for (int j = 0; j < kCh && !done; ++j) {
             int k = k0 + j;
             if (k >= a.K) break;
             int g = k / pl.Kg;
@@ -77,6 +175,20 @@ __global__ void __launch_bounds__(kThreads) conv_generic_kernel(ConvArgs a) {
             }
             acc[j] = s;
         }
+        if constexpr (sizeof(AccT) == 8 && kCh == 4) {
+            // four int8 codes of one pixel as one dword
+            if (a.out_dtype == MPQ_INT8 && epi.kind == kEpiRequant && k0 + 3 < a.K && a.K % 4 == 0 &&
+                reinterpret_cast<uintptr_t>(a.y) % 4 == 0) {
+                unsigned packed = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const long long t = acc[j] + (bias ? (long long)((const int *)bias)[k0 + j] : 0ll);
+                    packed |= ((unsigned)requant64(t, epi) & 0xffu) << (8 * j);
+                }
+                *reinterpret_cast<unsigned *>((int8_t *)a.y + m * a.K + k0) = packed;
+                continue;
+            }
+        }
 #pragma unroll
         for (int j = 0; j < kCh; ++j) {
             int k = k0 + j;
@@ -99,23 +211,40 @@ __global__ void __launch_bounds__(kThreads) conv_generic_kernel(ConvArgs a) {
             }
         }
     }
+    }
+}
+
+template <int kCh>
+hipError_t launch_generic_ch(const ConvArgs &a, hipStream_t st) {
+    size_t M = (size_t)a.N * a.P * a.Q;
+    const int kq = (a.K + kCh - 1) / kCh;
+    size_t bx = (M + kThreads - 1) / kThreads;
+    if (bx > 256 * 64) bx = 256 * 64;
+    const dim3 blocks((unsigned)bx, (unsigned)(kq < 65535 ? kq : 65535));
+    if (a.in_dtype == MPQ_INT8) {
+        // whole dwords of channels per tap, the channels of a thread in one group, 4-byte aligned
+        // rows, and sums that fit 32 bits
+        ConvArgs b = a;
+        b.vec4 = (a.plan.Cg % 4 == 0 && a.C % 4 == 0 && (a.groups == 1 || a.plan.Kg % kCh == 0) && a.plan.Kdim <= 65536 &&
+                  (a.plan.Kp % 4) == 0 && reinterpret_cast<uintptr_t>(a.x) % 4 == 0 && reinterpret_cast<uintptr_t>(a.w) % 4 == 0 &&
+                  (!a.seg.offsets || a.seg.w_stride % 4 == 0)) ? 1 : 0;
+        conv_generic_kernel<int8_t, long long, kCh><<<blocks, kThreads, 0, st>>>(b);
+    } else if (a.in_dtype == MPQ_INT16) {
+        conv_generic_kernel<int16_t, long long, kCh><<<blocks, kThreads, 0, st>>>(a);
+    } else {
+        conv_generic_kernel<_Float16, float, kCh><<<blocks, kThreads, 0, st>>>(a);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_conv_generic(const ConvArgs &a, hipStream_t st) {
     size_t M = (size_t)a.N * a.P * a.Q;
-    size_t total = M * ((a.K + kCh - 1) / kCh);
-    if (total == 0) return hipSuccess;
-    size_t blocks = (total + kThreads - 1) / kThreads;
-    if (blocks > 256 * 64) blocks = 256 * 64;
-    if (a.in_dtype == MPQ_INT8)
-        conv_generic_kernel<int8_t, long long><<<(int)blocks, kThreads, 0, st>>>(a);
-    else if (a.in_dtype == MPQ_INT16)
-        conv_generic_kernel<int16_t, long long><<<(int)blocks, kThreads, 0, st>>>(a);
-    else
-        conv_generic_kernel<_Float16, float><<<(int)blocks, kThreads, 0, st>>>(a);
-    return hipGetLastError();
+    if (M * a.K == 0) return hipSuccess;
+    // fewer than one wavefront per CU with four channels per thread: one channel per thread
+    if (M * ((a.K + 3) / 4) < (size_t)256 * 64) return launch_generic_ch<1>(a, st);
+    return launch_generic_ch<4>(a, st);
 }
 
 }  // namespace mpq
