@@ -206,8 +206,9 @@ struct WsLayout {
     size_t total;
 };
 
-// Below this many multiply-accumulates a digit-plane run (ten launches) loses to the direct kernel.
-constexpr long long kDigitMinMacs = 1ll << 24;
+// Below this many multiply-accumulates a digit-plane run (ten launches) loses to the direct kernel
+// (measured on config 3's layers at batch 1..4: the two meet between 1e8 and 2.5e8).
+constexpr long long kDigitMinMacs = 1ll << 27;
 
 mpq_conv_desc digit_desc(const mpq_conv_desc &d) {
     mpq_conv_desc d8 = d;

@@ -179,7 +179,7 @@ RANDOM_I16 = _random_geometries(20240, 14, 1 << 24, 1 << 27)
 def test_int16_conv_random_geometries(idx):
     """int16 layers large enough for the digit-plane path, random geometry (non-square kernels,
     padding wider than half the kernel, strides, groups, input zero-points, pools)."""
-    case = RANDOM_I16[idx]
+    case = _grown(RANDOM_I16[idx])
     _say("int16 random", case)
     _int_conv_case(mb.INT16, *case, seed=7000 + 31 * idx)
 
@@ -261,11 +261,12 @@ def test_int8_conv_round_to_nearest(idx):
 
 @pytest.mark.parametrize("idx", [0, 3, 5, 8, 18])
 def test_int16_conv_round_to_nearest(idx):
-    _say("int16 nearest", CONV_CASES[idx])
-    _int_conv_case(mb.INT16, *CONV_CASES[idx], seed=8100 + idx, nearest=True)
+    case = _grown(CONV_CASES[idx]) if idx in (0, 18) else CONV_CASES[idx]       # (digit planes / direct kernel)
+    _say("int16 nearest", case)
+    _int_conv_case(mb.INT16, *case, seed=8100 + idx, nearest=True)
 
 
-@pytest.mark.parametrize("M", [1, 3, 40, 300])
+@pytest.mark.parametrize("M", [1, 3, 40, 600])
 @pytest.mark.parametrize("dtype", [mb.INT8, mb.INT16])
 def test_fc_round_to_nearest(M, dtype):
     """FC layers (a 1x1 convolution on a 1x1 image through mpq_conv2d, which carries the option):
@@ -274,15 +275,38 @@ def test_fc_round_to_nearest(M, dtype):
     _int_conv_case(dtype, M, 1024, 1, 1, 260, 1, 1, 1, 0, 1, True, (0, 0), 0, 0, 3, seed=8200 + M, nearest=True)
 
 
-# (int16 layers of at least 2^24 multiply-accumulates whose shape the int8 kernels accept run as
-# byte-digit planes on the matrix cores: c0, c1, c2, c10, c18, c22, c23, c24; the rest on the direct kernel)
+# (int16 layers of at least 2^27 multiply-accumulates whose shape the int8 kernels accept run as
+# byte-digit planes on the matrix cores; smaller ones, and the other shapes, on the direct kernel)
 I16_CASES = (0, 1, 2, 3, 5, 8, 9, 10, 18, 22, 23, 24)
+DIGIT_MIN_MACS = 1 << 27
+
+
+def _macs(case):
+    N, C, H, W, K, R, S, stride, pad, groups = case[:10]
+    P, Q = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    return N * P * Q * K * (C // groups) * R * S
+
+
+def _grown(case):
+    """The same layer with enough images to pass the digit-plane threshold."""
+    per_image = _macs(case) // case[0]
+    n = max(case[0], -(-(DIGIT_MIN_MACS + per_image) // per_image))
+    return (n,) + tuple(case[1:])
 
 
 @pytest.mark.parametrize("case", [CONV_CASES[i] for i in I16_CASES], ids=[f"c{i}" for i in I16_CASES])
 def test_int16_conv(case):
     _say("int16 conv", case)
     _int_conv_case(mb.INT16, *case, seed=2000 + 17 * CONV_CASES.index(case))
+
+
+@pytest.mark.parametrize("idx", [0, 1, 18, 22, 23, 24])
+def test_int16_conv_digit_planes(idx):
+    """The cases above whose shape the int8 kernels accept, at a batch that takes the digit-plane path."""
+    case = _grown(CONV_CASES[idx])
+    _say("int16 conv, digit planes", case)
+    assert _macs(case) >= DIGIT_MIN_MACS
+    _int_conv_case(mb.INT16, *case, seed=2600 + 17 * idx)
 
 
 def test_int8_conv_raw_accumulators():
@@ -448,8 +472,8 @@ def test_int8_gemm_weight_zero_point(M, K, N, zx, zw, ws):
     assert np.array_equal(y.cpu().numpy().astype(np.int32), ref) and len(np.unique(ref)) > 20
 
 
-@pytest.mark.parametrize("M,N,ws", [(2, 3, True), (64, 96, True), (64, 96, False)],
-                         ids=["gemv", "digit_planes", "direct_without_workspace"])
+@pytest.mark.parametrize("M,N,ws", [(2, 3, True), (384, 96, True), (384, 96, False), (64, 96, True)],
+                         ids=["gemv", "digit_planes", "direct_without_workspace", "direct_small"])
 def test_int16_gemm_accumulates_beyond_int32(M, N, ws):
     K = 4096
     x = np.full((M, K), 32767, np.int64)

@@ -261,7 +261,7 @@ def test_moe_all_to_one_expert_and_empty_experts():
 def test_moe_int16_digit_planes_with_empty_and_single_experts():
     """int16 expert convolution large enough for the digit-plane path: everything routed to one
     expert (two empty segments), then one sample each for two experts and the rest to the third."""
-    B = 160
+    B = 320            # (the expert convolution: 320 x 49 x 64 x 144 = 1.4e8 multiply-accumulates)
     layers, params, scales, x, E = _tiny_moe_case("int16", B, 860)
     s_x = 0.02 * 127.0 / 32767
     for variant in range(2):
