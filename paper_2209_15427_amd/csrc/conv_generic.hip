@@ -218,7 +218,9 @@ template <int kCh>
 hipError_t launch_generic_ch(const ConvArgs &a, hipStream_t st) {
     size_t M = (size_t)a.N * a.P * a.Q;
     const int kq = (a.K + kCh - 1) / kCh;
-    size_t bx = (M + kThreads - 1) / kThreads;
+    // (fewer pixels than a workgroup has threads: whole wavefronts only as far as there are pixels)
+    const int threads = M >= (size_t)kThreads ? kThreads : (int)((M + 63) / 64 * 64);
+    size_t bx = (M + threads - 1) / threads;
     if (bx > 256 * 64) bx = 256 * 64;
     const dim3 blocks((unsigned)bx, (unsigned)(kq < 65535 ? kq : 65535));
     if (a.in_dtype == MPQ_INT8) {
@@ -228,11 +230,11 @@ hipError_t launch_generic_ch(const ConvArgs &a, hipStream_t st) {
         b.vec4 = (a.plan.Cg % 4 == 0 && a.C % 4 == 0 && (a.groups == 1 || a.plan.Kg % kCh == 0) && a.plan.Kdim <= 65536 &&
                   (a.plan.Kp % 4) == 0 && reinterpret_cast<uintptr_t>(a.x) % 4 == 0 && reinterpret_cast<uintptr_t>(a.w) % 4 == 0 &&
                   (!a.seg.offsets || a.seg.w_stride % 4 == 0)) ? 1 : 0;
-        conv_generic_kernel<int8_t, long long, kCh><<<blocks, kThreads, 0, st>>>(b);
+        conv_generic_kernel<int8_t, long long, kCh><<<blocks, threads, 0, st>>>(b);
     } else if (a.in_dtype == MPQ_INT16) {
-        conv_generic_kernel<int16_t, long long, kCh><<<blocks, kThreads, 0, st>>>(a);
+        conv_generic_kernel<int16_t, long long, kCh><<<blocks, threads, 0, st>>>(a);
     } else {
-        conv_generic_kernel<_Float16, float, kCh><<<blocks, kThreads, 0, st>>>(a);
+        conv_generic_kernel<_Float16, float, kCh><<<blocks, threads, 0, st>>>(a);
     }
     return hipGetLastError();
 }
